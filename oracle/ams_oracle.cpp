@@ -1,0 +1,383 @@
+// CPU oracle for one AMS KV-compression event.  TEST INFRASTRUCTURE ONLY: see
+// ams_oracle.h.  Plain loops, double accumulation, one rounding to float per
+// stored value, no blocking or fusion beyond what the paper's steps state.
+#include "ams_oracle.h"
+
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+namespace {
+
+inline bool is_nan(float x) { return x != x; }
+
+// Ordering used by the in-segment top-k: larger score first, NaN counts as
+// -infinity, equal scores (including -0 == +0) keep the lower index first.
+inline float sel_value(float x) { return is_nan(x) ? -INFINITY : x; }
+
+}  // namespace
+
+extern "C" {
+
+// ---------------------------------------------------------------------------
+// Usage u (Sec. 3.2; Alg. 1 step 1) and base score g (Sec. 3.3).
+//   s[n][t] = q_n . k_t / sqrt(D)
+//   p[n][t] = softmax over t of s[n][:]
+//   u[t]    = mean over the N = G*W (head, query) pairs of p[n][t]
+// ---------------------------------------------------------------------------
+int amso_score(const float* Q, const float* K, int G, int W, int T, int D,
+               int scorer, float* u, float* g) {
+  if (!Q || !K || !u || !g || G < 1 || W < 1 || T < 1 || D < 1) return -1;
+  const int N = G * W;
+  const double inv_sqrt_d = 1.0 / std::sqrt((double)D);
+  std::vector<double> s((size_t)T), usage((size_t)T, 0.0), last((size_t)T, 0.0);
+
+  for (int n = 0; n < N; ++n) {
+    const float* q = Q + (size_t)n * D;
+    double smax = -INFINITY;
+    for (int t = 0; t < T; ++t) {
+      const float* k = K + (size_t)t * D;
+      double dot = 0.0;
+      for (int d = 0; d < D; ++d) dot += (double)q[d] * (double)k[d];
+      s[t] = dot * inv_sqrt_d;
+      smax = std::max(smax, s[t]);
+    }
+    double z = 0.0;
+    for (int t = 0; t < T; ++t) {
+      s[t] = std::exp(s[t] - smax);
+      z += s[t];
+    }
+    const bool newest = (n % W) == W - 1;  // last query of this head's window
+    for (int t = 0; t < T; ++t) {
+      const double p = s[t] / z;
+      usage[t] += p;
+      if (newest) last[t] += p;
+    }
+  }
+  for (int t = 0; t < T; ++t) u[t] = (float)(usage[t] / (double)N);
+
+  switch (scorer) {
+    case AMSO_SCORER_MEAN_WINDOW:
+      for (int t = 0; t < T; ++t) g[t] = u[t];
+      break;
+    case AMSO_SCORER_LAST_QUERY:
+      for (int t = 0; t < T; ++t) g[t] = (float)(last[t] / (double)G);
+      break;
+    case AMSO_SCORER_KEYDIFF: {
+      // g_t = -cos(k_t, kbar), kbar = mean key of the unit.
+      std::vector<double> kbar((size_t)D, 0.0);
+      for (int t = 0; t < T; ++t)
+        for (int d = 0; d < D; ++d) kbar[d] += (double)K[(size_t)t * D + d];
+      double nb = 0.0;
+      for (int d = 0; d < D; ++d) {
+        kbar[d] /= (double)T;
+        nb += kbar[d] * kbar[d];
+      }
+      nb = std::sqrt(nb);
+      for (int t = 0; t < T; ++t) {
+        const float* k = K + (size_t)t * D;
+        double dot = 0.0, nk = 0.0;
+        for (int d = 0; d < D; ++d) {
+          dot += (double)k[d] * kbar[d];
+          nk += (double)k[d] * (double)k[d];
+        }
+        const double den = std::sqrt(nk) * nb;
+        g[t] = den > 0.0 ? (float)(-dot / den) : 0.0f;
+      }
+      break;
+    }
+    case AMSO_SCORER_EXPECTED: {
+      // Queries of the window modelled as Gaussian(mu, Sigma); the score is the
+      // log of E[exp(q.k/sqrt(D))] = mu.k/sqrt(D) + k' Sigma k / (2 D).
+      std::vector<double> mu((size_t)D, 0.0), sigma((size_t)D * D, 0.0);
+      for (int n = 0; n < N; ++n)
+        for (int d = 0; d < D; ++d) mu[d] += (double)Q[(size_t)n * D + d];
+      for (int d = 0; d < D; ++d) mu[d] /= (double)N;
+      for (int n = 0; n < N; ++n)
+        for (int a = 0; a < D; ++a) {
+          const double da = (double)Q[(size_t)n * D + a] - mu[a];
+          for (int b = 0; b < D; ++b)
+            sigma[(size_t)a * D + b] += da * ((double)Q[(size_t)n * D + b] - mu[b]);
+        }
+      for (size_t i = 0; i < sigma.size(); ++i) sigma[i] /= (double)N;
+      for (int t = 0; t < T; ++t) {
+        const float* k = K + (size_t)t * D;
+        double lin = 0.0, quad = 0.0;
+        for (int a = 0; a < D; ++a) {
+          lin += mu[a] * (double)k[a];
+          double row = 0.0;
+          for (int b = 0; b < D; ++b) row += sigma[(size_t)a * D + b] * (double)k[b];
+          quad += (double)k[a] * row;
+        }
+        g[t] = (float)(lin * inv_sqrt_d + quad / (2.0 * (double)D));
+      }
+      break;
+    }
+    default:
+      return -2;
+  }
+  return 0;
+}
+
+// Eq. (1).
+int amso_mass(const float* u, int T, float eps, float* m_cur) {
+  if (!u || !m_cur || T < 1 || !(eps > 0.0f)) return -1;
+  double z = 0.0;
+  for (int t = 0; t < T; ++t) z += std::max((double)u[t], 0.0) + (double)eps;
+  for (int t = 0; t < T; ++t)
+    m_cur[t] = (float)((std::max((double)u[t], 0.0) + (double)eps) / z);
+  return 0;
+}
+
+// c <- lambda c + (1-lambda) m_cur ; m_used = normalize(beta m_cur + (1-beta) normalize(c)).
+int amso_ema(const float* m_cur, float* credit, int T, float lambda, float beta,
+             float* m_used) {
+  if (!m_cur || !credit || !m_used || T < 1) return -1;
+  if (!(lambda >= 0.0f && lambda < 1.0f) || !(beta >= 0.0f && beta <= 1.0f)) return -1;
+  const double lam = (double)lambda, bet = (double)beta;
+  if (lambda == 0.0f) {  // credit not used
+    for (int t = 0; t < T; ++t) {
+      credit[t] = m_cur[t];
+      m_used[t] = m_cur[t];
+    }
+    return 0;
+  }
+  double csum = 0.0;
+  for (int t = 0; t < T; ++t) {
+    credit[t] = (float)(lam * (double)credit[t] + (1.0 - lam) * (double)m_cur[t]);
+    csum += (double)credit[t];
+  }
+  std::vector<double> mix((size_t)T);
+  double msum = 0.0;
+  for (int t = 0; t < T; ++t) {
+    const double ctil = csum > 0.0 ? (double)credit[t] / csum : (double)m_cur[t];
+    mix[t] = bet * (double)m_cur[t] + (1.0 - bet) * ctil;
+    msum += mix[t];
+  }
+  for (int t = 0; t < T; ++t) m_used[t] = (float)(mix[t] / msum);
+  return 0;
+}
+
+// Prefix sums, cut points at k/S, segment masses.
+int amso_segment(const float* m_used, int T, int S, int32_t* bounds, float* seg_mass) {
+  if (!m_used || !bounds || !seg_mass || T < 1 || S < 1) return -1;
+  bounds[0] = 0;
+  bounds[S] = T;
+  int k = 1;
+  double c = 0.0;
+  for (int t = 0; t < T; ++t) {
+    c += (double)m_used[t];
+    // one token may carry the curve across several thresholds at once
+    while (k < S && c >= (double)k / (double)S) {
+      bounds[k] = t + 1;  // the crossing token closes the earlier segment
+      ++k;
+    }
+  }
+  for (; k < S; ++k) bounds[k] = T;  // threshold never reached
+  for (int i = 0; i < S; ++i) {
+    double m = 0.0;
+    for (int t = bounds[i]; t < bounds[i + 1]; ++t) m += (double)m_used[t];
+    seg_mass[i] = (float)m;
+  }
+  return 0;
+}
+
+// Quotas: floor q_min, remainder shared in proportion to segment mass, no
+// segment above its length, total exactly min(budget, T).
+int amso_quota(const int32_t* bounds, const float* seg_mass, int S, int budget,
+               int q_min, int32_t* quota) {
+  if (!bounds || !seg_mass || !quota || S < 1 || budget < 1 || q_min < 0) return -1;
+  const int T = bounds[S];
+  const int64_t bud = std::min<int64_t>(budget, T);
+  std::vector<int64_t> len((size_t)S), qlo((size_t)S), room((size_t)S);
+  int nonempty = 0;
+  for (int i = 0; i < S; ++i) {
+    len[i] = bounds[i + 1] - bounds[i];
+    if (len[i] < 0) return -1;
+    if (len[i] > 0) ++nonempty;
+  }
+  int64_t floor_q = q_min, need = 0;
+  for (int i = 0; i < S; ++i) need += std::min<int64_t>(floor_q, len[i]);
+  if (need > bud) floor_q = nonempty > 0 ? bud / nonempty : 0;  // budget too small for q_min each
+  int64_t rem = bud;
+  std::vector<char> active((size_t)S);
+  for (int i = 0; i < S; ++i) {
+    qlo[i] = std::min<int64_t>(floor_q, len[i]);
+    room[i] = len[i] - qlo[i];
+    active[i] = room[i] > 0;
+    quota[i] = (int32_t)qlo[i];
+    rem -= qlo[i];
+  }
+  std::vector<double> raw((size_t)S, 0.0);
+  // Proportional shares; a segment whose share reaches its room is filled and
+  // leaves the pool, and the shares of the others are recomputed.
+  for (;;) {
+    int n_active = 0;
+    double msum = 0.0;
+    for (int i = 0; i < S; ++i)
+      if (active[i]) {
+        ++n_active;
+        msum += (double)seg_mass[i];
+      }
+    if (n_active == 0 || rem <= 0) break;
+    bool filled = false;
+    for (int i = 0; i < S; ++i)
+      if (active[i])
+        raw[i] = msum > 0.0 ? (double)rem * (double)seg_mass[i] / msum
+                            : (double)rem / (double)n_active;
+    int64_t taken = 0;
+    for (int i = 0; i < S; ++i)
+      if (active[i] && raw[i] >= (double)room[i]) {
+        quota[i] = (int32_t)len[i];
+        taken += room[i];
+        active[i] = 0;
+        filled = true;
+      }
+    rem -= taken;
+    if (!filled) break;
+  }
+  if (rem > 0) {
+    // integer parts, then one extra unit each to the largest fractional parts
+    std::vector<int> order;
+    std::vector<double> frac((size_t)S, 0.0);
+    int64_t given = 0;
+    for (int i = 0; i < S; ++i)
+      if (active[i]) {
+        const double fl = std::floor(raw[i]);
+        frac[i] = raw[i] - fl;
+        quota[i] += (int32_t)fl;
+        given += (int64_t)fl;
+        order.push_back(i);
+      }
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int a, int b) { return frac[a] > frac[b]; });
+    int64_t left = rem - given;
+    while (left > 0) {
+      bool any = false;
+      for (size_t j = 0; j < order.size() && left > 0; ++j) {
+        const int i = order[j];
+        if (quota[i] < len[i]) {
+          ++quota[i];
+          --left;
+          any = true;
+        }
+      }
+      if (!any) return -3;
+    }
+  }
+  return 0;
+}
+
+int amso_select(const float* g, const int32_t* bounds, const int32_t* quota, int S,
+                int32_t* idx, int32_t* n_kept) {
+  if (!g || !bounds || !quota || !idx || !n_kept || S < 1) return -1;
+  int out = 0;
+  std::vector<int32_t> pos;
+  for (int i = 0; i < S; ++i) {
+    const int a = bounds[i], b = bounds[i + 1], q = quota[i];
+    if (q < 0 || q > b - a) return -1;
+    pos.resize((size_t)(b - a));
+    for (int t = a; t < b; ++t) pos[(size_t)(t - a)] = t;
+    std::stable_sort(pos.begin(), pos.end(), [&](int32_t x, int32_t y) {
+      return sel_value(g[x]) > sel_value(g[y]);
+    });
+    std::sort(pos.begin(), pos.begin() + q);
+    for (int j = 0; j < q; ++j) idx[out++] = pos[(size_t)j];
+  }
+  *n_kept = out;
+  return 0;
+}
+
+int amso_compact(const void* K, const void* V, const float* credit, int64_t row_bytes,
+                 const int32_t* idx, int n_kept, void* K_out, void* V_out, float* credit_out) {
+  if (!idx || n_kept < 0 || row_bytes < 1) return -1;
+  for (int j = 0; j < n_kept; ++j) {
+    const int64_t src = (int64_t)idx[j] * row_bytes, dst = (int64_t)j * row_bytes;
+    if (K && K_out) std::memcpy((char*)K_out + dst, (const char*)K + src, (size_t)row_bytes);
+    if (V && V_out) std::memcpy((char*)V_out + dst, (const char*)V + src, (size_t)row_bytes);
+    if (credit && credit_out) credit_out[j] = credit[idx[j]];
+  }
+  return 0;
+}
+
+int amso_compact_paged(const void* K_pool, const void* V_pool, const int32_t* src_table,
+                       void* K_pool_out, void* V_pool_out, const int32_t* dst_table,
+                       int block, int H, int h, int64_t row_bytes,
+                       const int32_t* idx, int n_kept) {
+  if (!src_table || !dst_table || !idx || block < 1 || H < 1 || h < 0 || h >= H) return -1;
+  for (int j = 0; j < n_kept; ++j) {
+    const int p = idx[j];
+    const int64_t s_src = (int64_t)src_table[p / block] * block + p % block;
+    const int64_t s_dst = (int64_t)dst_table[j / block] * block + j % block;
+    const int64_t o_src = (s_src * H + h) * row_bytes, o_dst = (s_dst * H + h) * row_bytes;
+    if (K_pool && K_pool_out)
+      std::memcpy((char*)K_pool_out + o_dst, (const char*)K_pool + o_src, (size_t)row_bytes);
+    if (V_pool && V_pool_out)
+      std::memcpy((char*)V_pool_out + o_dst, (const char*)V_pool + o_src, (size_t)row_bytes);
+  }
+  return 0;
+}
+
+int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K,
+                       const void* K_rows, const void* V_rows, int64_t row_bytes,
+                       float* credit,
+                       float* u, float* g, float* m_used, int32_t* bounds, float* seg_mass,
+                       int32_t* quota, int32_t* idx, int32_t* n_kept,
+                       void* K_out, void* V_out, float* credit_out) {
+  if (!p || !credit || !idx || !n_kept) return -1;
+  const int T = p->T, S = p->S;
+  std::vector<float> u_((size_t)T), g_((size_t)T), mc((size_t)T), mu((size_t)T), sm((size_t)S);
+  std::vector<int32_t> bd((size_t)S + 1), qt((size_t)S);
+  int rc;
+  if ((rc = amso_score(Q, K, p->G, p->W, T, p->D, p->scorer, u_.data(), g_.data()))) return rc;
+  if ((rc = amso_mass(u_.data(), T, p->eps, mc.data()))) return rc;
+  if ((rc = amso_ema(mc.data(), credit, T, p->lambda, p->beta, mu.data()))) return rc;
+  if ((rc = amso_segment(mu.data(), T, S, bd.data(), sm.data()))) return rc;
+  if ((rc = amso_quota(bd.data(), sm.data(), S, p->budget, p->q_min, qt.data()))) return rc;
+  if ((rc = amso_select(g_.data(), bd.data(), qt.data(), S, idx, n_kept))) return rc;
+  if ((rc = amso_compact(K_rows, V_rows, credit, row_bytes, idx, *n_kept, K_out, V_out, credit_out)))
+    return rc;
+  if (u) std::memcpy(u, u_.data(), sizeof(float) * (size_t)T);
+  if (g) std::memcpy(g, g_.data(), sizeof(float) * (size_t)T);
+  if (m_used) std::memcpy(m_used, mu.data(), sizeof(float) * (size_t)T);
+  if (bounds) std::memcpy(bounds, bd.data(), sizeof(int32_t) * ((size_t)S + 1));
+  if (seg_mass) std::memcpy(seg_mass, sm.data(), sizeof(float) * (size_t)S);
+  if (quota) std::memcpy(quota, qt.data(), sizeof(int32_t) * (size_t)S);
+  return 0;
+}
+
+int amso_compress_many(const amso_unit_params* p, int n_units, int n_threads,
+                       const float* Q, int64_t q_stride,
+                       const float* K, int64_t k_stride,
+                       float* credit, int64_t c_stride,
+                       float* u, float* g, int32_t* idx, int32_t* n_kept) {
+  if (!p || n_units < 1 || !Q || !K || !credit || !idx || !n_kept) return -1;
+  if (n_threads < 1) n_threads = (int)std::thread::hardware_concurrency();
+  if (n_threads < 1) n_threads = 1;
+  n_threads = std::min(n_threads, n_units);
+  std::atomic<int> next(0), failed(0);
+  auto work = [&]() {
+    for (;;) {
+      const int i = next.fetch_add(1);
+      if (i >= n_units) return;
+      int32_t* my_idx = idx + (size_t)i * p->budget;
+      for (int j = 0; j < p->budget; ++j) my_idx[j] = -1;
+      const int rc = amso_compress_unit(
+          p, Q + (size_t)i * q_stride, K + (size_t)i * k_stride, nullptr, nullptr, 1,
+          credit + (size_t)i * c_stride,
+          u ? u + (size_t)i * p->T : nullptr, g ? g + (size_t)i * p->T : nullptr,
+          nullptr, nullptr, nullptr, nullptr, my_idx, n_kept + i, nullptr, nullptr, nullptr);
+      if (rc) failed.store(rc);
+    }
+  };
+  std::vector<std::thread> pool;
+  for (int t = 1; t < n_threads; ++t) pool.emplace_back(work);
+  work();
+  for (auto& th : pool) th.join();
+  return failed.load() ? -4 : n_threads;
+}
+
+}  // extern "C"

@@ -1,0 +1,114 @@
+/*
+ * CPU oracle for one Adaptive Mass-Segmented (AMS) KV compression event.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is the plain, slow definition of what the
+ * GPU library must compute; it is imported by tests, by the smoke check and by
+ * the benchmark's CPU-baseline leg, never by the product path.  It shares no
+ * code with the HIP kernels.
+ *
+ * Every function works on ONE unit = one (layer, sequence, KV head) triple
+ * ("retention policies [are computed] independently for each attention head",
+ * Sec. 3.1) with host pointers.  All accumulation is in double; every stored
+ * result is rounded once to float.  Stages take the float outputs of the
+ * previous stage, so a stage can be checked on its own.
+ *
+ * Pinned by tests (see tests/test_oracle_*.py): every function below.
+ * Parity unpinned (documented choices nothing in the paper can confirm): the
+ * value of eps in Eq. (1); plain-mean aggregation of the window softmax over
+ * the G*W (head, query) pairs with scale 1/sqrt(D); the largest-remainder
+ * reading of "round ... followed by a lightweight adjustment step"; credit of
+ * gathered / appended tokens; population covariance and no value-norm term in
+ * the expected-attention score; raw-key mean in the key-diversity score.
+ */
+#ifndef AMS_ORACLE_H
+#define AMS_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  AMSO_SCORER_LAST_QUERY = 0,  /* attention of the newest query of each head   */
+  AMSO_SCORER_MEAN_WINDOW = 1, /* the usage u itself                            */
+  AMSO_SCORER_KEYDIFF = 2,     /* negative cosine to the mean key               */
+  AMSO_SCORER_EXPECTED = 3     /* log Gaussian moment of the query window       */
+};
+
+/* Step 1 of Alg. 1 (usage) + the plug-in base score g (Sec. 3.3 "In-Segment
+ * Selection").  Q is [G][W][D] (query heads of this KV head, then window
+ * position), K is [T][D], both already widened to float.  u, g are [T]. */
+int amso_score(const float* Q, const float* K, int G, int W, int T, int D,
+               int scorer, float* u, float* g);
+
+/* Eq. (1): m_t = (max(u_t,0)+eps) / sum_v (max(u_v,0)+eps). */
+int amso_mass(const float* u, int T, float eps, float* m_cur);
+
+/* Sec. 3.3 "EMA Credit" / Alg. 1 step 2.  credit is updated in place.
+ * lambda == 0 takes the "credit not used" branch: m_used = m_cur bit for bit
+ * (credit still becomes m_cur). */
+int amso_ema(const float* m_cur, float* credit, int T, float lambda, float beta,
+             float* m_used);
+
+/* Alg. 1 step 3 with Delta = 1/S and no split/merge: bounds[0]=0,
+ * bounds[S]=T, bounds[k] = 1 + first 0-based j whose inclusive prefix sum
+ * reaches k/S (T if none).  seg_mass[i] = sum of m over [bounds[i],bounds[i+1]). */
+int amso_segment(const float* m_used, int T, int S, int32_t* bounds, float* seg_mass);
+
+/* Alg. 1 step 4: minimum quota, proportional share of the remainder, clip to
+ * the segment length, adjust so the quotas sum to min(budget, T). */
+int amso_quota(const int32_t* bounds, const float* seg_mass, int S, int budget,
+               int q_min, int32_t* quota);
+
+/* Alg. 1 step 5 without a must-keep set: per segment the quota[i] largest g,
+ * equal scores resolved towards the lower index, result ascending.
+ * idx has room for sum(quota); returns the number written in *n_kept. */
+int amso_select(const float* g, const int32_t* bounds, const int32_t* quota, int S,
+                int32_t* idx, int32_t* n_kept);
+
+/* Alg. 1 step 6: row gather of K, V (row_bytes bytes per token) and credit. */
+int amso_compact(const void* K, const void* V, const float* credit, int64_t row_bytes,
+                 const int32_t* idx, int n_kept, void* K_out, void* V_out, float* credit_out);
+
+/* Paged form of the same gather (App. E): token p of the sequence lives in
+ * physical slot table[p/block]*block + p%block; a slot holds H rows, row of
+ * head h at ((slot*H)+h)*row_bytes.  Destination slot of compact position j is
+ * taken from dst_table the same way. */
+int amso_compact_paged(const void* K_pool, const void* V_pool, const int32_t* src_table,
+                       void* K_pool_out, void* V_pool_out, const int32_t* dst_table,
+                       int block, int H, int h, int64_t row_bytes,
+                       const int32_t* idx, int n_kept);
+
+/* One whole event for one unit, stages chained through their float outputs.
+ * Any of the optional outputs may be NULL.  credit [T] in/out (full length,
+ * updated), credit_out [n_kept] gathered. */
+typedef struct {
+  int G, W, T, D;
+  int scorer;
+  int budget, S, q_min;
+  float lambda, beta, eps;
+} amso_unit_params;
+
+int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K,
+                       const void* K_rows, const void* V_rows, int64_t row_bytes,
+                       float* credit,
+                       float* u, float* g, float* m_used, int32_t* bounds, float* seg_mass,
+                       int32_t* quota, int32_t* idx, int32_t* n_kept,
+                       void* K_out, void* V_out, float* credit_out);
+
+/* Runs amso_compress_unit over n_units independent units laid out back to back
+ * (strides given in elements / bytes), with a plain thread parallel-for over
+ * units.  Used for timing the oracle and for checking many units at once.
+ * Outputs idx [n_units][budget] (tail -1), n_kept [n_units], u/g [n_units][T]
+ * (either may be NULL).  Returns the number of threads used (>0) or <0 on error. */
+int amso_compress_many(const amso_unit_params* p, int n_units, int n_threads,
+                       const float* Q, int64_t q_stride,
+                       const float* K, int64_t k_stride,
+                       float* credit, int64_t c_stride,
+                       float* u, float* g, int32_t* idx, int32_t* n_kept);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
