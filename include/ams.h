@@ -1,0 +1,184 @@
+/*
+ * ams.h - C ABI of the MI355X (gfx950) hot path of Adaptive Mass-Segmented
+ * (AMS) KV-cache compression.
+ *
+ * One "compression event" (Alg. 1 of the paper) bounds a KV cache of length T
+ * to a budget T_keep.  It runs independently for every unit = (layer,
+ * sequence, KV head) ("retention policies [are computed] independently for
+ * each attention head", Sec. 3.1).  The entry points below are the stages of
+ * that event plus a fused call that chains them.
+ *
+ * General conventions
+ *  - Pointers marked [dev] are DEVICE pointers owned by the caller; pointers
+ *    marked [host] are host pointers read before the call returns.  The
+ *    library allocates no device memory, never frees anything and never
+ *    synchronises: all work is enqueued on `stream` (a hipStream_t passed as
+ *    void*, NULL = the default stream) and the call returns at once.
+ *  - Every call returns an ams_status.  Argument errors are found on the host
+ *    before anything is launched; nothing aborts or throws.
+ *  - Units are ordered unit = (layer * batch + b) * n_kv_heads + h.
+ *  - Per-unit fp32 vectors (u, g, credit, m_used) are rows of a
+ *    [units, t_stride] array; only the first seq_lens[b] entries of a row are
+ *    read or written.
+ *  - Positions are 0-based positions in the CURRENT cache (the mass curve is
+ *    defined "over current KV-cache positions", Fig. 3 caption).
+ *  - KV head h owns query heads h*group .. h*group + group - 1.
+ */
+#ifndef AMS_H
+#define AMS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AMS_OK = 0,
+  AMS_ERR_INVALID_ARG = 1,         /* null pointer, size < 1, value out of range          */
+  AMS_ERR_UNSUPPORTED = 2,         /* valid request this build has no kernel for          */
+  AMS_ERR_WORKSPACE_TOO_SMALL = 3, /* ws_bytes < ams_workspace_bytes(...)                 */
+  AMS_ERR_HIP = 4                  /* a HIP launch reported an error                      */
+} ams_status;
+
+typedef enum { AMS_F32 = 0, AMS_BF16 = 1 } ams_dtype;
+
+/* Plug-in base scorer g (Sec. 3.3 "In-Segment Selection with a Plug-and-Play
+ * Scorer").  The mass that places segments always comes from the mean
+ * recent-window attention (Sec. 3.2); only the in-segment ranking changes. */
+typedef enum {
+  AMS_SCORER_LAST_QUERY = 0,  /* attention of the newest query of each head (TOVA-style)   */
+  AMS_SCORER_MEAN_WINDOW = 1, /* g = u, the mean attention over the query window           */
+  AMS_SCORER_KEYDIFF = 2,     /* negative cosine between a key and the mean key            */
+  AMS_SCORER_EXPECTED = 3,    /* log Gaussian moment of the window's query distribution    */
+  AMS_SCORER_EXTERNAL = 4     /* caller supplies g (stage calls only)                      */
+} ams_scorer;
+
+typedef enum {
+  AMS_LAYOUT_DENSE = 0, /* K, V = [layers, batch, kv_heads, t_capacity, head_dim]          */
+  AMS_LAYOUT_PAGED = 1  /* per layer a pool [n_slots, kv_heads, head_dim]; token p of
+                           sequence b lives in slot block_table[b][p / 16] * 16 + p % 16  */
+} ams_layout;
+
+/* Problem statement of one event (Alg. 1 "Require").  Plain data, [host]. */
+typedef struct {
+  int32_t n_layers, batch, n_kv_heads;
+  int32_t group;      /* G: query heads per KV head                                        */
+  int32_t head_dim;   /* D: 128                                                            */
+  int32_t window;     /* W: recent decoding queries per query head (Sec. 3.2)             */
+  int32_t kv_dtype;   /* ams_dtype of K, V and Q                                           */
+  int32_t t_max;      /* upper bound of every seq_lens[b]; sizes the launches              */
+  int64_t t_stride;   /* row stride (elements) of the per-unit fp32 vectors, >= t_max      */
+  int32_t budget;     /* T_keep                                                            */
+  int32_t n_segments; /* S: segments of target mass Delta = 1/S (Sec. 3.3)                 */
+  int32_t q_min;      /* minimum quota per non-empty segment (paper default 1)            */
+  float ema_lambda;   /* credit decay, 0 <= lambda < 1; 0 = credit not used                */
+  float ema_beta;     /* mass mixing, 0 <= beta <= 1 (paper default 0.9)                   */
+  float mass_eps;     /* epsilon of Eq. (1), > 0                                           */
+  int32_t scorer;     /* ams_scorer                                                        */
+} ams_params;
+
+/* A KV cache as the library sees it.  Plain data, [host]; k, v, block_table [dev]. */
+typedef struct {
+  int32_t layout;             /* ams_layout                                                */
+  void* k;                    /* [dev]                                                     */
+  void* v;                    /* [dev] may be NULL for ams_score                           */
+  int64_t t_capacity;         /* dense: rows per unit slab                                 */
+  const int32_t* block_table; /* paged: [dev] [batch, max_blocks_per_seq]                  */
+  int32_t max_blocks_per_seq; /* paged                                                     */
+  int32_t block_size;         /* paged: must be 16                                         */
+  int64_t n_slots;            /* paged: slots per layer pool                               */
+} ams_kv_view;
+
+const char* ams_status_string(int status);
+
+/* Bytes of scratch the calls below need for these parameters ([host], pure). */
+size_t ams_workspace_bytes(const ams_params* p);
+
+/* Where ams_compress_step leaves its intermediates inside the workspace (byte
+ * offsets, [host], pure): u, g, m_used are fp32 [units, t_stride] (g == u for
+ * AMS_SCORER_MEAN_WINDOW), bounds int32 [units, S+1], seg_mass fp32 [units, S],
+ * quota int32 [units, S].  For inspection and tests; the layout is otherwise
+ * private. */
+typedef struct {
+  size_t u, g, m_used, bounds, seg_mass, quota;
+} ams_workspace_view;
+int ams_workspace_layout(const ams_params* p, ams_workspace_view* out);
+
+/*
+ * ams_score - usage u and base score g (Alg. 1 step 1; Sec. 3.2; Sec. 3.3).
+ *   s[n][t] = q_n . k_t / sqrt(D) over the N = G*W recent queries of the unit,
+ *   p = softmax over t, u[t] = mean_n p[n][t]; g per p->scorer (g may equal u
+ *   as a pointer only for AMS_SCORER_MEAN_WINDOW; for AMS_SCORER_EXTERNAL g is
+ *   left untouched).
+ *   q  [dev] [layers, batch, kv_heads*group, window, head_dim], kv_dtype
+ *   seq_lens [dev] [batch] int32, each in [1, t_max]
+ *   u, g [dev] fp32 [units, t_stride], written
+ */
+int ams_score(const ams_params* p, const ams_kv_view* src, const int32_t* seq_lens, const void* q,
+              float* u, float* g, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * ams_ema_update - Eq. (1) followed by the EMA credit (Sec. 3.3 "EMA Credit for
+ * Temporal Stability"; Alg. 1 step 2):
+ *   m = normalize(max(u,0)+eps); credit <- lambda*credit + (1-lambda)*m;
+ *   m_used = normalize(beta*m + (1-beta)*normalize(credit)).
+ * lambda == 0: m_used = m and credit <- m.
+ *   u [dev] in; credit [dev] in/out; m_used [dev] out; all fp32 [units, t_stride]
+ */
+int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u, float* credit,
+                   float* m_used, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * ams_mass_segment - prefix sum of the mass and cut points (Sec. 3.3
+ * "Mass-based adaptive segmentation"; Alg. 1 step 3) with Delta = 1/S:
+ *   bounds[0] = 0, bounds[S] = T, bounds[k] = 1 + min{ j : c(j) >= k/S } (T if the
+ *   threshold is never reached); seg_mass[i] = sum of m_used over segment i.
+ *   bounds [dev] int32 [units, S+1]; seg_mass [dev] fp32 [units, S]
+ */
+int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* m_used,
+                     int32_t* bounds, float* seg_mass, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * ams_select - segment quotas and in-segment top-k (Sec. 3.3 "Segment-wise Quota
+ * Allocation", "In-Segment Selection"; Alg. 1 steps 4-5, no must-keep set).
+ *   quota: floor min(q_min, L_i), remainder shared in proportion to seg_mass,
+ *   no quota above the segment length, sum = min(budget, T).
+ *   idx: per segment the quota[i] positions of largest g (equal scores: lower
+ *   position first; NaN ranks below everything), ascending; entries from n_kept
+ *   to budget are -1.
+ *   quota [dev] int32 [units, S]; idx [dev] int32 [units, budget]; n_kept [dev] int32 [units]
+ */
+int ams_select(const ams_params* p, const int32_t* seq_lens, const float* g, const int32_t* bounds,
+               const float* seg_mass, int32_t* quota, int32_t* idx, int32_t* n_kept,
+               void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * ams_compact - gather of the kept rows (Alg. 1 step 6: K' = K[idx], V' = V[idx]);
+ * with a paged destination it is the head-wise compaction of App. E:
+ *   K_new[pi_new(b, j), h, :] <- K_old[pi_old(b, idx[b,h,j]), h, :].
+ * Row j of unit (l,b,h) goes to row j of the destination unit slab (dense) or to
+ * slot dst.block_table[b][j/16]*16 + j%16 (paged).  src and dst must not overlap.
+ *   credit_src [dev] fp32 [units, t_stride] or NULL; credit_dst [dev] fp32
+ *   [units, budget] (row j = credit_src[idx[j]]) or NULL.
+ */
+int ams_compact(const ams_params* p, const ams_kv_view* src, const int32_t* idx,
+                const int32_t* n_kept, const ams_kv_view* dst, const float* credit_src,
+                float* credit_dst, void* stream);
+
+/*
+ * ams_compress_step - one whole event: score -> Eq. (1) -> EMA -> prefix sum and
+ * boundaries -> quotas -> segmented top-k -> gather-compact, in that order, all
+ * enqueued on `stream`.  credit [units, t_stride] is updated in place at full
+ * length; credit_dst [units, budget] receives the kept tokens' credit.
+ * p->scorer must not be AMS_SCORER_EXTERNAL.
+ */
+int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t* seq_lens,
+                      const void* q, float* credit, const ams_kv_view* dst, float* credit_dst,
+                      int32_t* idx, int32_t* n_kept, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,243 @@
+// Host side of the C ABI declared in include/ams.h: argument checks, workspace carving and the
+// order of the launches.  Nothing here touches device memory or waits for the stream.
+#include <math.h>
+
+#include "ams_internal.h"
+
+namespace ams {
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Number of 32-query column blocks the scoring kernels are instantiated for.
+static int padded_queries(int n, bool bf16) {
+  const int nb = (n + 31) / 32;
+  const int avail_bf16[] = {1, 2, 4, 7, 8}, avail_f32[] = {1, 2, 4};
+  if (bf16) {
+    for (int v : avail_bf16)
+      if (nb <= v) return v * 32;
+  } else {
+    for (int v : avail_f32)
+      if (nb <= v) return v * 32;
+  }
+  return 0;
+}
+
+WsLayout ws_layout(const ams_params* p) {
+  WsLayout w;
+  const size_t units = (size_t)p->n_layers * p->batch * p->n_kv_heads;
+  w.n_chunks = div_up(p->t_max, kScoreChunk);
+  w.n_pad = padded_queries(p->group * p->window, p->kv_dtype == AMS_BF16);
+  const size_t vec = align256(units * (size_t)p->t_stride * sizeof(float));
+  size_t o = 0;
+  w.part_stats = o; o += align256(units * w.n_chunks * (size_t)w.n_pad * sizeof(float2));
+  w.fin_stats = o;  o += align256(units * (size_t)w.n_pad * sizeof(float4));
+  w.u = o;          o += vec;
+  w.g = o;          o += vec;
+  w.m_used = o;     o += vec;
+  w.bounds = o;     o += align256(units * (size_t)(p->n_segments + 1) * sizeof(int32_t));
+  w.seg_mass = o;   o += align256(units * (size_t)p->n_segments * sizeof(float));
+  w.quota = o;      o += align256(units * (size_t)p->n_segments * sizeof(int32_t));
+  w.kbar = o;       o += align256(units * w.n_chunks * (size_t)p->head_dim * sizeof(double));
+  w.total = o;
+  return w;
+}
+
+static int check_params(const ams_params* p) {
+  if (!p) return AMS_ERR_INVALID_ARG;
+  if (p->n_layers < 1 || p->batch < 1 || p->n_kv_heads < 1 || p->group < 1 || p->window < 1 ||
+      p->head_dim < 1 || p->t_max < 1 || p->t_stride < p->t_max || p->budget < 1 || p->n_segments < 1 ||
+      p->q_min < 0)
+    return AMS_ERR_INVALID_ARG;
+  if (p->kv_dtype != AMS_F32 && p->kv_dtype != AMS_BF16) return AMS_ERR_INVALID_ARG;
+  if (!(p->ema_lambda >= 0.f && p->ema_lambda < 1.f) || !(p->ema_beta >= 0.f && p->ema_beta <= 1.f) ||
+      !(p->mass_eps > 0.f) || isinf(p->mass_eps))
+    return AMS_ERR_INVALID_ARG;
+  if (p->scorer < AMS_SCORER_LAST_QUERY || p->scorer > AMS_SCORER_EXTERNAL) return AMS_ERR_INVALID_ARG;
+  if (p->head_dim != 128) return AMS_ERR_UNSUPPORTED;
+  if (p->n_segments > 1024) return AMS_ERR_UNSUPPORTED;
+  const int64_t units = (int64_t)p->n_layers * p->batch * p->n_kv_heads;
+  if (units > 65535) return AMS_ERR_UNSUPPORTED;
+  if ((int64_t)p->group * p->window > 256) return AMS_ERR_UNSUPPORTED;
+  if (padded_queries(p->group * p->window, p->kv_dtype == AMS_BF16) == 0) return AMS_ERR_UNSUPPORTED;
+  return AMS_OK;
+}
+
+static int check_view(const ams_params* p, const ams_kv_view* v, int64_t rows_needed, bool need_v) {
+  if (!v || !v->k || (need_v && !v->v)) return AMS_ERR_INVALID_ARG;
+  if (v->layout == AMS_LAYOUT_DENSE) {
+    if (v->t_capacity < rows_needed) return AMS_ERR_INVALID_ARG;
+  } else if (v->layout == AMS_LAYOUT_PAGED) {
+    if (!v->block_table || v->max_blocks_per_seq < 1 || v->n_slots < 16) return AMS_ERR_INVALID_ARG;
+    if (v->block_size != 16) return AMS_ERR_UNSUPPORTED;
+    if ((int64_t)v->max_blocks_per_seq * 16 < rows_needed) return AMS_ERR_INVALID_ARG;
+  } else {
+    return AMS_ERR_INVALID_ARG;
+  }
+  (void)p;
+  return AMS_OK;
+}
+
+static Dims make_dims(const ams_params* p) {
+  Dims d;
+  d.L = p->n_layers;
+  d.B = p->batch;
+  d.H = p->n_kv_heads;
+  d.G = p->group;
+  d.W = p->window;
+  d.D = p->head_dim;
+  d.N = p->group * p->window;
+  d.units = p->n_layers * p->batch * p->n_kv_heads;
+  d.t_max = p->t_max;
+  d.t_stride = p->t_stride;
+  return d;
+}
+
+static KvDev make_kv(const ams_params* p, const ams_kv_view* v, void* base) {
+  KvDev k;
+  k.base = (char*)base;
+  k.block_table = v->block_table;
+  k.t_capacity = v->t_capacity;
+  k.n_slots = v->n_slots;
+  k.layout = v->layout;
+  k.max_blocks = v->max_blocks_per_seq;
+  k.B = p->batch;
+  k.H = p->n_kv_heads;
+  k.row_bytes = p->head_dim * (p->kv_dtype == AMS_BF16 ? 2 : 4);
+  return k;
+}
+
+static int hip_status(hipError_t e) { return e == hipSuccess ? AMS_OK : AMS_ERR_HIP; }
+
+}  // namespace ams
+
+using namespace ams;
+
+extern "C" {
+
+const char* ams_status_string(int status) {
+  switch (status) {
+    case AMS_OK: return "ok";
+    case AMS_ERR_INVALID_ARG: return "invalid argument";
+    case AMS_ERR_UNSUPPORTED: return "unsupported configuration";
+    case AMS_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case AMS_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+size_t ams_workspace_bytes(const ams_params* p) {
+  if (check_params(p) != AMS_OK) return 0;
+  return ws_layout(p).total;
+}
+
+int ams_workspace_layout(const ams_params* p, ams_workspace_view* out) {
+  const int rc = check_params(p);
+  if (rc) return rc;
+  if (!out) return AMS_ERR_INVALID_ARG;
+  const WsLayout wl = ws_layout(p);
+  out->u = wl.u;
+  out->g = p->scorer == AMS_SCORER_MEAN_WINDOW ? wl.u : wl.g;
+  out->m_used = wl.m_used;
+  out->bounds = wl.bounds;
+  out->seg_mass = wl.seg_mass;
+  out->quota = wl.quota;
+  return AMS_OK;
+}
+
+int ams_score(const ams_params* p, const ams_kv_view* src, const int32_t* seq_lens, const void* q,
+              float* u, float* g, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if ((rc = check_view(p, src, p->t_max, false))) return rc;
+  if (!seq_lens || !q || !u || !ws) return AMS_ERR_INVALID_ARG;
+  if (p->scorer != AMS_SCORER_EXTERNAL && !g) return AMS_ERR_INVALID_ARG;
+  if (p->scorer != AMS_SCORER_MEAN_WINDOW && p->scorer != AMS_SCORER_EXTERNAL && g == u)
+    return AMS_ERR_INVALID_ARG;
+  const WsLayout wl = ws_layout(p);
+  if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
+  return hip_status(launch_score(p, make_dims(p), make_kv(p, src, src->k), seq_lens, q, u, g, (char*)ws,
+                                 wl, (hipStream_t)stream));
+}
+
+int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u, float* credit,
+                   float* m_used, void* ws, size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  const int rc = check_params(p);
+  if (rc) return rc;
+  if (!seq_lens || !u || !credit || !m_used) return AMS_ERR_INVALID_ARG;
+  return hip_status(launch_ema(p, make_dims(p), seq_lens, u, credit, m_used, (hipStream_t)stream));
+}
+
+int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* m_used,
+                     int32_t* bounds, float* seg_mass, void* ws, size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  const int rc = check_params(p);
+  if (rc) return rc;
+  if (!seq_lens || !m_used || !bounds || !seg_mass) return AMS_ERR_INVALID_ARG;
+  return hip_status(launch_segment(p, make_dims(p), seq_lens, m_used, bounds, seg_mass, (hipStream_t)stream));
+}
+
+int ams_select(const ams_params* p, const int32_t* seq_lens, const float* g, const int32_t* bounds,
+               const float* seg_mass, int32_t* quota, int32_t* idx, int32_t* n_kept,
+               void* ws, size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  const int rc = check_params(p);
+  if (rc) return rc;
+  if (!seq_lens || !g || !bounds || !seg_mass || !quota || !idx || !n_kept) return AMS_ERR_INVALID_ARG;
+  return hip_status(launch_select(p, make_dims(p), seq_lens, g, bounds, seg_mass, quota, idx, n_kept,
+                                  (hipStream_t)stream));
+}
+
+int ams_compact(const ams_params* p, const ams_kv_view* src, const int32_t* idx, const int32_t* n_kept,
+                const ams_kv_view* dst, const float* credit_src, float* credit_dst, void* stream) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  const int64_t keep = p->budget < p->t_max ? p->budget : p->t_max;
+  if ((rc = check_view(p, src, p->t_max, true))) return rc;
+  if ((rc = check_view(p, dst, keep, true))) return rc;
+  if (!idx || !n_kept) return AMS_ERR_INVALID_ARG;
+  if (src->k == dst->k || src->v == dst->v) return AMS_ERR_INVALID_ARG;
+  return hip_status(launch_compact(p, make_dims(p), make_kv(p, src, src->k), make_kv(p, src, src->v),
+                                   make_kv(p, dst, dst->k), make_kv(p, dst, dst->v), idx, n_kept,
+                                   credit_src, credit_dst, (hipStream_t)stream));
+}
+
+int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t* seq_lens,
+                      const void* q, float* credit, const ams_kv_view* dst, float* credit_dst,
+                      int32_t* idx, int32_t* n_kept, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if (p->scorer == AMS_SCORER_EXTERNAL) return AMS_ERR_INVALID_ARG;
+  const int64_t keep = p->budget < p->t_max ? p->budget : p->t_max;
+  if ((rc = check_view(p, src, p->t_max, true))) return rc;
+  if ((rc = check_view(p, dst, keep, true))) return rc;
+  if (!seq_lens || !q || !credit || !idx || !n_kept || !ws) return AMS_ERR_INVALID_ARG;
+  if (src->k == dst->k || src->v == dst->v) return AMS_ERR_INVALID_ARG;
+  const WsLayout wl = ws_layout(p);
+  if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
+  char* w = (char*)ws;
+  const Dims d = make_dims(p);
+  hipStream_t s = (hipStream_t)stream;
+  float* u = (float*)(w + wl.u);
+  float* g = p->scorer == AMS_SCORER_MEAN_WINDOW ? u : (float*)(w + wl.g);
+  float* m_used = (float*)(w + wl.m_used);
+  int32_t* bounds = (int32_t*)(w + wl.bounds);
+  float* seg_mass = (float*)(w + wl.seg_mass);
+  int32_t* quota = (int32_t*)(w + wl.quota);
+  hipError_t e;
+  if ((e = launch_score(p, d, make_kv(p, src, src->k), seq_lens, q, u, g, w, wl, s)) != hipSuccess)
+    return AMS_ERR_HIP;
+  if ((e = launch_ema(p, d, seq_lens, u, credit, m_used, s)) != hipSuccess) return AMS_ERR_HIP;
+  if ((e = launch_segment(p, d, seq_lens, m_used, bounds, seg_mass, s)) != hipSuccess) return AMS_ERR_HIP;
+  if ((e = launch_select(p, d, seq_lens, g, bounds, seg_mass, quota, idx, n_kept, s)) != hipSuccess)
+    return AMS_ERR_HIP;
+  if ((e = launch_compact(p, d, make_kv(p, src, src->k), make_kv(p, src, src->v), make_kv(p, dst, dst->k),
+                          make_kv(p, dst, dst->v), idx, n_kept, credit, credit_dst, s)) != hipSuccess)
+    return AMS_ERR_HIP;
+  return AMS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+// Shared declarations of the HIP implementation behind include/ams.h.
+#ifndef AMS_INTERNAL_H
+#define AMS_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ams.h"
+
+namespace ams {
+
+// Device-side description of one of K / V of a cache.
+struct KvDev {
+  char* base;
+  const int32_t* block_table;
+  int64_t t_capacity;  // dense: rows per unit slab
+  int64_t n_slots;     // paged: slots per layer
+  int32_t layout;
+  int32_t max_blocks;
+  int32_t B, H;
+  int32_t row_bytes;
+};
+
+// Address of the row of token t of unit (l, b, h).
+__device__ __forceinline__ char* kv_row(const KvDev& kv, int l, int b, int h, int t) {
+  if (kv.layout == AMS_LAYOUT_DENSE) {
+    const int64_t unit = ((int64_t)l * kv.B + b) * kv.H + h;
+    return kv.base + (unit * kv.t_capacity + t) * (int64_t)kv.row_bytes;
+  }
+  const int64_t slot = (int64_t)kv.block_table[(int64_t)b * kv.max_blocks + (t >> 4)] * 16 + (t & 15);
+  return kv.base + (((int64_t)l * kv.n_slots + slot) * kv.H + h) * (int64_t)kv.row_bytes;
+}
+
+struct Dims {
+  int32_t L, B, H, G, W, D, N;  // N = G*W
+  int32_t units;
+  int32_t t_max;
+  int64_t t_stride;
+};
+
+__device__ __forceinline__ void unit_coords(const Dims& d, int unit, int& l, int& b, int& h) {
+  h = unit % d.H;
+  const int lb = unit / d.H;
+  b = lb % d.B;
+  l = lb / d.B;
+}
+
+constexpr int kScoreChunk = 1024;  // tokens per workgroup of the scoring kernels
+
+inline int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// Workspace carving (offsets in bytes, 256-byte aligned).
+struct WsLayout {
+  size_t part_stats, fin_stats, u, g, m_used, bounds, seg_mass, quota, kbar, total;
+  int n_chunks, n_pad;
+};
+WsLayout ws_layout(const ams_params* p);
+
+// ---- launchers (each returns hipGetLastError() of its launches) ----
+hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
+                        const void* q, float* u, float* g, char* ws, const WsLayout& wl, hipStream_t s);
+hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
+                      float* credit, float* m_used, hipStream_t s);
+hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq_lens,
+                          const float* m_used, int32_t* bounds, float* seg_mass, hipStream_t s);
+hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* g,
+                         const int32_t* bounds, const float* seg_mass, int32_t* quota, int32_t* idx,
+                         int32_t* n_kept, hipStream_t s);
+hipError_t launch_compact(const ams_params* p, const Dims& d, const KvDev& ks, const KvDev& vs,
+                          const KvDev& kd, const KvDev& vd, const int32_t* idx, const int32_t* n_kept,
+                          const float* credit_src, float* credit_dst, hipStream_t s);
+
+}  // namespace ams
+#endif

@@ -1,0 +1,501 @@
+// Usage u and base score g (Alg. 1 step 1; Sec. 3.2; Sec. 3.3 plug-in scorer).
+//
+// s[n][t] = q_n . k_t / sqrt(D) is a dense N x D by D x T contraction and runs on
+// the matrix cores (32x32 MFMA tiles, token rows x query columns).  The row
+// softmax needs every row's normaliser before a column can be finished, so the
+// work is two sweeps over K:
+//   sweep 1  per 1024-token chunk, per query: running (max, sum of exp) in the
+//            log2 domain, lane-local, merged per chunk          -> part_stats
+//   reduce   chunks merged in a fixed order                     -> (M_n, weights)
+//   sweep 2  tiles recomputed, exp2(s - M_n) weighted by 1/(N Z_n) and summed
+//            over the queries of each token                     -> u (and g)
+// The score matrix itself never reaches memory.
+#include "ams_internal.h"
+
+namespace ams {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+namespace {
+
+constexpr float kNegInit = -3.0e38f;  // finite "minus infinity" for running maxima
+constexpr int kThreads = 256;
+
+enum { MODE_MEAN = 0, MODE_LAST = 1, MODE_EXPECTED = 2 };
+
+struct ScoreArgs {
+  KvDev k;
+  Dims d;
+  const int32_t* seq_lens;
+  const char* q;
+  float2* part;  // [units][n_chunks][n_pad]  (max, sum) in the log2 domain
+  float4* fin;   // [units][n_pad]  (M, weight for u, weight for g, query is real)
+  float* u;
+  float* g;
+  int n_chunks, n_pad;
+  float c2;          // log2(e) / sqrt(D)
+  float inv_sqrt_d;  // 1 / sqrt(D)
+};
+
+template <bool BF16>
+struct Tr;
+template <>
+struct Tr<true> {
+  static constexpr int kRowBytes = 256, kQStride = 272, kAVecs = 8;
+};
+template <>
+struct Tr<false> {
+  static constexpr int kRowBytes = 512, kQStride = 528, kAVecs = 16;
+};
+
+// Query window of the unit -> LDS, rows padded against bank conflicts, rows >= N zero.
+template <bool BF16, int NB>
+__device__ __forceinline__ void load_q(const ScoreArgs& a, int l, int b, int h, char* qlds) {
+  constexpr int RB = Tr<BF16>::kRowBytes, QS = Tr<BF16>::kQStride, CPR = RB / 16;
+  const char* src = a.q + ((((int64_t)l * a.d.B + b) * a.d.H + h) * a.d.G) * (int64_t)a.d.W * RB;
+  for (int ch = threadIdx.x; ch < NB * 32 * CPR; ch += kThreads) {
+    const int n = ch / CPR, col = ch % CPR;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (n < a.d.N) v = *(const uint4*)(src + (int64_t)n * RB + col * 16);
+    *(uint4*)(qlds + n * QS + col * 16) = v;
+  }
+}
+
+// Lane (r = lane % 32, hf = lane / 32) reads the hf-th half of row t0 + r: one contiguous
+// 128-byte (bf16) or 256-byte (fp32) piece.  The contraction index is permuted the same way on
+// the query side, which leaves the dot products unchanged.
+template <bool BF16>
+__device__ __forceinline__ void load_a(const ScoreArgs& a, int l, int b, int h, int t0, int T,
+                                       int lane, uint4 (&av)[Tr<BF16>::kAVecs]) {
+  constexpr int NV = Tr<BF16>::kAVecs;
+  const int t = t0 + (lane & 31);
+  if (t < T) {
+    const uint4* p = (const uint4*)(kv_row(a.k, l, b, h, t) + (lane >> 5) * (Tr<BF16>::kRowBytes / 2));
+#pragma unroll
+    for (int i = 0; i < NV; ++i) av[i] = p[i];
+  } else {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) av[i] = make_uint4(0, 0, 0, 0);
+  }
+}
+
+// acc[nb][i] = s_raw[token 8*(i/4) + 4*hf + i%4][query nb*32 + lane%32]
+template <bool BF16, int NB>
+__device__ __forceinline__ void tile_mma(const uint4 (&av)[Tr<BF16>::kAVecs], const char* qlds,
+                                         int lane, floatx16 (&acc)[NB]) {
+  constexpr int QS = Tr<BF16>::kQStride;
+  const char* qb = qlds + (lane & 31) * QS + (lane >> 5) * (Tr<BF16>::kRowBytes / 2);
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[nb][i] = 0.f;
+  if constexpr (BF16) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8 A = __builtin_bit_cast(bf16x8, av[ks]);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const uint4 bv = *(const uint4*)(qb + nb * 32 * QS + ks * 16);
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(bf16x8, bv), acc[nb], 0, 0, 0);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const float4 A = __builtin_bit_cast(float4, av[j]);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const float4 bv = *(const float4*)(qb + nb * 32 * QS + j * 16);
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(A.x, bv.x, acc[nb], 0, 0, 0);
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(A.y, bv.y, acc[nb], 0, 0, 0);
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(A.z, bv.z, acc[nb], 0, 0, 0);
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(A.w, bv.w, acc[nb], 0, 0, 0);
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ int acc_row(int i, int hf) { return 8 * (i >> 2) + 4 * hf + (i & 3); }
+
+// Sum of 16 per-lane values over the 32 lanes of a half wave, halving the number of live values
+// at every exchange.  Lane c ends up with the total of value index c >> 1.
+__device__ __forceinline__ float reduce16_over32(const float (&v)[16], int c) {
+  float w8[8], w4[4], w2[2];
+  const bool b4 = c & 16, b3 = c & 8, b2 = c & 4, b1 = c & 2;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float keep = b4 ? v[j + 8] : v[j], send = b4 ? v[j] : v[j + 8];
+    w8[j] = keep + __shfl_xor(send, 16);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float keep = b3 ? w8[j + 4] : w8[j], send = b3 ? w8[j] : w8[j + 4];
+    w4[j] = keep + __shfl_xor(send, 8);
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const float keep = b2 ? w4[j + 2] : w4[j], send = b2 ? w4[j] : w4[j + 2];
+    w2[j] = keep + __shfl_xor(send, 4);
+  }
+  const float keep = b1 ? w2[1] : w2[0], send = b1 ? w2[0] : w2[1];
+  const float w1 = keep + __shfl_xor(send, 2);
+  return w1 + __shfl_xor(w1, 1);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Sweep 1: per chunk, per query (max, sum exp2) of the scaled logits.
+// ---------------------------------------------------------------------------------------------
+template <bool BF16, int NB>
+__global__ __launch_bounds__(kThreads) void score_stats_kernel(ScoreArgs a) {
+  extern __shared__ __align__(16) char qlds[];
+  __shared__ float2 xch[4][NB * 32];
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  const int c0 = chunk * kScoreChunk;
+  if (c0 >= T) return;
+  load_q<BF16, NB>(a, l, b, h, qlds);
+  __syncthreads();
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
+  float m[NB], z[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    m[nb] = kNegInit;
+    z[nb] = 0.f;
+  }
+  uint4 av[Tr<BF16>::kAVecs];
+  floatx16 acc[NB];
+  for (int blk = 0; blk < kScoreChunk / 128; ++blk) {
+    const int t0 = c0 + (blk * 4 + wave) * 32;
+    if (t0 >= T) break;
+    load_a<BF16>(a, l, b, h, t0, T, lane, av);
+    tile_mma<BF16, NB>(av, qlds, lane, acc);
+    const bool ragged = t0 + 32 > T;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      float x[16];
+      float mx = m[nb];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        x[i] = acc[nb][i] * a.c2;
+        if (ragged && t0 + acc_row(i, hf) >= T) x[i] = -INFINITY;
+        mx = fmaxf(mx, x[i]);
+      }
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s += __builtin_amdgcn_exp2f(x[i] - mx);
+      z[nb] = z[nb] * __builtin_amdgcn_exp2f(m[nb] - mx) + s;
+      m[nb] = mx;
+    }
+  }
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const float m2 = __shfl_xor(m[nb], 32), z2 = __shfl_xor(z[nb], 32);
+    const float M = fmaxf(m[nb], m2);
+    // lower half first so that both halves compute the same value
+    const float zl = hf ? z2 : z[nb], ml = hf ? m2 : m[nb], zh = hf ? z[nb] : z2, mh = hf ? m[nb] : m2;
+    const float Z = zl * __builtin_amdgcn_exp2f(ml - M) + zh * __builtin_amdgcn_exp2f(mh - M);
+    if (hf == 0) xch[wave][nb * 32 + (lane & 31)] = make_float2(M, Z);
+  }
+  __syncthreads();
+  for (int n = threadIdx.x; n < NB * 32; n += kThreads) {
+    float M = kNegInit;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, xch[w][n].x);
+    float Z = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) Z += xch[w][n].y * __builtin_amdgcn_exp2f(xch[w][n].x - M);
+    a.part[((int64_t)unit * a.n_chunks + chunk) * a.n_pad + n] = make_float2(M, Z);
+  }
+}
+
+// Chunks merged in ascending order: M_n, and the per-query weights of the column sums.
+__global__ void score_reduce_kernel(ScoreArgs a) {
+  const int unit = blockIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  const int nch = (T + kScoreChunk - 1) / kScoreChunk;
+  for (int n = threadIdx.x; n < a.n_pad; n += blockDim.x) {
+    const float2* p = a.part + (int64_t)unit * a.n_chunks * a.n_pad + n;
+    float M = kNegInit;
+    for (int c = 0; c < nch; ++c) M = fmaxf(M, p[(int64_t)c * a.n_pad].x);
+    double Z = 0.0;
+    for (int c = 0; c < nch; ++c) {
+      const float2 s = p[(int64_t)c * a.n_pad];
+      Z += (double)s.y * (double)__builtin_amdgcn_exp2f(s.x - M);
+    }
+    const bool real = n < a.d.N;
+    const bool newest = real && (n % a.d.W) == a.d.W - 1;
+    float4 f;
+    f.x = M;
+    f.y = real ? (float)(1.0 / ((double)a.d.N * Z)) : 0.f;
+    f.z = newest ? (float)(1.0 / ((double)a.d.G * Z)) : 0.f;
+    f.w = real ? 1.f : 0.f;
+    a.fin[(int64_t)unit * a.n_pad + n] = f;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Sweep 2: u[t] = sum_n exp2(x[n][t] - M_n) / (N Z_n), and g for the softmax- or moment-based scorers.
+// ---------------------------------------------------------------------------------------------
+template <bool BF16, int NB, int MODE>
+__global__ __launch_bounds__(kThreads) void score_usage_kernel(ScoreArgs a) {
+  extern __shared__ __align__(16) char qlds[];
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  const int c0 = chunk * kScoreChunk;
+  if (c0 >= T) return;
+  load_q<BF16, NB>(a, l, b, h, qlds);
+  __syncthreads();
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5, c = lane & 31;
+  float4 f[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) f[nb] = a.fin[(int64_t)unit * a.n_pad + nb * 32 + c];
+  float* u_row = a.u + (int64_t)unit * a.d.t_stride;
+  float* g_row = a.g ? a.g + (int64_t)unit * a.d.t_stride : nullptr;
+  const float inv_n = 1.f / (float)a.d.N;
+  uint4 av[Tr<BF16>::kAVecs];
+  floatx16 acc[NB];
+  for (int blk = 0; blk < kScoreChunk / 128; ++blk) {
+    const int t0 = c0 + (blk * 4 + wave) * 32;
+    if (t0 >= T) break;
+    load_a<BF16>(a, l, b, h, t0, T, lane, av);
+    tile_mma<BF16, NB>(av, qlds, lane, acc);
+    float pu[16], pg[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) pu[i] = pg[i] = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float e = __builtin_amdgcn_exp2f(acc[nb][i] * a.c2 - f[nb].x);
+        pu[i] += f[nb].y * e;
+        if (MODE == MODE_LAST) pg[i] += f[nb].z * e;
+        if (MODE == MODE_EXPECTED) pg[i] += acc[nb][i] * a.inv_sqrt_d;  // padded queries add exact zeros
+      }
+    const float ru = reduce16_over32(pu, c);
+    float rg = ru;
+    if (MODE == MODE_LAST) rg = reduce16_over32(pg, c);
+    if (MODE == MODE_EXPECTED) {
+      // mean and centred second moment of the N logits of each token
+      const float mean_mine = reduce16_over32(pg, c) * inv_n;
+      float pv[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float mean_i = __shfl(mean_mine, 2 * i + 32 * hf);
+        float s2 = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const float dlt = acc[nb][i] * a.inv_sqrt_d - mean_i;
+          s2 += f[nb].w * dlt * dlt;
+        }
+        pv[i] = s2;
+      }
+      rg = mean_mine + 0.5f * reduce16_over32(pv, c) * inv_n;
+    }
+    const int t = t0 + acc_row(c >> 1, hf);
+    if ((c & 1) == 0 && t < T) {
+      u_row[t] = ru;
+      if (g_row) g_row[t] = rg;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Key-diversity score: g[t] = -cos(k_t, kbar), kbar the mean key of the unit.
+// ---------------------------------------------------------------------------------------------
+template <bool BF16>
+__device__ __forceinline__ void widen8(const uint4& v, float (&x)[8], int& n) {
+  if constexpr (BF16) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = __uint_as_float(w[i] << 16);
+      x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+    n = 8;
+  } else {
+    x[0] = __uint_as_float(v.x);
+    x[1] = __uint_as_float(v.y);
+    x[2] = __uint_as_float(v.z);
+    x[3] = __uint_as_float(v.w);
+    n = 4;
+  }
+}
+
+// partial key sums per chunk: ksum[unit][chunk][D] (double)
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void keysum_kernel(ScoreArgs a, double* ksum) {
+  constexpr int CPR = Tr<BF16>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
+  __shared__ double sm[kThreads][EPC];
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  const int c0 = chunk * kScoreChunk;
+  if (c0 >= T) return;
+  const int col = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
+  double s[EPC];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) s[e] = 0.0;
+  for (int t = c0 + r0; t < min(T, c0 + kScoreChunk); t += RPI) {
+    const uint4 v = *(const uint4*)(kv_row(a.k, l, b, h, t) + col * 16);
+    float x[8];
+    int n;
+    widen8<BF16>(v, x, n);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) s[e] += (double)x[e];
+  }
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) sm[threadIdx.x][e] = s[e];
+  __syncthreads();
+  if (threadIdx.x < CPR) {
+    for (int e = 0; e < EPC; ++e) {
+      double t = 0.0;
+      for (int r = 0; r < RPI; ++r) t += sm[r * CPR + threadIdx.x][e];
+      ksum[((int64_t)unit * a.n_chunks + chunk) * a.d.D + threadIdx.x * EPC + e] = t;
+    }
+  }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const double* ksum) {
+  constexpr int CPR = Tr<BF16>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
+  __shared__ double kbar[128];
+  __shared__ double kbar_norm;
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  const int c0 = chunk * kScoreChunk;
+  if (c0 >= T) return;
+  const int nch = (T + kScoreChunk - 1) / kScoreChunk;
+  if (threadIdx.x < a.d.D) {
+    double t = 0.0;
+    for (int c = 0; c < nch; ++c) t += ksum[((int64_t)unit * a.n_chunks + c) * a.d.D + threadIdx.x];
+    kbar[threadIdx.x] = t / (double)T;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double n2 = 0.0;
+    for (int d = 0; d < a.d.D; ++d) n2 += kbar[d] * kbar[d];
+    kbar_norm = sqrt(n2);
+  }
+  __syncthreads();
+  const int col = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
+  float* g_row = a.g + (int64_t)unit * a.d.t_stride;
+  for (int tb = c0; tb < min(T, c0 + kScoreChunk); tb += RPI) {
+    const int t = tb + r0;
+    double dot = 0.0, nk = 0.0;
+    if (t < T) {
+      const uint4 v = *(const uint4*)(kv_row(a.k, l, b, h, t) + col * 16);
+      float x[8];
+      int n;
+      widen8<BF16>(v, x, n);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) {
+        dot += (double)x[e] * kbar[col * EPC + e];
+        nk += (double)x[e] * (double)x[e];
+      }
+    }
+    // the CPR lanes of a row are consecutive lanes of one wave
+#pragma unroll
+    for (int o = CPR / 2; o >= 1; o >>= 1) {
+      dot += __shfl_xor(dot, o);
+      nk += __shfl_xor(nk, o);
+    }
+    if (col == 0 && t < T) {
+      const double den = sqrt(nk) * kbar_norm;
+      g_row[t] = den > 0.0 ? (float)(-dot / den) : 0.f;
+    }
+  }
+}
+
+template <typename K>
+hipError_t set_lds(K kernel, int bytes) {
+  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+template <bool BF16, int NB>
+hipError_t run_softmax_sweeps(const ScoreArgs& a, int mode, hipStream_t s) {
+  const int lds = NB * 32 * Tr<BF16>::kQStride;
+  const dim3 grid(a.n_chunks, a.d.units), blk(kThreads);
+  hipError_t e;
+  if ((e = set_lds(score_stats_kernel<BF16, NB>, lds)) != hipSuccess) return e;
+  hipLaunchKernelGGL((score_stats_kernel<BF16, NB>), grid, blk, lds, s, a);
+  hipLaunchKernelGGL(score_reduce_kernel, dim3(a.d.units), dim3(256), 0, s, a);
+  switch (mode) {
+    case MODE_LAST:
+      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_LAST>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_LAST>), grid, blk, lds, s, a);
+      break;
+    case MODE_EXPECTED:
+      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_EXPECTED>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_EXPECTED>), grid, blk, lds, s, a);
+      break;
+    default:
+      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_MEAN>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_MEAN>), grid, blk, lds, s, a);
+  }
+  return hipGetLastError();
+}
+
+template <bool BF16>
+hipError_t run_by_nb(const ScoreArgs& a, int nb, int mode, hipStream_t s) {
+  if (nb <= 1) return run_softmax_sweeps<BF16, 1>(a, mode, s);
+  if (nb <= 2) return run_softmax_sweeps<BF16, 2>(a, mode, s);
+  if (nb <= 4) return run_softmax_sweeps<BF16, 4>(a, mode, s);
+  if constexpr (BF16) {
+    if (nb <= 7) return run_softmax_sweeps<BF16, 7>(a, mode, s);
+    if (nb <= 8) return run_softmax_sweeps<BF16, 8>(a, mode, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
+                        const void* q, float* u, float* g, char* ws, const WsLayout& wl, hipStream_t s) {
+  ScoreArgs a;
+  a.k = k;
+  a.d = d;
+  a.seq_lens = seq_lens;
+  a.q = (const char*)q;
+  a.part = (float2*)(ws + wl.part_stats);
+  a.fin = (float4*)(ws + wl.fin_stats);
+  a.u = u;
+  a.n_chunks = wl.n_chunks;
+  a.n_pad = wl.n_pad;
+  a.inv_sqrt_d = (float)(1.0 / sqrt((double)d.D));
+  a.c2 = (float)(1.4426950408889634 / sqrt((double)d.D));
+  const bool bf16 = p->kv_dtype == AMS_BF16;
+  int mode = MODE_MEAN;
+  a.g = nullptr;
+  if (p->scorer == AMS_SCORER_MEAN_WINDOW) a.g = (g != u) ? g : nullptr;
+  if (p->scorer == AMS_SCORER_LAST_QUERY) { mode = MODE_LAST; a.g = g; }
+  if (p->scorer == AMS_SCORER_EXPECTED) { mode = MODE_EXPECTED; a.g = g; }
+  const int nb = wl.n_pad / 32;
+  hipError_t e = bf16 ? run_by_nb<true>(a, nb, mode, s) : run_by_nb<false>(a, nb, mode, s);
+  if (e != hipSuccess) return e;
+  if (p->scorer == AMS_SCORER_KEYDIFF) {
+    a.g = g;
+    double* ksum = (double*)(ws + wl.kbar);
+    const dim3 grid(a.n_chunks, d.units), blk(kThreads);
+    if (bf16) {
+      hipLaunchKernelGGL(keysum_kernel<true>, grid, blk, 0, s, a, ksum);
+      hipLaunchKernelGGL(keydiff_kernel<true>, grid, blk, 0, s, a, (const double*)ksum);
+    } else {
+      hipLaunchKernelGGL(keysum_kernel<false>, grid, blk, 0, s, a, ksum);
+      hipLaunchKernelGGL(keydiff_kernel<false>, grid, blk, 0, s, a, (const double*)ksum);
+    }
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace ams

@@ -1,0 +1,235 @@
+// Segment quotas and in-segment top-k (Sec. 3.3 "Segment-wise Quota Allocation" and "In-Segment
+// Selection"; Alg. 1 steps 4-5, without a must-keep set).
+//
+// quota_kernel   one wave per unit; the arithmetic is a handful of double operations per segment
+//                and is done in index order so that it is reproducible bit for bit.
+// select_kernel  one workgroup per (segment, unit): radix select (4 x 8 bits, most significant
+//                digit first) of the quota-th largest score on an order-preserving integer image
+//                of the floats, then an ordered compaction that keeps everything above the
+//                threshold and the first few positions equal to it, ascending.
+#include "ams_internal.h"
+
+namespace ams {
+namespace {
+
+constexpr int kMaxSeg = 1024;
+
+__global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_lens, int S, int budget,
+                                                   int q_min, const int32_t* bounds_all,
+                                                   const float* seg_mass_all, int32_t* quota_all,
+                                                   int32_t* idx_all, int32_t* n_kept_all) {
+  __shared__ int32_t len[kMaxSeg], room[kMaxSeg], quo[kMaxSeg];
+  __shared__ double raw[kMaxSeg];
+  __shared__ uint8_t active[kMaxSeg];
+  const int unit = blockIdx.x;
+  int l, b, h;
+  unit_coords(d, unit, l, b, h);
+  const int T = seq_lens[b];
+  const int32_t* bounds = bounds_all + (int64_t)unit * (S + 1);
+  const float* mass = seg_mass_all + (int64_t)unit * S;
+  const int bud = min(budget, T);
+  if (threadIdx.x == 0) {
+    int nonempty = 0;
+    for (int i = 0; i < S; ++i) {
+      len[i] = bounds[i + 1] - bounds[i];
+      nonempty += len[i] > 0;
+    }
+    int floor_q = q_min;
+    long long need = 0;
+    for (int i = 0; i < S; ++i) need += min(floor_q, len[i]);
+    if (need > bud) floor_q = nonempty > 0 ? bud / nonempty : 0;
+    int rem = bud;
+    for (int i = 0; i < S; ++i) {
+      const int lo = min(floor_q, len[i]);
+      room[i] = len[i] - lo;
+      active[i] = room[i] > 0;
+      quo[i] = lo;
+      rem -= lo;
+      raw[i] = 0.0;
+    }
+    // proportional shares; a segment whose share reaches its room is filled and leaves the pool
+    for (;;) {
+      int n_active = 0;
+      double msum = 0.0;
+      for (int i = 0; i < S; ++i)
+        if (active[i]) {
+          ++n_active;
+          msum += (double)mass[i];
+        }
+      if (n_active == 0 || rem <= 0) break;
+      for (int i = 0; i < S; ++i)
+        if (active[i])
+          raw[i] = msum > 0.0 ? (double)rem * (double)mass[i] / msum : (double)rem / (double)n_active;
+      bool filled = false;
+      int taken = 0;
+      for (int i = 0; i < S; ++i)
+        if (active[i] && raw[i] >= (double)room[i]) {
+          quo[i] = len[i];
+          taken += room[i];
+          active[i] = 0;
+          filled = true;
+        }
+      rem -= taken;
+      if (!filled) break;
+    }
+    if (rem > 0) {
+      int given = 0;
+      for (int i = 0; i < S; ++i)
+        if (active[i]) {
+          const double fl = floor(raw[i]);
+          raw[i] -= fl;  // now the fractional part
+          quo[i] += (int)fl;
+          given += (int)fl;
+        }
+      int left = rem - given;
+      // one extra each, largest fractional part first, equal parts by lower segment index;
+      // a served segment is marked with a negative part
+      while (left > 0) {
+        int best = -1;
+        for (int i = 0; i < S; ++i)
+          if (active[i] && raw[i] >= 0.0 && quo[i] < len[i] && (best < 0 || raw[i] > raw[best])) best = i;
+        if (best < 0) {  // every segment served once: start another round
+          bool any = false;
+          for (int i = 0; i < S; ++i)
+            if (active[i] && raw[i] < 0.0) {
+              raw[i] = -raw[i] - 1.0;
+              any = any || quo[i] < len[i];
+            }
+          if (!any) break;
+          continue;
+        }
+        ++quo[best];
+        raw[best] = -raw[best] - 1.0;
+        --left;
+      }
+    }
+  }
+  __syncthreads();
+  int32_t* quota = quota_all + (int64_t)unit * S;
+  for (int i = threadIdx.x; i < S; i += 64) quota[i] = quo[i];
+  // entries of idx beyond the kept count are -1
+  int32_t* idx = idx_all + (int64_t)unit * budget;
+  for (int j = bud + threadIdx.x; j < budget; j += 64) idx[j] = -1;
+  if (threadIdx.x == 0) n_kept_all[unit] = bud;
+}
+
+// Order-preserving image of a score: larger float <-> larger unsigned; -0 and +0 coincide and
+// NaN ranks with -infinity.
+__device__ __forceinline__ uint32_t score_key(float x) {
+  if (x != x) x = -INFINITY;
+  if (x == 0.f) x = 0.f;
+  const uint32_t b = __float_as_uint(x);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+constexpr int kSelBlock = 512;
+constexpr int kSelWaves = kSelBlock / 64;
+
+__global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int budget, const float* g_all,
+                                                           const int32_t* bounds_all,
+                                                           const int32_t* quota_all, int32_t* idx_all) {
+  __shared__ int hist[256];
+  __shared__ uint32_t sel_prefix;
+  __shared__ int sel_rem;
+  __shared__ int2 wave_cnt[kSelWaves];
+  const int unit = blockIdx.y, seg = blockIdx.x;
+  const int32_t* bounds = bounds_all + (int64_t)unit * (S + 1);
+  const int32_t* quota = quota_all + (int64_t)unit * S;
+  const int a = bounds[seg], b = bounds[seg + 1], q = quota[seg];
+  if (q <= 0) return;
+  int out0 = 0;
+  for (int i = 0; i < seg; ++i) out0 += quota[i];
+  const float* g = g_all + (int64_t)unit * d.t_stride;
+  int32_t* out = idx_all + (int64_t)unit * budget + out0;
+  const int L = b - a;
+  if (q >= L) {  // whole segment kept
+    for (int j = threadIdx.x; j < L; j += kSelBlock) out[j] = a + j;
+    return;
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  // radix select of the q-th largest key
+  uint32_t prefix = 0, mask = 0;
+  int rem = q;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int i = threadIdx.x; i < 256; i += kSelBlock) hist[i] = 0;
+    __syncthreads();
+    for (int t = a + threadIdx.x; t < b; t += kSelBlock) {
+      const uint32_t k = score_key(g[t]);
+      if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+    }
+    __syncthreads();
+    if (wave == 0) {
+      int hb[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) hb[i] = hist[lane * 4 + i];
+      const int s = hb[0] + hb[1] + hb[2] + hb[3];
+      int incl = s;  // sum over lanes >= this one
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_down(incl, o);
+        if (lane + o < 64) incl += v;
+      }
+      int cum = incl - s;  // keys in bins above this lane's
+#pragma unroll
+      for (int i = 3; i >= 0; --i) {
+        if (cum < rem && rem <= cum + hb[i]) {
+          sel_prefix = prefix | ((uint32_t)(lane * 4 + i) << shift);
+          sel_rem = rem - cum;
+        }
+        cum += hb[i];
+      }
+    }
+    __syncthreads();
+    prefix = sel_prefix;
+    rem = sel_rem;
+    mask |= 0xFFu << shift;
+    __syncthreads();
+  }
+  // prefix = key of the q-th largest score; rem = how many of the keys equal to it are kept
+  const uint32_t thr = prefix;
+  int base_gt = 0, base_eq = 0;  // counts over the positions before the current tile
+  for (int t0 = a; t0 < b; t0 += kSelBlock) {
+    const int t = t0 + threadIdx.x;
+    uint32_t k = 0;
+    const bool in = t < b;
+    if (in) k = score_key(g[t]);
+    const bool gt = in && k > thr, eq = in && k == thr;
+    const uint64_t bgt = __ballot(gt), beq = __ballot(eq);
+    const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    if (lane == 0) wave_cnt[wave] = make_int2(__popcll(bgt), __popcll(beq));
+    __syncthreads();
+    int n_gt = base_gt + __popcll(bgt & below), n_eq = base_eq + __popcll(beq & below);
+    int tot_gt = 0, tot_eq = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) {
+      const int2 c = wave_cnt[w];
+      if (w < wave) {
+        n_gt += c.x;
+        n_eq += c.y;
+      }
+      tot_gt += c.x;
+      tot_eq += c.y;
+    }
+    if (gt || (eq && n_eq < rem)) out[n_gt + min(n_eq, rem)] = t;
+    base_gt += tot_gt;
+    base_eq += tot_eq;
+    __syncthreads();
+  }
+}
+
+}  // namespace
+
+hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* g,
+                         const int32_t* bounds, const float* seg_mass, int32_t* quota, int32_t* idx,
+                         int32_t* n_kept, hipStream_t s) {
+  const int S = p->n_segments;
+  if (S > kMaxSeg) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(quota_kernel, dim3(d.units), dim3(64), 0, s, d, seq_lens, S, p->budget, p->q_min,
+                     bounds, seg_mass, quota, idx, n_kept);
+  hipLaunchKernelGGL(select_kernel, dim3(S, d.units), dim3(kSelBlock), 0, s, d, S, p->budget, g, bounds,
+                     quota, idx);
+  return hipGetLastError();
+}
+
+}  // namespace ams

@@ -1,0 +1,271 @@
+"""Stage-wise parity of the HIP library against the CPU oracle, through the C ABI.
+
+Every stage is fed the same inputs as the oracle.  Float outputs: relative 1e-5 (absolute floor
+1e-12); signed scores that pass through zero: 1e-5 of the vector's largest magnitude.  Integer
+outputs, indices and gathered bytes: exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_23200_amd import binding as B
+from paper_2605_23200_amd import inputs
+from gpu_util import (DEV, assert_close_norm, assert_close_rel, params_for, to_dev, to_host, unit_list,
+                      workspace)
+
+pytestmark = pytest.mark.gpu
+
+SCORERS = {"last": B.SCORER_LAST_QUERY, "mean": B.SCORER_MEAN_WINDOW, "keydiff": B.SCORER_KEYDIFF,
+           "expected": B.SCORER_EXPECTED}
+
+
+def _workload(dtype, G, W, T, **kw):
+    return inputs.CONFIGS[0].scaled(dtype=dtype, G=G, W=W, T=T, H=2, L=1, n_spans=4, span_len=(16, 200),
+                                    budget=min(512, T), **kw)
+
+
+@pytest.mark.parametrize("dtype,G,W,T", [("f32", 1, 8, 4096), ("f32", 2, 20, 2500), ("bf16", 4, 32, 5000),
+                                          ("bf16", 7, 32, 2085), ("bf16", 3, 5, 1), ("bf16", 8, 32, 1300),
+                                          ("f32", 4, 32, 777)])
+@pytest.mark.parametrize("scorer", list(SCORERS))
+def test_score_parity(oracle, dtype, G, W, T, scorer):
+    w = _workload(dtype, G, W, T)
+    host = inputs.dense_cache(w, n_threads=4)
+    p = params_for(w, scorer=SCORERS[scorer])
+    ws = workspace(p)
+    K, Q = to_dev(host["K"]), to_dev(host["Q"])
+    lens = to_dev(host["seq_lens"])
+    u = torch.full((p.units, w.T), -7.0, device=DEV)
+    g = torch.full((p.units, w.T), -7.0, device=DEV)
+    B.ams_score(p, B.dense_view(K, None), lens, Q, u, g, ws)
+    torch.cuda.synchronize()
+    u_h, g_h = to_host(u), to_host(g)
+    for i, (l, b, h) in enumerate(unit_list(w)):
+        uo, go = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), host["K"][l, b, h, :T],
+                              w.G, w.W, SCORERS[scorer])
+        assert_close_rel(u_h[i], uo, what=f"u unit {i}")
+        if scorer in ("mean", "last"):
+            assert_close_rel(g_h[i], go, what=f"g unit {i}")
+        else:
+            assert_close_norm(g_h[i], go, what=f"g unit {i}")
+
+
+def test_score_ragged_batch_paged(oracle):
+    # ragged batch in a paged layout: lengths that are not multiples of 16 or 32, permuted blocks
+    w = inputs.CONFIGS[2].scaled(L=2, B=3, H=2, T=1500, T_min=300, n_spans=3, span_len=(16, 64), budget=128)
+    host = inputs.dense_cache(w, n_threads=4)
+    lens = host["seq_lens"]
+    src, dst, n_slots = inputs.block_tables(w, lens, w.budget)
+    Kp = inputs.paged_pool_from_dense(w, host["K"], lens, src, n_slots)
+    p = params_for(w, t_max=int(lens.max()))              # the block tables cover max(lens) positions
+    ws = workspace(p)
+    u = torch.zeros((p.units, w.T), device=DEV)
+    Kp_d, src_d, lens_d, Q_d = to_dev(Kp), to_dev(src), to_dev(lens), to_dev(host["Q"])
+    B.ams_score(p, B.paged_view(Kp_d, None, src_d), lens_d, Q_d, u, u, ws)
+    torch.cuda.synchronize()
+    u_h = to_host(u)
+    for i, (l, b, h) in enumerate(unit_list(w)):
+        T = int(lens[b])
+        uo, _ = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), host["K"][l, b, h, :T],
+                             w.G, w.W)
+        assert_close_rel(u_h[i, :T], uo, what=f"u unit {i}")
+        assert (u_h[i, T:] == 0).all()                     # nothing written beyond the sequence
+
+
+def _vec_params(units, T, S=8, budget=64, lam=0.9, beta=0.9, eps=1e-6, t_stride=None, B_=1):
+    return B.make_params(n_layers=1, batch=B_, n_kv_heads=units // B_, group=1, window=8, t_max=T,
+                         t_stride=t_stride or T, budget=budget, n_segments=S, ema_lambda=lam, ema_beta=beta,
+                         mass_eps=eps)
+
+
+@pytest.mark.parametrize("T", [1, 63, 4096, 10000, 70001])
+@pytest.mark.parametrize("lam,beta", [(0.9, 0.9), (0.0, 0.5), (0.5, 1.0), (0.95, 0.0)])
+def test_ema_parity(oracle, T, lam, beta):
+    rng = np.random.default_rng(T)
+    units = 3
+    u = (rng.standard_normal((units, T)) ** 3).astype(np.float32) / T
+    credit = (rng.random((units, T)) / T).astype(np.float32)
+    credit[1] = 0
+    p = _vec_params(units, T, lam=lam, beta=beta, t_stride=T + 5)
+    pad = lambda a: np.pad(a, ((0, 0), (0, 5)), constant_values=9.0)
+    u_d, c_d = to_dev(pad(u)), to_dev(pad(credit))
+    m_d = torch.full((units, T + 5), 9.0, device=DEV)
+    B.ams_ema_update(p, to_dev(np.array([T], np.int32)), u_d, c_d, m_d)
+    torch.cuda.synchronize()
+    for i in range(units):
+        m_used, c_new = oracle.ema(oracle.mass(u[i], 1e-6), credit[i], lam, beta)
+        assert_close_rel(to_host(m_d)[i, :T], m_used, what="m_used")
+        assert_close_rel(to_host(c_d)[i, :T], c_new, what="credit")
+    assert (to_host(m_d)[:, T:] == 9.0).all() and (to_host(c_d)[:, T:] == 9.0).all()
+
+
+def _segment(m, S, T):
+    units = m.shape[0]
+    p = _vec_params(units, T, S=S)
+    bounds = torch.zeros((units, S + 1), dtype=torch.int32, device=DEV)
+    seg_mass = torch.zeros((units, S), device=DEV)
+    B.ams_mass_segment(p, to_dev(np.array([T], np.int32)), to_dev(m), bounds, seg_mass)
+    torch.cuda.synchronize()
+    return to_host(bounds), to_host(seg_mass)
+
+
+@pytest.mark.parametrize("T,S", [(4096, 8), (10000, 16), (70001, 64), (5, 8), (1, 1), (4097, 1), (33000, 1000)])
+def test_segment_parity_random(oracle, T, S):
+    rng = np.random.default_rng(T + S)
+    m = np.stack([oracle.mass((rng.random(T) ** 6).astype(np.float32)) for _ in range(3)])
+    bounds, seg_mass = _segment(m, S, T)
+    for i in range(3):
+        bo, so = oracle.segment(m[i], S)
+        np.testing.assert_array_equal(bounds[i], bo)
+        assert_close_rel(seg_mass[i], so, what="seg_mass")
+
+
+def test_segment_exact_cases(oracle):
+    T, S = 4096, 8
+    m = np.stack([np.full(T, 1 / T, np.float32),                      # thresholds hit exactly
+                  np.where(np.arange(T) == 1234, 1.0, 1e-9).astype(np.float32),   # one spike: boundaries collapse
+                  np.full(T, 0.5 / T, np.float32)])                   # total mass 0.5: upper thresholds never reached
+    bounds, seg_mass = _segment(m, S, T)
+    for i in range(3):
+        bo, so = oracle.segment(m[i], S)
+        np.testing.assert_array_equal(bounds[i], bo)
+        assert_close_rel(seg_mass[i], so, what="seg_mass")
+    np.testing.assert_array_equal(bounds[0], np.arange(9) * 512)
+
+
+def _select(g, bounds, seg_mass, budget, T, q_min=1):
+    units, S = seg_mass.shape
+    p = _vec_params(units, T, S=S, budget=budget)
+    p.q_min = q_min
+    quota = torch.zeros((units, S), dtype=torch.int32, device=DEV)
+    idx = torch.full((units, budget), -5, dtype=torch.int32, device=DEV)
+    n_kept = torch.zeros(units, dtype=torch.int32, device=DEV)
+    B.ams_select(p, to_dev(np.array([T], np.int32)), to_dev(g), to_dev(bounds), to_dev(seg_mass), quota, idx,
+                 n_kept)
+    torch.cuda.synchronize()
+    return to_host(quota), to_host(idx), to_host(n_kept)
+
+
+@pytest.mark.parametrize("T,S,budget", [(4096, 8, 1024), (10000, 16, 2048), (70001, 64, 4096), (300, 8, 512),
+                                        (5000, 1, 700), (2000, 100, 150), (2000, 100, 60), (40000, 4, 1)])
+def test_select_parity(oracle, T, S, budget):
+    rng = np.random.default_rng(T * 7 + S)
+    units = 4
+    g = rng.standard_normal((units, T)).astype(np.float32)
+    g[1] = np.round(g[1] * 2) / 2            # heavy ties
+    g[2] = 0.25                               # all equal: pure tie-break
+    g[3, ::7] = -0.0
+    g[3, 3::7] = 0.0
+    g[3, 5::11] = np.nan
+    g[3, 6::13] = -np.inf
+    m = np.stack([oracle.mass((rng.random(T) ** 8).astype(np.float32)) for _ in range(units)])
+    segs = [oracle.segment(m[i], S) for i in range(units)]
+    bounds = np.stack([s[0] for s in segs])
+    seg_mass = np.stack([s[1] for s in segs])
+    quota, idx, n_kept = _select(g, bounds, seg_mass, budget, T)
+    for i in range(units):
+        qo = oracle.quota(bounds[i], seg_mass[i], budget, 1)
+        np.testing.assert_array_equal(quota[i], qo)
+        io = oracle.select(g[i], bounds[i], qo)
+        assert n_kept[i] == len(io) == min(budget, T)
+        np.testing.assert_array_equal(idx[i, :len(io)], io)
+        assert (idx[i, len(io):] == -1).all()
+
+
+def test_select_single_segment_is_global_topk():
+    T, k = 30000, 2048
+    g = np.random.default_rng(0).standard_normal((2, T)).astype(np.float32)
+    g[1] = np.round(g[1], 1)
+    bounds = np.tile(np.array([0, T], np.int32), (2, 1))
+    quota, idx, n_kept = _select(g, bounds, np.ones((2, 1), np.float32), k, T)
+    for i in range(2):
+        order = np.argsort(-g[i].astype(np.float64), kind="stable")
+        np.testing.assert_array_equal(idx[i], np.sort(order[:k]))
+
+
+def test_quota_adversarial(oracle):
+    # masses with exact ties, empty segments, caps that bind, budgets below the number of segments
+    rng = np.random.default_rng(3)
+    S, units = 16, 64
+    bounds = np.zeros((units, S + 1), np.int32)
+    mass = np.zeros((units, S), np.float32)
+    for i in range(units):
+        lens = rng.integers(0, 40, size=S)
+        lens[rng.integers(0, S)] += 5
+        bounds[i, 1:] = np.cumsum(lens)
+        mass[i] = (rng.integers(0, 5, size=S) / 8).astype(np.float32)
+        mass[i][lens == 0] = 0
+    T = int(bounds[:, -1].max())
+    for budget in (3, 17, 200, 100000):
+        for i in range(units):
+            Ti = int(bounds[i, -1])
+            p = _vec_params(1, Ti, S=S, budget=budget)
+            quota = torch.zeros((1, S), dtype=torch.int32, device=DEV)
+            idx = torch.zeros((1, budget), dtype=torch.int32, device=DEV) if budget < 1000 else \
+                torch.zeros((1, budget), dtype=torch.int32, device=DEV)
+            n_kept = torch.zeros(1, dtype=torch.int32, device=DEV)
+            B.ams_select(p, to_dev(np.array([Ti], np.int32)), torch.zeros((1, Ti), device=DEV),
+                         to_dev(bounds[i:i + 1]), to_dev(mass[i:i + 1]), quota, idx, n_kept)
+            np.testing.assert_array_equal(to_host(quota)[0], oracle.quota(bounds[i], mass[i], budget, 1))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_compact_dense(oracle, dtype):
+    w = inputs.CONFIGS[0].scaled(dtype=dtype, L=2, B=2, H=3, T=900, budget=200, n_spans=0)
+    host = inputs.dense_cache(w, n_threads=4)
+    rng = np.random.default_rng(1)
+    units = w.units
+    idx = np.full((units, w.budget), -1, np.int32)
+    n_kept = rng.integers(1, w.budget + 1, size=units).astype(np.int32)
+    n_kept[0] = w.budget
+    for i in range(units):
+        idx[i, :n_kept[i]] = np.sort(rng.choice(w.T, size=n_kept[i], replace=False))
+    credit = rng.random((units, w.T)).astype(np.float32)
+    p = params_for(w)
+    K, V = to_dev(host["K"]), to_dev(host["V"])
+    Kd = torch.zeros((w.L, w.B, w.H, w.budget, w.D), dtype=K.dtype, device=DEV)
+    Vd = torch.zeros_like(Kd)
+    cd = torch.zeros((units, w.budget), device=DEV)
+    B.ams_compact(p, B.dense_view(K, V), to_dev(idx), to_dev(n_kept), B.dense_view(Kd, Vd), to_dev(credit), cd)
+    torch.cuda.synchronize()
+    Kd_h = to_host(Kd, host["K"].dtype).reshape(units, w.budget, w.D)
+    Vd_h = to_host(Vd, host["V"].dtype).reshape(units, w.budget, w.D)
+    for i, (l, b, h) in enumerate(unit_list(w)):
+        n = n_kept[i]
+        Ko, Vo, co = oracle.compact(host["K"][l, b, h], host["V"][l, b, h], credit[i], idx[i, :n])
+        np.testing.assert_array_equal(Kd_h[i, :n], Ko)
+        np.testing.assert_array_equal(Vd_h[i, :n], Vo)
+        np.testing.assert_array_equal(to_host(cd)[i, :n], co)
+        assert not Kd_h[i, n:].any() and not Vd_h[i, n:].any()
+
+
+def test_compact_paged(oracle):
+    w = inputs.CONFIGS[2].scaled(L=2, B=4, H=2, T=700, T_min=100, n_spans=0, budget=100)
+    host = inputs.dense_cache(w, n_threads=4)
+    lens = host["seq_lens"]
+    src, dst, n_slots = inputs.block_tables(w, lens, w.budget)
+    Kp = inputs.paged_pool_from_dense(w, host["K"], lens, src, n_slots)
+    Vp = inputs.paged_pool_from_dense(w, host["V"], lens, src, n_slots)
+    rng = np.random.default_rng(2)
+    units = w.units
+    idx = np.full((units, w.budget), -1, np.int32)
+    n_kept = np.zeros(units, np.int32)
+    for i, (l, b, h) in enumerate(unit_list(w)):
+        n_kept[i] = min(w.budget, int(lens[b]))
+        idx[i, :n_kept[i]] = np.sort(rng.choice(int(lens[b]), size=n_kept[i], replace=False))
+    p = params_for(w, t_max=int(lens.max()))
+    Kp_d, Vp_d = to_dev(Kp), to_dev(Vp)
+    Kq_d, Vq_d = torch.zeros_like(Kp_d), torch.zeros_like(Vp_d)
+    src_d, dst_d, idx_d, nk_d = to_dev(src), to_dev(dst), to_dev(idx), to_dev(n_kept)
+    B.ams_compact(p, B.paged_view(Kp_d, Vp_d, src_d), idx_d, nk_d, B.paged_view(Kq_d, Vq_d, dst_d))
+    torch.cuda.synchronize()
+    Ko, Vo = np.zeros_like(Kp), np.zeros_like(Vp)
+    for i, (l, b, h) in enumerate(unit_list(w)):
+        oracle.compact_paged(Kp[l], Vp[l], src[b], Ko[l], Vo[l], dst[b], w.block, h, idx[i, :n_kept[i]])
+    np.testing.assert_array_equal(to_host(Kq_d, np.uint16), Ko)
+    np.testing.assert_array_equal(to_host(Vq_d, np.uint16), Vo)
+    # and the paged result is the dense gather, row for row
+    for i, (l, b, h) in enumerate(unit_list(w)):
+        j = np.arange(n_kept[i])
+        slots = dst[b, j // 16].astype(np.int64) * 16 + j % 16
+        np.testing.assert_array_equal(to_host(Kq_d, np.uint16)[l, slots, h], host["K"][l, b, h, idx[i, :n_kept[i]]])
