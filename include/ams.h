@@ -107,6 +107,20 @@ typedef struct {
 int ams_workspace_layout(const ams_params* p, ams_workspace_view* out);
 
 /*
+ * Per-kernel timing for benchmarks (no citation: measurement aid, not part of
+ * the method).  Between ams_profile_begin() and ams_profile_end() every kernel
+ * the library launches is preceded by a HIP event on its stream.
+ * ams_profile_end() records a final event on `stream`, WAITS for it (the only
+ * call of this library that blocks the host), and writes up to max_entries
+ * (label, milliseconds) pairs in launch order: the time from one kernel's
+ * start marker to the next marker.  labels[i] points to a static string.
+ * Returns the number of pairs written, or a negative ams_status.  Collection
+ * is process-wide and not thread-safe; at most 4096 markers are kept.
+ */
+int ams_profile_begin(void);
+int ams_profile_end(void* stream, int max_entries, const char** labels, float* ms);
+
+/*
  * ams_score - usage u and base score g (Alg. 1 step 1; Sec. 3.2; Sec. 3.3).
  *   s[n][t] = q_n . k_t / sqrt(D) over the N = G*W recent queries of the unit,
  *   p = softmax over t, u[t] = mean_n p[n][t]; g per p->scorer (g may equal u

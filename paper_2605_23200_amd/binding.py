@@ -22,7 +22,8 @@ F32, BF16 = 0, 1
 SCORER_LAST_QUERY, SCORER_MEAN_WINDOW, SCORER_KEYDIFF, SCORER_EXPECTED, SCORER_EXTERNAL = 0, 1, 2, 3, 4
 LAYOUT_DENSE, LAYOUT_PAGED = 0, 1
 
-EXPORTS = ("ams_status_string", "ams_workspace_bytes", "ams_workspace_layout", "ams_score",
+EXPORTS = ("ams_status_string", "ams_workspace_bytes", "ams_workspace_layout", "ams_profile_begin",
+           "ams_profile_end", "ams_score",
            "ams_ema_update", "ams_mass_segment", "ams_select", "ams_compact", "ams_compress_step")
 
 
@@ -79,9 +80,9 @@ def lib() -> C.CDLL:
         l.ams_select.argtypes = [P, p, p, p, p, p, p, p, p, C.c_size_t, p]
         l.ams_compact.argtypes = [P, V, p, p, V, p, p, p]
         l.ams_compress_step.argtypes = [P, V, p, p, p, V, p, p, p, p, C.c_size_t, p]
-        for name in EXPORTS[3:]:
+        l.ams_profile_end.argtypes = [p, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_float)]
+        for name in EXPORTS[2:]:
             getattr(l, name).restype = C.c_int
-        l.ams_workspace_layout.restype = C.c_int
         _lib = l
     return _lib
 
@@ -141,6 +142,20 @@ def ams_workspace_layout(p: Params) -> WorkspaceView:
     out = WorkspaceView()
     _check(lib().ams_workspace_layout(C.byref(p), C.byref(out)), "ams_workspace_layout")
     return out
+
+
+def ams_profile_begin():
+    _check(lib().ams_profile_begin(), "ams_profile_begin")
+
+
+def ams_profile_end(stream=None, max_entries: int = 4096):
+    """Returns [(kernel label, milliseconds), ...] in launch order; waits for the stream."""
+    labels = (C.c_char_p * max_entries)()
+    ms = (C.c_float * max_entries)()
+    n = lib().ams_profile_end(_stream(stream), max_entries, labels, ms)
+    if n < 0:
+        raise AmsError(-n, "ams_profile_end")
+    return [(labels[i].decode(), float(ms[i])) for i in range(n)]
 
 
 def ams_score(p, src, seq_lens, q, u, g, ws, stream=None):

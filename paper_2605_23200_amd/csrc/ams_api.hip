@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/ams.h: argument checks, workspace carving and the
 // order of the launches.  Nothing here touches device memory or waits for the stream.
 #include <math.h>
+#include <string.h>
 
 #include "ams_internal.h"
 
@@ -106,7 +107,34 @@ static KvDev make_kv(const ams_params* p, const ams_kv_view* v, void* base) {
   return k;
 }
 
-static int hip_status(hipError_t e) { return e == hipSuccess ? AMS_OK : AMS_ERR_HIP; }
+
+// ---- per-kernel timing (host-side bookkeeping of HIP events; no device memory) ----
+namespace {
+constexpr int kMaxMarks = 4096;
+struct Profiler {
+  bool on = false;
+  int n = 0;
+  hipEvent_t ev[kMaxMarks];
+  const char* label[kMaxMarks];
+  int created = 0;
+} g_prof;
+}  // namespace
+
+void prof_mark(const char* label, hipStream_t s);
+static int hip_status(hipError_t e, hipStream_t s) {
+  prof_mark("end", s);  // closes the interval of the call's last kernel
+  return e == hipSuccess ? AMS_OK : AMS_ERR_HIP;
+}
+
+void prof_mark(const char* label, hipStream_t s) {
+  if (!g_prof.on || g_prof.n >= kMaxMarks) return;
+  if (g_prof.n >= g_prof.created) {
+    if (hipEventCreate(&g_prof.ev[g_prof.created]) != hipSuccess) return;
+    ++g_prof.created;
+  }
+  if (hipEventRecord(g_prof.ev[g_prof.n], s) != hipSuccess) return;
+  g_prof.label[g_prof.n++] = label;
+}
 
 }  // namespace ams
 
@@ -128,6 +156,30 @@ const char* ams_status_string(int status) {
 size_t ams_workspace_bytes(const ams_params* p) {
   if (check_params(p) != AMS_OK) return 0;
   return ws_layout(p).total;
+}
+
+int ams_profile_begin(void) {
+  g_prof.n = 0;
+  g_prof.on = true;
+  return AMS_OK;
+}
+
+int ams_profile_end(void* stream, int max_entries, const char** labels, float* ms) {
+  if (!g_prof.on) return 0;
+  prof_mark("end", (hipStream_t)stream);
+  g_prof.on = false;
+  if (g_prof.n < 2) return 0;
+  if (hipEventSynchronize(g_prof.ev[g_prof.n - 1]) != hipSuccess) return -AMS_ERR_HIP;
+  int out = 0;
+  for (int i = 0; i + 1 < g_prof.n && out < max_entries; ++i) {
+    if (!strcmp(g_prof.label[i], "end")) continue;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, g_prof.ev[i], g_prof.ev[i + 1]) != hipSuccess) return -AMS_ERR_HIP;
+    if (labels) labels[out] = g_prof.label[i];
+    if (ms) ms[out] = t;
+    ++out;
+  }
+  return out;
 }
 
 int ams_workspace_layout(const ams_params* p, ams_workspace_view* out) {
@@ -156,7 +208,7 @@ int ams_score(const ams_params* p, const ams_kv_view* src, const int32_t* seq_le
   const WsLayout wl = ws_layout(p);
   if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
   return hip_status(launch_score(p, make_dims(p), make_kv(p, src, src->k), seq_lens, q, u, g, (char*)ws,
-                                 wl, (hipStream_t)stream));
+                                 wl, (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u, float* credit,
@@ -166,7 +218,7 @@ int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u,
   const int rc = check_params(p);
   if (rc) return rc;
   if (!seq_lens || !u || !credit || !m_used) return AMS_ERR_INVALID_ARG;
-  return hip_status(launch_ema(p, make_dims(p), seq_lens, u, credit, m_used, (hipStream_t)stream));
+  return hip_status(launch_ema(p, make_dims(p), seq_lens, u, credit, m_used, (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* m_used,
@@ -176,7 +228,7 @@ int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* 
   const int rc = check_params(p);
   if (rc) return rc;
   if (!seq_lens || !m_used || !bounds || !seg_mass) return AMS_ERR_INVALID_ARG;
-  return hip_status(launch_segment(p, make_dims(p), seq_lens, m_used, bounds, seg_mass, (hipStream_t)stream));
+  return hip_status(launch_segment(p, make_dims(p), seq_lens, m_used, bounds, seg_mass, (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_select(const ams_params* p, const int32_t* seq_lens, const float* g, const int32_t* bounds,
@@ -188,7 +240,7 @@ int ams_select(const ams_params* p, const int32_t* seq_lens, const float* g, con
   if (rc) return rc;
   if (!seq_lens || !g || !bounds || !seg_mass || !quota || !idx || !n_kept) return AMS_ERR_INVALID_ARG;
   return hip_status(launch_select(p, make_dims(p), seq_lens, g, bounds, seg_mass, quota, idx, n_kept,
-                                  (hipStream_t)stream));
+                                  (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_compact(const ams_params* p, const ams_kv_view* src, const int32_t* idx, const int32_t* n_kept,
@@ -199,10 +251,12 @@ int ams_compact(const ams_params* p, const ams_kv_view* src, const int32_t* idx,
   if ((rc = check_view(p, src, p->t_max, true))) return rc;
   if ((rc = check_view(p, dst, keep, true))) return rc;
   if (!idx || !n_kept) return AMS_ERR_INVALID_ARG;
-  if (src->k == dst->k || src->v == dst->v) return AMS_ERR_INVALID_ARG;
+  if (src->layout == AMS_LAYOUT_DENSE && dst->layout == AMS_LAYOUT_DENSE &&
+      (src->k == dst->k || src->v == dst->v))
+    return AMS_ERR_INVALID_ARG;  // out of place only; paged views may share a pool (other blocks)
   return hip_status(launch_compact(p, make_dims(p), make_kv(p, src, src->k), make_kv(p, src, src->v),
                                    make_kv(p, dst, dst->k), make_kv(p, dst, dst->v), idx, n_kept,
-                                   credit_src, credit_dst, (hipStream_t)stream));
+                                   credit_src, credit_dst, (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t* seq_lens,
@@ -215,7 +269,9 @@ int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t
   if ((rc = check_view(p, src, p->t_max, true))) return rc;
   if ((rc = check_view(p, dst, keep, true))) return rc;
   if (!seq_lens || !q || !credit || !idx || !n_kept || !ws) return AMS_ERR_INVALID_ARG;
-  if (src->k == dst->k || src->v == dst->v) return AMS_ERR_INVALID_ARG;
+  if (src->layout == AMS_LAYOUT_DENSE && dst->layout == AMS_LAYOUT_DENSE &&
+      (src->k == dst->k || src->v == dst->v))
+    return AMS_ERR_INVALID_ARG;  // out of place only; paged views may share a pool (other blocks)
   const WsLayout wl = ws_layout(p);
   if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
   char* w = (char*)ws;
@@ -237,6 +293,7 @@ int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t
   if ((e = launch_compact(p, d, make_kv(p, src, src->k), make_kv(p, src, src->v), make_kv(p, dst, dst->k),
                           make_kv(p, dst, dst->v), idx, n_kept, credit, credit_dst, s)) != hipSuccess)
     return AMS_ERR_HIP;
+  prof_mark("end", s);
   return AMS_OK;
 }
 

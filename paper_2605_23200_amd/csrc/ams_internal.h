@@ -56,6 +56,10 @@ struct WsLayout {
 };
 WsLayout ws_layout(const ams_params* p);
 
+// Optional per-kernel timing: when collection is on, every launcher calls prof_mark(label, stream)
+// right before a kernel launch, which records a HIP event on that stream.  Off: a single branch.
+void prof_mark(const char* label, hipStream_t s);
+
 // ---- launchers (each returns hipGetLastError() of its launches) ----
 hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
                         const void* q, float* u, float* g, char* ws, const WsLayout& wl, hipStream_t s);

@@ -46,6 +46,7 @@ hipError_t launch_compact(const ams_params* p, const Dims& d, const KvDev& ks, c
                           const float* credit_src, float* credit_dst, hipStream_t s) {
   const int max_keep = p->budget < d.t_max ? p->budget : d.t_max;
   const dim3 grid((max_keep + kRowsPerBlock - 1) / kRowsPerBlock, d.units);
+  prof_mark("compact", s);
   hipLaunchKernelGGL(compact_kernel, grid, dim3(kBlock), 0, s, d, ks, vs, kd, vd, p->budget, idx, n_kept,
                      credit_src, credit_dst);
   return hipGetLastError();

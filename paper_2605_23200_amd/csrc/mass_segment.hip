@@ -172,6 +172,7 @@ __global__ __launch_bounds__(kBlock) void segment_kernel(Dims d, const int32_t* 
 
 hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
                       float* credit, float* m_used, hipStream_t s) {
+  prof_mark("ema", s);
   hipLaunchKernelGGL(ema_kernel, dim3(d.units), dim3(kBlock), 0, s, d, seq_lens, u, credit, m_used,
                      p->ema_lambda, p->ema_beta, p->mass_eps);
   return hipGetLastError();
@@ -180,6 +181,7 @@ hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_len
 hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq_lens,
                           const float* m_used, int32_t* bounds, float* seg_mass, hipStream_t s) {
   if (p->n_segments > kMaxSeg) return hipErrorInvalidValue;
+  prof_mark("segment", s);
   hipLaunchKernelGGL(segment_kernel, dim3(d.units), dim3(kBlock), 0, s, d, seq_lens, m_used,
                      p->n_segments, bounds, seg_mass);
   return hipGetLastError();

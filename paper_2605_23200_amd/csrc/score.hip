@@ -427,8 +427,11 @@ hipError_t run_softmax_sweeps(const ScoreArgs& a, int mode, hipStream_t s) {
   const dim3 grid(a.n_chunks, a.d.units), blk(kThreads);
   hipError_t e;
   if ((e = set_lds(score_stats_kernel<BF16, NB>, lds)) != hipSuccess) return e;
+  prof_mark("score_stats", s);
   hipLaunchKernelGGL((score_stats_kernel<BF16, NB>), grid, blk, lds, s, a);
+  prof_mark("score_reduce", s);
   hipLaunchKernelGGL(score_reduce_kernel, dim3(a.d.units), dim3(256), 0, s, a);
+  prof_mark("score_usage", s);
   switch (mode) {
     case MODE_LAST:
       if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_LAST>, lds)) != hipSuccess) return e;
@@ -486,11 +489,14 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
     a.g = g;
     double* ksum = (double*)(ws + wl.kbar);
     const dim3 grid(a.n_chunks, d.units), blk(kThreads);
+    prof_mark("keysum", s);
     if (bf16) {
       hipLaunchKernelGGL(keysum_kernel<true>, grid, blk, 0, s, a, ksum);
+      prof_mark("keydiff", s);
       hipLaunchKernelGGL(keydiff_kernel<true>, grid, blk, 0, s, a, (const double*)ksum);
     } else {
       hipLaunchKernelGGL(keysum_kernel<false>, grid, blk, 0, s, a, ksum);
+      prof_mark("keydiff", s);
       hipLaunchKernelGGL(keydiff_kernel<false>, grid, blk, 0, s, a, (const double*)ksum);
     }
     e = hipGetLastError();

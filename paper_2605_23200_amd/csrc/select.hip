@@ -225,8 +225,10 @@ hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_
                          int32_t* n_kept, hipStream_t s) {
   const int S = p->n_segments;
   if (S > kMaxSeg) return hipErrorInvalidValue;
+  prof_mark("quota", s);
   hipLaunchKernelGGL(quota_kernel, dim3(d.units), dim3(64), 0, s, d, seq_lens, S, p->budget, p->q_min,
                      bounds, seg_mass, quota, idx, n_kept);
+  prof_mark("select", s);
   hipLaunchKernelGGL(select_kernel, dim3(S, d.units), dim3(kSelBlock), 0, s, d, S, p->budget, g, bounds,
                      quota, idx);
   return hipGetLastError();
