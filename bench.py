@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Throughput of the fused AMS compression step on one MI355X.
+
+A step is one whole compression event (score -> mass -> EMA -> prefix sum / boundaries -> quotas ->
+segmented top-k -> gather-compact) over every (layer, KV head) of a synthetic cache with the shapes of
+the 32k-context configuration: 32 layers x 8 KV heads, group 4, head_dim 128, bf16, T = 32768, query
+window 32, budget 2048, S = 16, lambda = 0.9.  Inputs are resident in HBM before the timed region.
+Every timed step runs at T = 32768 against the same source cache (the destination is a separate
+buffer); the credit vector persists across steps at full length and a different query window is
+used from step to step, so each step does the full work of an event.
+
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
+
+
+def algorithmic_bytes(w):
+    """Bytes one event must move per unit: K read once for scoring, kept K/V rows read and written,
+    three fp32 vector passes (u write + read, credit read), index and credit' writes."""
+    e = w.elem_bytes
+    return w.T * w.D * e + 4 * w.budget * w.D * e + 4 * w.T * 3 + 4 * w.budget * 2
+
+
+def kernel_bytes(label, w):
+    """Algorithmic bytes of one launch of a kernel over all units (what it must read + write)."""
+    e, U, T, Bd, D, S = w.elem_bytes, w.units, w.T, w.budget, w.D, w.S
+    per_unit = {
+        "score_stats": T * D * e,                       # K stream
+        "score_usage": T * D * e + 4 * T,               # K stream + u
+        "score_reduce": 0,
+        "ema": 4 * T * 4,                               # u, credit in; credit, m_used out
+        "segment": 4 * T,                               # m_used in
+        "quota": 0,
+        "select": 4 * T + 4 * Bd,                       # g in, idx out
+        "compact": 4 * Bd * D * e + 4 * Bd * 3,         # K,V rows in + out, idx, credit gather
+    }.get(label, 0)
+    return per_unit * U
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="workload number (1 = the headline 32k configuration)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-units", type=int, default=64, help="units of the workload the CPU oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (units are independent; there is no multi-GPU path). "
+                 "Run with --gpus 1.")
+
+    import numpy as np
+    import torch
+    from paper_2605_23200_amd import binding as B
+    from paper_2605_23200_amd import inputs
+    from paper_2605_23200_amd.harness import Job
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    B.lib()                                   # fails loudly if the HIP library is not built
+    w = inputs.CONFIGS[args.config]
+    if w.paged or w.T_min is not None:
+        sys.exit("bench.py: only dense single-length workloads are benchmark lines")
+    t0 = time.time()
+    host = inputs.dense_cache(w, n_threads=16)
+    job = Job(w, host)
+    n_q = 4
+    q_windows = [job.Q] + [torch.empty_like(job.Q) for _ in range(n_q - 1)]
+    for e in range(1, n_q):
+        Q = np.zeros_like(host["Q"])
+        for (l, b, h) in inputs.unit_ids(w):
+            Q[l, b, h * w.G:(h + 1) * w.G] = inputs.unit_q(w, l, b, h, e)
+        q_windows[e].copy_(torch.from_numpy(Q.view(np.int16) if Q.dtype == np.uint16 else Q))
+    setup_s = time.time() - t0
+    stream = torch.cuda.current_stream()
+
+    def one_step(i):
+        job.Q = q_windows[i % n_q]
+        job.step(stream)
+
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # per-kernel durations: HIP events recorded by the library before every launch, same stream
+    B.ams_profile_begin()
+    for i in range(args.steps):
+        one_step(i)
+    marks = B.ams_profile_end(stream)
+    per = {}
+    for label, ms in marks:
+        per.setdefault(label, []).append(ms)
+    kern = {k: sum(v) / len(v) for k, v in per.items()}
+    dom = max(kern, key=kern.get)
+    dom_bytes = kernel_bytes(dom, w)
+    achieved = dom_bytes / (kern[dom] * 1e-3) / 1e9
+
+    step_bytes = algorithmic_bytes(w) * w.units
+    eff_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    out = {
+        "metric": "ams_compress_steps_per_sec", "value": round(1e3 / ms_per_step, 3), "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"config{args.config}: {w.L}L x {w.H} KV heads, group {w.G}, D {w.D}, {w.dtype}, "
+                               f"T {w.T}, window {w.W}, budget {w.budget}, S {w.S}, lambda {w.lam}, "
+                               f"{w.n_spans} planted spans, seed {w.seed}; steady-state events at full T",
+                   "units": w.units, "scorer": "mean_window"},
+        "effective_GBps": round(eff_gbps, 1), "algorithmic_bytes_per_step": step_bytes,
+        "hbm_peak_frac": round(eff_gbps / HBM_PEAK_GBPS, 4),
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel_ms": round(kern[dom], 4), "algorithmic_bytes_per_launch": dom_bytes},
+        "kernel_ms": {k: round(v, 4) for k, v in kern.items()},
+        "setup_s": round(setup_s, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import ams_oracle as O
+        n_units = min(args.cpu_units, w.units)
+        ids = inputs.unit_ids(w)[:n_units]
+        Qf = np.stack([inputs.as_f32(host["Q"][l, b, h * w.G:(h + 1) * w.G]).reshape(-1, w.D) for l, b, h in ids])
+        Kf = np.stack([inputs.as_f32(host["K"][l, b, h]) for l, b, h in ids])
+        Kr = np.stack([host["K"][l, b, h] for l, b, h in ids])
+        Vr = np.stack([host["V"][l, b, h] for l, b, h in ids])
+        credit = np.zeros((n_units, w.T), np.float32)
+        n_threads = min(16, os.cpu_count() or 1)
+        t0 = time.perf_counter()
+        _, _, used = O.compress_many(np.ascontiguousarray(Qf), np.ascontiguousarray(Kf), credit, G=w.G, W=w.W,
+                                     budget=w.budget, S=w.S, lam=w.lam, beta=w.beta, eps=w.eps, q_min=w.q_min,
+                                     n_threads=n_threads, K_rows=Kr, V_rows=Vr)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(n_units / cpu_s / w.units, 5), "unit": "steps/s", "cores": used,
+                               "kind": "oracle",
+                               "sample": f"first {n_units} of {w.units} units of the same workload, one event, "
+                                         f"{cpu_s:.1f} s wall, scaled linearly to a whole step"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -353,8 +353,11 @@ int amso_compress_many(const amso_unit_params* p, int n_units, int n_threads,
                        const float* Q, int64_t q_stride,
                        const float* K, int64_t k_stride,
                        float* credit, int64_t c_stride,
-                       float* u, float* g, int32_t* idx, int32_t* n_kept) {
+                       float* u, float* g, int32_t* idx, int32_t* n_kept,
+                       const void* K_rows, const void* V_rows, int64_t row_bytes,
+                       void* K_out, void* V_out, float* credit_out) {
   if (!p || n_units < 1 || !Q || !K || !credit || !idx || !n_kept) return -1;
+  const bool gather = K_rows && V_rows && K_out && V_out && row_bytes > 0;
   if (n_threads < 1) n_threads = (int)std::thread::hardware_concurrency();
   if (n_threads < 1) n_threads = 1;
   n_threads = std::min(n_threads, n_units);
@@ -365,11 +368,16 @@ int amso_compress_many(const amso_unit_params* p, int n_units, int n_threads,
       if (i >= n_units) return;
       int32_t* my_idx = idx + (size_t)i * p->budget;
       for (int j = 0; j < p->budget; ++j) my_idx[j] = -1;
+      const size_t src_off = (size_t)i * p->T * (size_t)row_bytes;
+      const size_t dst_off = (size_t)i * p->budget * (size_t)row_bytes;
       const int rc = amso_compress_unit(
-          p, Q + (size_t)i * q_stride, K + (size_t)i * k_stride, nullptr, nullptr, 1,
-          credit + (size_t)i * c_stride,
+          p, Q + (size_t)i * q_stride, K + (size_t)i * k_stride,
+          gather ? (const char*)K_rows + src_off : nullptr, gather ? (const char*)V_rows + src_off : nullptr,
+          gather ? row_bytes : 1, credit + (size_t)i * c_stride,
           u ? u + (size_t)i * p->T : nullptr, g ? g + (size_t)i * p->T : nullptr,
-          nullptr, nullptr, nullptr, nullptr, my_idx, n_kept + i, nullptr, nullptr, nullptr);
+          nullptr, nullptr, nullptr, nullptr, my_idx, n_kept + i,
+          gather ? (char*)K_out + dst_off : nullptr, gather ? (char*)V_out + dst_off : nullptr,
+          credit_out ? credit_out + (size_t)i * p->budget : nullptr);
       if (rc) failed.store(rc);
     }
   };

@@ -101,12 +101,17 @@ int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K
  * (strides given in elements / bytes), with a plain thread parallel-for over
  * units.  Used for timing the oracle and for checking many units at once.
  * Outputs idx [n_units][budget] (tail -1), n_kept [n_units], u/g [n_units][T]
- * (either may be NULL).  Returns the number of threads used (>0) or <0 on error. */
+ * (either may be NULL).  When K_rows, V_rows ([n_units][T] rows of row_bytes in the
+ * storage dtype) and K_out, V_out ([n_units][budget] rows) are given the rows are
+ * gathered too, credit_out [n_units][budget] likewise.
+ * Returns the number of threads used (>0) or <0 on error. */
 int amso_compress_many(const amso_unit_params* p, int n_units, int n_threads,
                        const float* Q, int64_t q_stride,
                        const float* K, int64_t k_stride,
                        float* credit, int64_t c_stride,
-                       float* u, float* g, int32_t* idx, int32_t* n_kept);
+                       float* u, float* g, int32_t* idx, int32_t* n_kept,
+                       const void* K_rows, const void* V_rows, int64_t row_bytes,
+                       void* K_out, void* V_out, float* credit_out);
 
 #ifdef __cplusplus
 }

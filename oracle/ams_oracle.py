@@ -171,9 +171,10 @@ def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, 
 
 
 def compress_many(Q, K, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_min=1,
-                  scorer=SCORER_MEAN_WINDOW, n_threads=0, want_scores=False):
+                  scorer=SCORER_MEAN_WINDOW, n_threads=0, want_scores=False, K_rows=None, V_rows=None):
     """Q [U, G*W, D], K [U, T, D] float32 (already widened), credit [U, T] (updated in
-    place).  Returns (idx [U, budget], n_kept [U], threads_used[, u, g])."""
+    place).  K_rows, V_rows [U, T, D] in the storage dtype: when given, the kept rows are
+    gathered as well (whole event).  Returns (idx [U, budget], n_kept [U], threads_used[, u, g])."""
     U, T, D = K.shape
     assert Q.shape == (U, G * W, D) and credit.shape == (U, T)
     for a in (Q, K, credit):
@@ -183,10 +184,21 @@ def compress_many(Q, K, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_m
     n_kept = np.empty(U, np.int32)
     u = np.empty((U, T), np.float32) if want_scores else None
     g = np.empty((U, T), np.float32) if want_scores else None
+    gather = K_rows is not None and V_rows is not None
+    if gather:
+        assert K_rows.shape == (U, T, D) and K_rows.flags["C_CONTIGUOUS"] and V_rows.flags["C_CONTIGUOUS"]
+        K_out = np.zeros((U, budget, D), K_rows.dtype)
+        V_out = np.zeros((U, budget, D), V_rows.dtype)
+        c_out = np.zeros((U, budget), np.float32)
+    vp = lambda a: a.ctypes.data_as(C.c_void_p)
     rc = lib().amso_compress_many(C.byref(p), U, int(n_threads), _f(Q), C.c_int64(G * W * D), _f(K),
                                   C.c_int64(T * D), _f(credit), C.c_int64(T),
                                   _f(u) if want_scores else None, _f(g) if want_scores else None,
-                                  _i(idx), _i(n_kept))
+                                  _i(idx), _i(n_kept),
+                                  vp(K_rows) if gather else None, vp(V_rows) if gather else None,
+                                  C.c_int64(K_rows[0, 0].nbytes if gather else 0),
+                                  vp(K_out) if gather else None, vp(V_out) if gather else None,
+                                  _f(c_out) if gather else None)
     if rc <= 0:
         raise RuntimeError(f"oracle compress_many failed with code {rc}")
     return (idx, n_kept, rc, u, g) if want_scores else (idx, n_kept, rc)
