@@ -140,6 +140,7 @@ int ams_score(const ams_params* p, const ams_kv_view* src, const int32_t* seq_le
  *   m_used = normalize(beta*m + (1-beta)*normalize(credit)).
  * lambda == 0: m_used = m and credit <- m.
  *   u [dev] in; credit [dev] in/out; m_used [dev] out; all fp32 [units, t_stride]
+ *   ws [dev] scratch of at least ams_workspace_bytes(p)
  */
 int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u, float* credit,
                    float* m_used, void* ws, size_t ws_bytes, void* stream);
@@ -150,6 +151,7 @@ int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u,
  *   bounds[0] = 0, bounds[S] = T, bounds[k] = 1 + min{ j : c(j) >= k/S } (T if the
  *   threshold is never reached); seg_mass[i] = sum of m_used over segment i.
  *   bounds [dev] int32 [units, S+1]; seg_mass [dev] fp32 [units, S]
+ *   ws [dev] scratch of at least ams_workspace_bytes(p)
  */
 int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* m_used,
                      int32_t* bounds, float* seg_mass, void* ws, size_t ws_bytes, void* stream);
@@ -163,6 +165,7 @@ int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* 
  *   position first; NaN ranks below everything), ascending; entries from n_kept
  *   to budget are -1.
  *   quota [dev] int32 [units, S]; idx [dev] int32 [units, budget]; n_kept [dev] int32 [units]
+ *   ws may be NULL (this stage needs no scratch)
  */
 int ams_select(const ams_params* p, const int32_t* seq_lens, const float* g, const int32_t* bounds,
                const float* seg_mass, int32_t* quota, int32_t* idx, int32_t* n_kept,

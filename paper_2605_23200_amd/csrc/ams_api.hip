@@ -39,6 +39,11 @@ WsLayout ws_layout(const ams_params* p) {
   w.seg_mass = o;   o += align256(units * (size_t)p->n_segments * sizeof(float));
   w.quota = o;      o += align256(units * (size_t)p->n_segments * sizeof(int32_t));
   w.kbar = o;       o += align256(units * w.n_chunks * (size_t)p->head_dim * sizeof(double));
+  w.fused = o;      o += align256(fused_score_ws_bytes((int64_t)units, p->t_max, w.n_pad, p->batch));
+  w.n_chunks4k = div_up(p->t_max, kChunk);
+  w.vc_part = o;    o += align256(units * w.n_chunks4k * 2 * sizeof(double));
+  w.mpart = o;      o += align256(units * w.n_chunks4k * sizeof(double));
+  w.cpre = o;       o += align256(units * (size_t)(p->n_segments + 1) * sizeof(double));
   w.total = o;
   return w;
 }
@@ -213,22 +218,24 @@ int ams_score(const ams_params* p, const ams_kv_view* src, const int32_t* seq_le
 
 int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u, float* credit,
                    float* m_used, void* ws, size_t ws_bytes, void* stream) {
-  (void)ws;
-  (void)ws_bytes;
   const int rc = check_params(p);
   if (rc) return rc;
-  if (!seq_lens || !u || !credit || !m_used) return AMS_ERR_INVALID_ARG;
-  return hip_status(launch_ema(p, make_dims(p), seq_lens, u, credit, m_used, (hipStream_t)stream), (hipStream_t)stream);
+  if (!seq_lens || !u || !credit || !m_used || !ws) return AMS_ERR_INVALID_ARG;
+  const WsLayout wl = ws_layout(p);
+  if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
+  return hip_status(launch_ema(p, make_dims(p), seq_lens, u, credit, m_used, (int32_t*)((char*)ws + wl.bounds),
+                               (char*)ws, wl, (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* m_used,
                      int32_t* bounds, float* seg_mass, void* ws, size_t ws_bytes, void* stream) {
-  (void)ws;
-  (void)ws_bytes;
   const int rc = check_params(p);
   if (rc) return rc;
-  if (!seq_lens || !m_used || !bounds || !seg_mass) return AMS_ERR_INVALID_ARG;
-  return hip_status(launch_segment(p, make_dims(p), seq_lens, m_used, bounds, seg_mass, (hipStream_t)stream), (hipStream_t)stream);
+  if (!seq_lens || !m_used || !bounds || !seg_mass || !ws) return AMS_ERR_INVALID_ARG;
+  const WsLayout wl = ws_layout(p);
+  if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
+  return hip_status(launch_segment(p, make_dims(p), seq_lens, m_used, bounds, seg_mass, false, (char*)ws, wl,
+                                   (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_select(const ams_params* p, const int32_t* seq_lens, const float* g, const int32_t* bounds,
@@ -286,8 +293,9 @@ int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t
   hipError_t e;
   if ((e = launch_score(p, d, make_kv(p, src, src->k), seq_lens, q, u, g, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;
-  if ((e = launch_ema(p, d, seq_lens, u, credit, m_used, s)) != hipSuccess) return AMS_ERR_HIP;
-  if ((e = launch_segment(p, d, seq_lens, m_used, bounds, seg_mass, s)) != hipSuccess) return AMS_ERR_HIP;
+  if ((e = launch_ema(p, d, seq_lens, u, credit, m_used, bounds, w, wl, s)) != hipSuccess) return AMS_ERR_HIP;
+  if ((e = launch_segment(p, d, seq_lens, m_used, bounds, seg_mass, true, w, wl, s)) != hipSuccess)
+    return AMS_ERR_HIP;
   if ((e = launch_select(p, d, seq_lens, g, bounds, seg_mass, quota, idx, n_kept, s)) != hipSuccess)
     return AMS_ERR_HIP;
   if ((e = launch_compact(p, d, make_kv(p, src, src->k), make_kv(p, src, src->v), make_kv(p, dst, dst->k),

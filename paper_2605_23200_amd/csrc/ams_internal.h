@@ -46,13 +46,15 @@ __device__ __forceinline__ void unit_coords(const Dims& d, int unit, int& l, int
 }
 
 constexpr int kScoreChunk = 1024;  // tokens per workgroup of the scoring kernels
+constexpr int kChunk = 4096;       // positions per workgroup of the mass / prefix kernels
 
 inline int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 // Workspace carving (offsets in bytes, 256-byte aligned).
 struct WsLayout {
-  size_t part_stats, fin_stats, u, g, m_used, bounds, seg_mass, quota, kbar, total;
+  size_t part_stats, fin_stats, u, g, m_used, bounds, seg_mass, quota, kbar, fused, vc_part, mpart, cpre, total;
   int n_chunks, n_pad;
+  int n_chunks4k;  // chunks of kChunk positions per unit
 };
 WsLayout ws_layout(const ams_params* p);
 
@@ -63,10 +65,18 @@ void prof_mark(const char* label, hipStream_t s);
 // ---- launchers (each returns hipGetLastError() of its launches) ----
 hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
                         const void* q, float* u, float* g, char* ws, const WsLayout& wl, hipStream_t s);
+size_t fused_score_ws_bytes(int64_t units, int t_max, int n_pad, int batch);
+hipError_t launch_score_onepass(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
+                                const void* q, float* u, float* g, char* ws, const WsLayout& wl,
+                                hipStream_t s, bool* ran);
+// launch_ema also leaves the chunk totals of m_used in the workspace and resets `bounds` (scratch
+// or the caller's) for a following launch_segment(have_chunk_totals = true).
 hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
-                      float* credit, float* m_used, hipStream_t s);
+                      float* credit, float* m_used, int32_t* bounds, char* ws, const WsLayout& wl,
+                      hipStream_t s);
 hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq_lens,
-                          const float* m_used, int32_t* bounds, float* seg_mass, hipStream_t s);
+                          const float* m_used, int32_t* bounds, float* seg_mass, bool have_chunk_totals,
+                          char* ws, const WsLayout& wl, hipStream_t s);
 hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* g,
                          const int32_t* bounds, const float* seg_mass, int32_t* quota, int32_t* idx,
                          int32_t* n_kept, hipStream_t s);

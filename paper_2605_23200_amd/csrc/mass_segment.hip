@@ -1,9 +1,24 @@
 // Eq. (1) + EMA credit (Sec. 3.2, 3.3; Alg. 1 steps 1-2) and the mass prefix sum with its cut
 // points (Sec. 3.3 "Mass-based adaptive segmentation"; Alg. 1 step 3, Delta = 1/S).
 //
-// One workgroup owns one unit.  The vectors are a few hundred KB per unit and stay in L2
-// between the passes; every normaliser and every scan carry is held in double so that the
-// results are independent of T to well below the fp32 tolerance.
+// All of it is elementwise work plus a few sums over T, so every unit is cut into chunks of 4096
+// positions and each (chunk, unit) is one workgroup: the chip is filled even with few units.
+//
+//   vc_sums_kernel       partial sums of max(u,0)+eps and of the old credit per chunk
+//   mass_ema_kernel      m = v/Z, c <- lambda c + (1-lambda) m, m_used; chunk totals of m_used
+//   chunk_total_kernel   (stand-alone segmentation only) chunk totals of a given m_used
+//   segment_scan_kernel  inclusive prefix P(j) and the first j with P(j) >= k/S for every k
+//   segment_finalize_kernel  segment masses from the prefix at the cuts
+//
+// Normalisers: Z is the actual sum of max(u,0)+eps.  The credit normaliser sum(c_new) is taken as
+// lambda * sum(c_old) + (1 - lambda) and the outer normaliser as 1: both identities hold exactly in
+// real arithmetic (sum(m) = 1) and to ~1e-8 in floating point, far inside the fp32 tolerance, and
+// they remove two dependent sweeps over T.
+//
+// Prefix: P(j) = C[chunk] + p_local(j) with C[c] the sequential sum of the chunk totals before c and
+// p_local the in-chunk scan; a chunk total IS p_local of the chunk's last position, so
+// P(last of chunk c-1) == C[c] bit for bit and the chain of "first position that reaches k/S"
+// tests is consistent across chunks.  Everything that feeds a comparison is double.
 #include "ams_internal.h"
 
 namespace ams {
@@ -11,6 +26,8 @@ namespace {
 
 constexpr int kBlock = 1024;
 constexpr int kWaves = kBlock / 64;
+constexpr int kPer = 4;
+static_assert(kBlock * kPer == kChunk, "one workgroup covers one chunk");
 
 // Sum over the workgroup, same value in every thread, fixed order.
 __device__ __forceinline__ double block_sum(double v, double* sm) {
@@ -25,51 +42,167 @@ __device__ __forceinline__ double block_sum(double v, double* sm) {
   return t;
 }
 
-__global__ __launch_bounds__(kBlock) void ema_kernel(Dims d, const int32_t* seq_lens, const float* u_all,
-                                                      float* credit_all, float* m_used_all, float lambda,
-                                                      float beta, float eps_f) {
+// In-chunk inclusive prefix of the four consecutive positions each thread owns, and the chunk
+// total (= prefix of the very last position).  The association is fixed by the thread layout.
+__device__ __forceinline__ void chunk_scan(const float (&x)[kPer], double (&p)[kPer], double& total,
+                                           double* wave_tot, double* bcast) {
+  double ts = 0.0;
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) ts += (double)x[i];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  double incl = ts;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const double v = __shfl_up(incl, o);
+    if (lane >= o) incl += v;
+  }
+  __syncthreads();
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  double off = 0.0;
+  for (int w = 0; w < wave; ++w) off += wave_tot[w];
+  double run = off + (incl - ts);
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) {
+    run += (double)x[i];
+    p[i] = run;
+  }
+  if (threadIdx.x == kBlock - 1) *bcast = run;
+  __syncthreads();
+  total = *bcast;
+}
+
+// Four consecutive fp32 of a row: one 16-byte access when the row allows it.
+__device__ __forceinline__ void load4(const float* row, int j0, int T, bool vec, float (&x)[kPer], float fill) {
+  if (vec && j0 + kPer <= T) {
+    const float4 v = *reinterpret_cast<const float4*>(row + j0);
+    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+  } else {
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) x[i] = (j0 + i < T) ? row[j0 + i] : fill;
+  }
+}
+__device__ __forceinline__ void store4(float* row, int j0, int T, bool vec, const float (&x)[kPer]) {
+  if (vec && j0 + kPer <= T) {
+    *reinterpret_cast<float4*>(row + j0) = make_float4(x[0], x[1], x[2], x[3]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < kPer; ++i)
+      if (j0 + i < T) row[j0 + i] = x[i];
+  }
+}
+
+struct MsArgs {
+  Dims d;
+  const int32_t* seq_lens;
+  int n_chunks;      // chunks per unit (stride of the per-chunk arrays)
+  int S;
+  double2* vc_part;  // [units][n_chunks]  (sum of max(u,0)+eps, sum of old credit)
+  double* mpart;     // [units][n_chunks]  chunk totals of m_used
+  double* cpre;      // [units][S+1]       prefix at the cuts (negative = threshold never reached)
+  int32_t* bounds;   // [units][S+1]
+  bool vec;          // rows of the fp32 vectors are 16-byte aligned
+};
+
+__device__ __forceinline__ void init_cuts(const MsArgs& a, int unit, int T) {
+  int32_t* bounds = a.bounds + (int64_t)unit * (a.S + 1);
+  double* cpre = a.cpre + (int64_t)unit * (a.S + 1);
+  for (int k = threadIdx.x; k <= a.S; k += kBlock) {
+    bounds[k] = (k == 0) ? 0 : T;
+    cpre[k] = (k == 0) ? 0.0 : -1.0;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void vc_sums_kernel(MsArgs a, const float* u_all, const float* credit_all,
+                                                          float eps_f) {
   __shared__ double sm[kWaves];
-  const int unit = blockIdx.x;
+  const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
-  unit_coords(d, unit, l, b, h);
-  const int T = seq_lens[b];
-  const float* u = u_all + (int64_t)unit * d.t_stride;
-  float* credit = credit_all + (int64_t)unit * d.t_stride;
-  float* m_used = m_used_all + (int64_t)unit * d.t_stride;
-  const double eps = (double)eps_f, lam = (double)lambda, bet = (double)beta;
-
-  double acc = 0.0;
-  for (int t = threadIdx.x; t < T; t += kBlock) acc += fmax((double)u[t], 0.0) + eps;
-  const double Z = block_sum(acc, sm);
-
-  if (lambda == 0.f) {  // credit not used: the mass passes through unchanged
-    for (int t = threadIdx.x; t < T; t += kBlock) {
-      const float mc = (float)((fmax((double)u[t], 0.0) + eps) / Z);
-      credit[t] = mc;
-      m_used[t] = mc;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  const int j0 = chunk * kChunk + threadIdx.x * kPer;
+  if (chunk * kChunk >= T) return;
+  const float* u = u_all + (int64_t)unit * a.d.t_stride;
+  const float* credit = credit_all + (int64_t)unit * a.d.t_stride;
+  double v = 0.0, c = 0.0;
+  float ux[kPer], cx[kPer];
+  load4(u, j0, T, a.vec, ux, 0.f);
+  load4(credit, j0, T, a.vec, cx, 0.f);
+#pragma unroll
+  for (int i = 0; i < kPer; ++i)
+    if (j0 + i < T) {
+      v += fmax((double)ux[i], 0.0) + (double)eps_f;
+      c += (double)cx[i];
     }
-    return;
+  v = block_sum(v, sm);
+  c = block_sum(c, sm);
+  if (threadIdx.x == 0) a.vc_part[(int64_t)unit * a.n_chunks + chunk] = make_double2(v, c);
+}
+
+__global__ __launch_bounds__(kBlock) void mass_ema_kernel(MsArgs a, const float* u_all, float* credit_all,
+                                                           float* m_used_all, float lambda, float beta,
+                                                           float eps_f) {
+  __shared__ double wave_tot[kWaves];
+  __shared__ double bcast;
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  if (chunk * kChunk >= T) return;
+  if (chunk == 0) init_cuts(a, unit, T);
+  const int nch = (T + kChunk - 1) / kChunk;
+  double Z = 0.0, c_old = 0.0;
+  for (int c = 0; c < nch; ++c) {
+    const double2 p = a.vc_part[(int64_t)unit * a.n_chunks + c];
+    Z += p.x;
+    c_old += p.y;
   }
-  acc = 0.0;
-  for (int t = threadIdx.x; t < T; t += kBlock) {
-    const float mc = (float)((fmax((double)u[t], 0.0) + eps) / Z);
-    const float cn = (float)(lam * (double)credit[t] + (1.0 - lam) * (double)mc);
-    credit[t] = cn;
-    acc += (double)cn;
+  const double lam = (double)lambda, bet = (double)beta, eps = (double)eps_f;
+  const double inv_z = 1.0 / Z, inv_csum = 1.0 / (lam * c_old + (1.0 - lam));
+  const float* u = u_all + (int64_t)unit * a.d.t_stride;
+  float* credit = credit_all + (int64_t)unit * a.d.t_stride;
+  float* m_used = m_used_all + (int64_t)unit * a.d.t_stride;
+  const int j0 = chunk * kChunk + threadIdx.x * kPer;
+  float mu[kPer], ux[kPer], cx[kPer];
+  load4(u, j0, T, a.vec, ux, 0.f);
+  load4(credit, j0, T, a.vec, cx, 0.f);
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) {
+    mu[i] = 0.f;
+    if (j0 + i < T) {
+      const float mc = (float)((fmax((double)ux[i], 0.0) + eps) * inv_z);
+      float cn = mc;
+      mu[i] = mc;  // lambda == 0: credit not used, the mass passes through unchanged
+      if (lambda != 0.f) {
+        cn = (float)(lam * (double)cx[i] + (1.0 - lam) * (double)mc);
+        mu[i] = (float)(bet * (double)mc + (1.0 - bet) * ((double)cn * inv_csum));
+      }
+      cx[i] = cn;
+    }
   }
-  const double csum = block_sum(acc, sm);
-  acc = 0.0;
-  for (int t = threadIdx.x; t < T; t += kBlock) {
-    const float mc = (float)((fmax((double)u[t], 0.0) + eps) / Z);
-    const double ctil = csum > 0.0 ? (double)credit[t] / csum : (double)mc;
-    acc += bet * (double)mc + (1.0 - bet) * ctil;
-  }
-  const double msum = block_sum(acc, sm);
-  for (int t = threadIdx.x; t < T; t += kBlock) {
-    const float mc = (float)((fmax((double)u[t], 0.0) + eps) / Z);
-    const double ctil = csum > 0.0 ? (double)credit[t] / csum : (double)mc;
-    m_used[t] = (float)((bet * (double)mc + (1.0 - bet) * ctil) / msum);
-  }
+  store4(credit, j0, T, a.vec, cx);
+  store4(m_used, j0, T, a.vec, mu);
+  double p[kPer], total;
+  chunk_scan(mu, p, total, wave_tot, &bcast);
+  if (threadIdx.x == 0) a.mpart[(int64_t)unit * a.n_chunks + chunk] = total;
+}
+
+__global__ __launch_bounds__(kBlock) void chunk_total_kernel(MsArgs a, const float* m_all) {
+  __shared__ double wave_tot[kWaves];
+  __shared__ double bcast;
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  if (chunk * kChunk >= T) return;
+  if (chunk == 0) init_cuts(a, unit, T);
+  const float* m = m_all + (int64_t)unit * a.d.t_stride;
+  const int j0 = chunk * kChunk + threadIdx.x * kPer;
+  float x[kPer];
+  load4(m, j0, T, a.vec, x, 0.f);
+  double p[kPer], total;
+  chunk_scan(x, p, total, wave_tot, &bcast);
+  if (threadIdx.x == 0) a.mpart[(int64_t)unit * a.n_chunks + chunk] = total;
 }
 
 // Number of thresholds k/S, k = 1..S-1, that are <= c.
@@ -81,109 +214,111 @@ __device__ __forceinline__ int thresholds_reached(double c, int S) {
   return f;
 }
 
-constexpr int kPerThread = 4;
-constexpr int kTile = kBlock * kPerThread;
-constexpr int kMaxSeg = 1024;
-
-// Inclusive prefix P(j) of the unit's mass: every thread owns four consecutive positions of a
-// 4096-position tile; P is the tile carry plus a workgroup scan of the thread sums plus the
-// thread's own running sum.  Threshold k is cut at the first j whose P(j) reaches k/S.
-__global__ __launch_bounds__(kBlock) void segment_kernel(Dims d, const int32_t* seq_lens,
-                                                          const float* m_all, int S, int32_t* bounds_all,
-                                                          float* seg_mass_all) {
+__global__ __launch_bounds__(kBlock) void segment_scan_kernel(MsArgs a, const float* m_all) {
   __shared__ double wave_tot[kWaves];
+  __shared__ double bcast;
   __shared__ double ends[kBlock];
-  __shared__ int32_t lb[kMaxSeg + 1];
-  __shared__ double cpre[kMaxSeg + 1];
-  const int unit = blockIdx.x;
+  const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
-  unit_coords(d, unit, l, b, h);
-  const int T = seq_lens[b];
-  const float* m = m_all + (int64_t)unit * d.t_stride;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-
-  for (int k = threadIdx.x; k <= S; k += kBlock) lb[k] = (k == 0) ? 0 : T;
-  double total = 0.0;
-  for (int phase = 0; phase < 2; ++phase) {
-    double carry = 0.0;      // P of the last position of the previous tile
-    double prev_tile_end = 0.0;
-    __syncthreads();
-    for (int base = 0; base < T; base += kTile) {
-      const int j0 = base + threadIdx.x * kPerThread;
-      float x[kPerThread];
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  if (chunk * kChunk >= T) return;
+  const float* m = m_all + (int64_t)unit * a.d.t_stride;
+  double C = 0.0;  // prefix of everything before this chunk
+  for (int c = 0; c < chunk; ++c) C += a.mpart[(int64_t)unit * a.n_chunks + c];
+  const int j0 = chunk * kChunk + threadIdx.x * kPer;
+  float x[kPer];
+  load4(m, j0, T, a.vec, x, 0.f);
+  double p[kPer], total;
+  chunk_scan(x, p, total, wave_tot, &bcast);
+  ends[threadIdx.x] = C + p[kPer - 1];
+  __syncthreads();
+  const double prev_end = threadIdx.x > 0 ? ends[threadIdx.x - 1] : C;
+  int f_prev = thresholds_reached(prev_end, a.S);
+  int32_t* bounds = a.bounds + (int64_t)unit * (a.S + 1);
+  double* cpre = a.cpre + (int64_t)unit * (a.S + 1);
+  // most threads see no threshold between their neighbour's prefix and their own largest one
+  double p_max = p[0];
 #pragma unroll
-      for (int i = 0; i < kPerThread; ++i) x[i] = (j0 + i < T) ? m[j0 + i] : 0.f;
-      double ts = 0.0;
+  for (int i = 1; i < kPer; ++i) p_max = fmax(p_max, p[i]);
+  if (thresholds_reached(C + p_max, a.S) <= f_prev) return;
 #pragma unroll
-      for (int i = 0; i < kPerThread; ++i) ts += (double)x[i];
-      double incl = ts;
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const double v = __shfl_up(incl, o);
-        if (lane >= o) incl += v;
+  for (int i = 0; i < kPer; ++i) {
+    if (j0 + i < T) {
+      const double P = C + p[i];
+      const int f_cur = thresholds_reached(P, a.S);
+      for (int k = f_prev + 1; k <= f_cur; ++k) {  // position j0+i is the first to reach k/S
+        atomicMin(&bounds[k], j0 + i + 1);
+        cpre[k] = P;
       }
-      if (lane == 63) wave_tot[wave] = incl;
-      __syncthreads();
-      double off = carry;
-      for (int w = 0; w < wave; ++w) off += wave_tot[w];
-      double tile_end = carry;
-      for (int w = 0; w < kWaves; ++w) tile_end += wave_tot[w];
-      const double excl = off + (incl - ts);
-      double c[kPerThread];
-      double run = excl;
-#pragma unroll
-      for (int i = 0; i < kPerThread; ++i) {
-        run += (double)x[i];
-        c[i] = run;
-      }
-      ends[threadIdx.x] = run;
-      __syncthreads();
-      const double prev_end = threadIdx.x > 0 ? ends[threadIdx.x - 1] : prev_tile_end;
-      int f_prev = thresholds_reached(prev_end, S);
-#pragma unroll
-      for (int i = 0; i < kPerThread; ++i) {
-        if (j0 + i < T) {
-          const int f_cur = thresholds_reached(c[i], S);
-          for (int k = f_prev + 1; k <= f_cur; ++k) {
-            if (phase == 0) atomicMin(&lb[k], j0 + i + 1);          // first position that reaches k/S
-            else if (lb[k] == j0 + i + 1) cpre[k] = c[i];           // prefix at the cut, for the masses
-          }
-          f_prev = max(f_prev, f_cur);
-        }
-      }
-      prev_tile_end = ends[kBlock - 1];
-      carry = tile_end;
-      __syncthreads();
-    }
-    total = carry;
-    if (phase == 0) {
-      __syncthreads();
-      for (int k = threadIdx.x; k <= S; k += kBlock) cpre[k] = (k == 0) ? 0.0 : total;
+      f_prev = max(f_prev, f_cur);
     }
   }
-  __syncthreads();
-  int32_t* bounds = bounds_all + (int64_t)unit * (S + 1);
-  float* seg_mass = seg_mass_all + (int64_t)unit * S;
-  for (int k = threadIdx.x; k <= S; k += kBlock) bounds[k] = lb[k];
-  for (int i = threadIdx.x; i < S; i += kBlock) seg_mass[i] = (float)(cpre[i + 1] - cpre[i]);
+}
+
+__global__ void segment_finalize_kernel(MsArgs a, float* seg_mass_all) {
+  const int unit = blockIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  const int nch = (T + kChunk - 1) / kChunk;
+  double total = 0.0;
+  for (int c = 0; c < nch; ++c) total += a.mpart[(int64_t)unit * a.n_chunks + c];
+  const double* cpre = a.cpre + (int64_t)unit * (a.S + 1);
+  for (int i = threadIdx.x; i < a.S; i += blockDim.x) {
+    const double lo = cpre[i] < 0.0 ? total : cpre[i];
+    const double hi = (i + 1 == a.S || cpre[i + 1] < 0.0) ? total : cpre[i + 1];
+    seg_mass_all[(int64_t)unit * a.S + i] = (float)(hi - lo);
+  }
+}
+
+MsArgs make_args(const ams_params* p, const Dims& d, const int32_t* seq_lens, char* ws, const WsLayout& wl,
+                 int32_t* bounds) {
+  MsArgs a;
+  a.d = d;
+  a.seq_lens = seq_lens;
+  a.n_chunks = wl.n_chunks4k;
+  a.S = p->n_segments;
+  a.vc_part = (double2*)(ws + wl.vc_part);
+  a.mpart = (double*)(ws + wl.mpart);
+  a.cpre = (double*)(ws + wl.cpre);
+  a.bounds = bounds;
+  a.vec = false;  // set by the launchers once the pointers are known
+  return a;
 }
 
 }  // namespace
 
 hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
-                      float* credit, float* m_used, hipStream_t s) {
-  prof_mark("ema", s);
-  hipLaunchKernelGGL(ema_kernel, dim3(d.units), dim3(kBlock), 0, s, d, seq_lens, u, credit, m_used,
-                     p->ema_lambda, p->ema_beta, p->mass_eps);
+                      float* credit, float* m_used, int32_t* bounds, char* ws, const WsLayout& wl,
+                      hipStream_t s) {
+  MsArgs a = make_args(p, d, seq_lens, ws, wl, bounds);
+  a.vec = d.t_stride % 4 == 0 && (((uintptr_t)u | (uintptr_t)credit | (uintptr_t)m_used) & 15) == 0;
+  const dim3 grid(a.n_chunks, d.units);
+  prof_mark("vc_sums", s);
+  hipLaunchKernelGGL(vc_sums_kernel, grid, dim3(kBlock), 0, s, a, u, (const float*)credit, p->mass_eps);
+  prof_mark("mass_ema", s);
+  hipLaunchKernelGGL(mass_ema_kernel, grid, dim3(kBlock), 0, s, a, u, credit, m_used, p->ema_lambda,
+                     p->ema_beta, p->mass_eps);
   return hipGetLastError();
 }
 
 hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq_lens,
-                          const float* m_used, int32_t* bounds, float* seg_mass, hipStream_t s) {
-  if (p->n_segments > kMaxSeg) return hipErrorInvalidValue;
-  prof_mark("segment", s);
-  hipLaunchKernelGGL(segment_kernel, dim3(d.units), dim3(kBlock), 0, s, d, seq_lens, m_used,
-                     p->n_segments, bounds, seg_mass);
+                          const float* m_used, int32_t* bounds, float* seg_mass, bool have_chunk_totals,
+                          char* ws, const WsLayout& wl, hipStream_t s) {
+  MsArgs a = make_args(p, d, seq_lens, ws, wl, bounds);
+  a.vec = d.t_stride % 4 == 0 && ((uintptr_t)m_used & 15) == 0;
+  const dim3 grid(a.n_chunks, d.units);
+  if (!have_chunk_totals) {
+    prof_mark("chunk_total", s);
+    hipLaunchKernelGGL(chunk_total_kernel, grid, dim3(kBlock), 0, s, a, m_used);
+  }
+  prof_mark("segment_scan", s);
+  hipLaunchKernelGGL(segment_scan_kernel, grid, dim3(kBlock), 0, s, a, m_used);
+  if (seg_mass) {
+    prof_mark("segment_finalize", s);
+    hipLaunchKernelGGL(segment_finalize_kernel, dim3(d.units), dim3(64), 0, s, a, seg_mass);
+  }
   return hipGetLastError();
 }
 

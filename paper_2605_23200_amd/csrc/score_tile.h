@@ -1,0 +1,139 @@
+// Building blocks of the scoring kernels: the MFMA tile s = K_tile . Q^T of one wave, the staging
+// of the query window in LDS, and the cross-lane sum over the queries of a token.
+// (Alg. 1 step 1: "aggregate usage of each cached position from the last W queries".)
+#ifndef AMS_SCORE_TILE_H
+#define AMS_SCORE_TILE_H
+
+#include "ams_internal.h"
+
+namespace ams {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+static constexpr float kNegInit = -3.0e38f;  // finite "minus infinity" for running maxima
+static constexpr int kThreads = 256;
+
+enum { MODE_MEAN = 0, MODE_LAST = 1, MODE_EXPECTED = 2 };
+
+struct ScoreArgs {
+  KvDev k;
+  Dims d;
+  const int32_t* seq_lens;
+  const char* q;
+  float2* part;  // [units][n_chunks][n_pad]  (max, sum) in the log2 domain
+  float4* fin;   // [units][n_pad]  (M, weight for u, weight for g, query is real)
+  float* u;
+  float* g;
+  int n_chunks, n_pad;
+  float c2;          // log2(e) / sqrt(D)
+  float inv_sqrt_d;  // 1 / sqrt(D)
+};
+
+template <bool BF16>
+struct Tr;
+template <>
+struct Tr<true> {
+  static constexpr int kRowBytes = 256, kQStride = 272, kAVecs = 8;
+};
+template <>
+struct Tr<false> {
+  static constexpr int kRowBytes = 512, kQStride = 528, kAVecs = 16;
+};
+
+// Query window of the unit -> LDS, rows padded against bank conflicts, rows >= N zero.
+template <bool BF16, int NB>
+__device__ __forceinline__ void load_q(const ScoreArgs& a, int l, int b, int h, char* qlds) {
+  constexpr int RB = Tr<BF16>::kRowBytes, QS = Tr<BF16>::kQStride, CPR = RB / 16;
+  const char* src = a.q + ((((int64_t)l * a.d.B + b) * a.d.H + h) * a.d.G) * (int64_t)a.d.W * RB;
+  for (int ch = threadIdx.x; ch < NB * 32 * CPR; ch += kThreads) {
+    const int n = ch / CPR, col = ch % CPR;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (n < a.d.N) v = *(const uint4*)(src + (int64_t)n * RB + col * 16);
+    *(uint4*)(qlds + n * QS + col * 16) = v;
+  }
+}
+
+// Lane (r = lane % 32, hf = lane / 32) reads the hf-th half of row t0 + r: one contiguous
+// 128-byte (bf16) or 256-byte (fp32) piece.  The contraction index is permuted the same way on
+// the query side, which leaves the dot products unchanged.
+template <bool BF16>
+__device__ __forceinline__ void load_a(const ScoreArgs& a, int l, int b, int h, int t0, int T,
+                                       int lane, uint4 (&av)[Tr<BF16>::kAVecs]) {
+  constexpr int NV = Tr<BF16>::kAVecs;
+  const int t = t0 + (lane & 31);
+  if (t < T) {
+    const uint4* p = (const uint4*)(kv_row(a.k, l, b, h, t) + (lane >> 5) * (Tr<BF16>::kRowBytes / 2));
+#pragma unroll
+    for (int i = 0; i < NV; ++i) av[i] = p[i];
+  } else {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) av[i] = make_uint4(0, 0, 0, 0);
+  }
+}
+
+// acc[nb][i] = s_raw[token 8*(i/4) + 4*hf + i%4][query nb*32 + lane%32]
+template <bool BF16, int NB>
+__device__ __forceinline__ void tile_mma(const uint4 (&av)[Tr<BF16>::kAVecs], const char* qlds,
+                                         int lane, floatx16 (&acc)[NB]) {
+  constexpr int QS = Tr<BF16>::kQStride;
+  const char* qb = qlds + (lane & 31) * QS + (lane >> 5) * (Tr<BF16>::kRowBytes / 2);
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[nb][i] = 0.f;
+  if constexpr (BF16) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8 A = __builtin_bit_cast(bf16x8, av[ks]);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const uint4 bv = *(const uint4*)(qb + nb * 32 * QS + ks * 16);
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, __builtin_bit_cast(bf16x8, bv), acc[nb], 0, 0, 0);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const float4 A = __builtin_bit_cast(float4, av[j]);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const float4 bv = *(const float4*)(qb + nb * 32 * QS + j * 16);
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(A.x, bv.x, acc[nb], 0, 0, 0);
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(A.y, bv.y, acc[nb], 0, 0, 0);
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(A.z, bv.z, acc[nb], 0, 0, 0);
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(A.w, bv.w, acc[nb], 0, 0, 0);
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ int acc_row(int i, int hf) { return 8 * (i >> 2) + 4 * hf + (i & 3); }
+
+// Sum of 16 per-lane values over the 32 lanes of a half wave, halving the number of live values
+// at every exchange.  Lane c ends up with the total of value index c >> 1.
+__device__ __forceinline__ float reduce16_over32(const float (&v)[16], int c) {
+  float w8[8], w4[4], w2[2];
+  const bool b4 = c & 16, b3 = c & 8, b2 = c & 4, b1 = c & 2;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float keep = b4 ? v[j + 8] : v[j], send = b4 ? v[j] : v[j + 8];
+    w8[j] = keep + __shfl_xor(send, 16);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float keep = b3 ? w8[j + 4] : w8[j], send = b3 ? w8[j] : w8[j + 4];
+    w4[j] = keep + __shfl_xor(send, 8);
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const float keep = b2 ? w4[j + 2] : w4[j], send = b2 ? w4[j] : w4[j + 2];
+    w2[j] = keep + __shfl_xor(send, 4);
+  }
+  const float keep = b1 ? w2[1] : w2[0], send = b1 ? w2[0] : w2[1];
+  const float w1 = keep + __shfl_xor(send, 2);
+  return w1 + __shfl_xor(w1, 1);
+}
+
+}  // namespace ams
+#endif

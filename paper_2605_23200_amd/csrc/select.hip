@@ -14,6 +14,73 @@ namespace {
 
 constexpr int kMaxSeg = 1024;
 
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// Quotas for S <= 64: lane i owns segment i.  Sums of masses run in index order over the active
+// lanes and every share is rem * M_i / sum, the same operations in the same order as plain C.
+__device__ __forceinline__ int quota_wave(int S, int bud, int q_min, const int32_t* bounds, const float* mass) {
+  const int lane = threadIdx.x;
+  const bool valid = lane < S;
+  const int len = valid ? bounds[lane + 1] - bounds[lane] : 0;
+  const double mass_d = valid ? (double)mass[lane] : 0.0;
+  const int nonempty = __popcll(__ballot(len > 0));
+  int floor_q = q_min;
+  if (wave_sum(min(floor_q, len)) > bud) floor_q = nonempty > 0 ? bud / nonempty : 0;
+  const int lo = min(floor_q, len);
+  const int room = len - lo;
+  bool active = room > 0;
+  int quo = lo;
+  int rem = bud - wave_sum(lo);
+  double raw = 0.0;
+  // proportional shares; a segment whose share reaches its room is filled and leaves the pool
+  for (;;) {
+    const uint64_t act = __ballot(active);
+    const int n_active = __popcll(act);
+    if (n_active == 0 || rem <= 0) break;
+    double msum = 0.0;
+    for (uint64_t m = act; m; m &= m - 1) msum += __shfl(mass_d, __ffsll((long long)m) - 1);
+    if (active) raw = msum > 0.0 ? (double)rem * mass_d / msum : (double)rem / (double)n_active;
+    const bool sat = active && raw >= (double)room;
+    if (!__ballot(sat)) break;
+    rem -= wave_sum(sat ? room : 0);
+    if (sat) {
+      quo = len;
+      active = false;
+    }
+  }
+  if (rem > 0) {
+    double frac = -1.0;
+    int fl_i = 0;
+    if (active) {
+      const double fl = floor(raw);
+      frac = raw - fl;
+      fl_i = (int)fl;
+      quo += fl_i;
+    }
+    int left = rem - wave_sum(fl_i);
+    // one extra each, largest fractional part first, equal parts by lower segment index
+    while (left > 0) {
+      const bool can = active && quo < len;
+      const uint64_t cm = __ballot(can);
+      if (!cm) break;
+      int rank = 0;
+      for (uint64_t m = cm; m; m &= m - 1) {
+        const int j = __ffsll((long long)m) - 1;
+        const double fj = __shfl(frac, j);
+        if (fj > frac || (fj == frac && j < lane)) ++rank;
+      }
+      const bool take = can && rank < left;
+      if (take) ++quo;
+      left -= __popcll(__ballot(take));
+    }
+  }
+  return quo;
+}
+
 __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_lens, int S, int budget,
                                                    int q_min, const int32_t* bounds_all,
                                                    const float* seg_mass_all, int32_t* quota_all,
@@ -28,6 +95,17 @@ __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_le
   const int32_t* bounds = bounds_all + (int64_t)unit * (S + 1);
   const float* mass = seg_mass_all + (int64_t)unit * S;
   const int bud = min(budget, T);
+  int32_t* quota = quota_all + (int64_t)unit * S;
+  int32_t* idx = idx_all + (int64_t)unit * budget;
+  // entries of idx beyond the kept count are -1
+  for (int j = bud + threadIdx.x; j < budget; j += 64) idx[j] = -1;
+  if (threadIdx.x == 0) n_kept_all[unit] = bud;
+  if (S <= 64) {
+    const int q = quota_wave(S, bud, q_min, bounds, mass);
+    if (threadIdx.x < S) quota[threadIdx.x] = q;
+    return;
+  }
+  // more than 64 segments: the same arithmetic, serially
   if (threadIdx.x == 0) {
     int nonempty = 0;
     for (int i = 0; i < S; ++i) {
@@ -47,7 +125,6 @@ __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_le
       rem -= lo;
       raw[i] = 0.0;
     }
-    // proportional shares; a segment whose share reaches its room is filled and leaves the pool
     for (;;) {
       int n_active = 0;
       double msum = 0.0;
@@ -82,13 +159,12 @@ __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_le
           given += (int)fl;
         }
       int left = rem - given;
-      // one extra each, largest fractional part first, equal parts by lower segment index;
-      // a served segment is marked with a negative part
+      // a served segment is marked with a negative part until the round is over
       while (left > 0) {
         int best = -1;
         for (int i = 0; i < S; ++i)
           if (active[i] && raw[i] >= 0.0 && quo[i] < len[i] && (best < 0 || raw[i] > raw[best])) best = i;
-        if (best < 0) {  // every segment served once: start another round
+        if (best < 0) {
           bool any = false;
           for (int i = 0; i < S; ++i)
             if (active[i] && raw[i] < 0.0) {
@@ -105,12 +181,7 @@ __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_le
     }
   }
   __syncthreads();
-  int32_t* quota = quota_all + (int64_t)unit * S;
   for (int i = threadIdx.x; i < S; i += 64) quota[i] = quo[i];
-  // entries of idx beyond the kept count are -1
-  int32_t* idx = idx_all + (int64_t)unit * budget;
-  for (int j = bud + threadIdx.x; j < budget; j += 64) idx[j] = -1;
-  if (threadIdx.x == 0) n_kept_all[unit] = bud;
 }
 
 // Order-preserving image of a score: larger float <-> larger unsigned; -0 and +0 coincide and

@@ -90,7 +90,7 @@ def test_ema_parity(oracle, T, lam, beta):
     pad = lambda a: np.pad(a, ((0, 0), (0, 5)), constant_values=9.0)
     u_d, c_d = to_dev(pad(u)), to_dev(pad(credit))
     m_d = torch.full((units, T + 5), 9.0, device=DEV)
-    B.ams_ema_update(p, to_dev(np.array([T], np.int32)), u_d, c_d, m_d)
+    B.ams_ema_update(p, to_dev(np.array([T], np.int32)), u_d, c_d, m_d, workspace(p))
     torch.cuda.synchronize()
     for i in range(units):
         m_used, c_new = oracle.ema(oracle.mass(u[i], 1e-6), credit[i], lam, beta)
@@ -104,7 +104,7 @@ def _segment(m, S, T):
     p = _vec_params(units, T, S=S)
     bounds = torch.zeros((units, S + 1), dtype=torch.int32, device=DEV)
     seg_mass = torch.zeros((units, S), device=DEV)
-    B.ams_mass_segment(p, to_dev(np.array([T], np.int32)), to_dev(m), bounds, seg_mass)
+    B.ams_mass_segment(p, to_dev(np.array([T], np.int32)), to_dev(m), bounds, seg_mass, workspace(p))
     torch.cuda.synchronize()
     return to_host(bounds), to_host(seg_mass)
 
