@@ -41,7 +41,7 @@ WsLayout ws_layout(const ams_params* p) {
   w.kbar = o;       o += align256(units * w.n_chunks * (size_t)p->head_dim * sizeof(double));
   w.fused = o;      o += align256(fused_score_ws_bytes((int64_t)units, p->t_max, w.n_pad, p->batch));
   w.n_chunks4k = div_up(p->t_max, kChunk);
-  w.vc_part = o;    o += align256(units * w.n_chunks4k * 2 * sizeof(double));
+  w.vc_part = o;    o += align256(units * (size_t)w.n_chunks * 2 * sizeof(double));  // n_chunks >= n_chunks4k
   w.mpart = o;      o += align256(units * w.n_chunks4k * sizeof(double));
   w.cpre = o;       o += align256(units * (size_t)(p->n_segments + 1) * sizeof(double));
   w.total = o;
@@ -212,8 +212,8 @@ int ams_score(const ams_params* p, const ams_kv_view* src, const int32_t* seq_le
     return AMS_ERR_INVALID_ARG;
   const WsLayout wl = ws_layout(p);
   if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
-  return hip_status(launch_score(p, make_dims(p), make_kv(p, src, src->k), seq_lens, q, u, g, (char*)ws,
-                                 wl, (hipStream_t)stream), (hipStream_t)stream);
+  return hip_status(launch_score(p, make_dims(p), make_kv(p, src, src->k), seq_lens, q, u, g, nullptr, nullptr,
+                                 (char*)ws, wl, (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u, float* credit,
@@ -224,7 +224,7 @@ int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u,
   const WsLayout wl = ws_layout(p);
   if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
   return hip_status(launch_ema(p, make_dims(p), seq_lens, u, credit, m_used, (int32_t*)((char*)ws + wl.bounds),
-                               (char*)ws, wl, (hipStream_t)stream), (hipStream_t)stream);
+                               false, (char*)ws, wl, (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* m_used,
@@ -246,8 +246,9 @@ int ams_select(const ams_params* p, const int32_t* seq_lens, const float* g, con
   const int rc = check_params(p);
   if (rc) return rc;
   if (!seq_lens || !g || !bounds || !seg_mass || !quota || !idx || !n_kept) return AMS_ERR_INVALID_ARG;
-  return hip_status(launch_select(p, make_dims(p), seq_lens, g, bounds, seg_mass, quota, idx, n_kept,
-                                  (hipStream_t)stream), (hipStream_t)stream);
+  // seg_mass is only read here; the launcher's non-const pointer serves the fused path
+  return hip_status(launch_select(p, make_dims(p), seq_lens, g, bounds, const_cast<float*>(seg_mass), quota, idx,
+                                  n_kept, nullptr, nullptr, 0, (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_compact(const ams_params* p, const ams_kv_view* src, const int32_t* idx, const int32_t* n_kept,
@@ -291,12 +292,15 @@ int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t
   float* seg_mass = (float*)(w + wl.seg_mass);
   int32_t* quota = (int32_t*)(w + wl.quota);
   hipError_t e;
-  if ((e = launch_score(p, d, make_kv(p, src, src->k), seq_lens, q, u, g, w, wl, s)) != hipSuccess)
+  bool have_vc = false;
+  if ((e = launch_score(p, d, make_kv(p, src, src->k), seq_lens, q, u, g, credit, &have_vc, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;
-  if ((e = launch_ema(p, d, seq_lens, u, credit, m_used, bounds, w, wl, s)) != hipSuccess) return AMS_ERR_HIP;
-  if ((e = launch_segment(p, d, seq_lens, m_used, bounds, seg_mass, true, w, wl, s)) != hipSuccess)
+  if ((e = launch_ema(p, d, seq_lens, u, credit, m_used, bounds, have_vc, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;
-  if ((e = launch_select(p, d, seq_lens, g, bounds, seg_mass, quota, idx, n_kept, s)) != hipSuccess)
+  if ((e = launch_segment(p, d, seq_lens, m_used, bounds, nullptr, true, w, wl, s)) != hipSuccess)
+    return AMS_ERR_HIP;
+  if ((e = launch_select(p, d, seq_lens, g, bounds, seg_mass, quota, idx, n_kept, (const double*)(w + wl.cpre),
+                         (const double*)(w + wl.mpart), wl.n_chunks4k, s)) != hipSuccess)
     return AMS_ERR_HIP;
   if ((e = launch_compact(p, d, make_kv(p, src, src->k), make_kv(p, src, src->v), make_kv(p, dst, dst->k),
                           make_kv(p, dst, dst->v), idx, n_kept, credit, credit_dst, s)) != hipSuccess)

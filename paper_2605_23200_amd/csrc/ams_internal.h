@@ -63,8 +63,11 @@ WsLayout ws_layout(const ams_params* p);
 void prof_mark(const char* label, hipStream_t s);
 
 // ---- launchers (each returns hipGetLastError() of its launches) ----
+// credit (optional) and vc_emitted (optional): when vc_emitted is given and comes back true, the
+// per-chunk sums that launch_ema needs are already in the workspace (1024-token chunks).
 hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
-                        const void* q, float* u, float* g, char* ws, const WsLayout& wl, hipStream_t s);
+                        const void* q, float* u, float* g, const float* credit, bool* vc_emitted, char* ws,
+                        const WsLayout& wl, hipStream_t s);
 size_t fused_score_ws_bytes(int64_t units, int t_max, int n_pad, int batch);
 hipError_t launch_score_onepass(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
                                 const void* q, float* u, float* g, char* ws, const WsLayout& wl,
@@ -72,14 +75,17 @@ hipError_t launch_score_onepass(const ams_params* p, const Dims& d, const KvDev&
 // launch_ema also leaves the chunk totals of m_used in the workspace and resets `bounds` (scratch
 // or the caller's) for a following launch_segment(have_chunk_totals = true).
 hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
-                      float* credit, float* m_used, int32_t* bounds, char* ws, const WsLayout& wl,
-                      hipStream_t s);
+                      float* credit, float* m_used, int32_t* bounds, bool have_vc_sums, char* ws,
+                      const WsLayout& wl, hipStream_t s);
 hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq_lens,
                           const float* m_used, int32_t* bounds, float* seg_mass, bool have_chunk_totals,
                           char* ws, const WsLayout& wl, hipStream_t s);
+// cpre / mpart (optional, with n_chunks): the prefix-sum kernel's raw output; when given, seg_mass is
+// WRITTEN by the quota kernel instead of read.
 hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* g,
-                         const int32_t* bounds, const float* seg_mass, int32_t* quota, int32_t* idx,
-                         int32_t* n_kept, hipStream_t s);
+                         const int32_t* bounds, float* seg_mass, int32_t* quota, int32_t* idx,
+                         int32_t* n_kept, const double* cpre, const double* mpart, int n_chunks,
+                         hipStream_t s);
 hipError_t launch_compact(const ams_params* p, const Dims& d, const KvDev& ks, const KvDev& vs,
                           const KvDev& kd, const KvDev& vd, const int32_t* idx, const int32_t* n_kept,
                           const float* credit_src, float* credit_dst, hipStream_t s);

@@ -24,9 +24,10 @@
 namespace ams {
 namespace {
 
-constexpr int kBlock = 1024;
+constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / 64;
-constexpr int kPer = 4;
+constexpr int kPer = 16;  // consecutive positions per thread
+constexpr int kMaxSegments = 1024;
 static_assert(kBlock * kPer == kChunk, "one workgroup covers one chunk");
 
 // Sum over the workgroup, same value in every thread, fixed order.
@@ -42,7 +43,7 @@ __device__ __forceinline__ double block_sum(double v, double* sm) {
   return t;
 }
 
-// In-chunk inclusive prefix of the four consecutive positions each thread owns, and the chunk
+// In-chunk inclusive prefix of the kPer consecutive positions each thread owns, and the chunk
 // total (= prefix of the very last position).  The association is fixed by the thread layout.
 __device__ __forceinline__ void chunk_scan(const float (&x)[kPer], double (&p)[kPer], double& total,
                                            double* wave_tot, double* bcast) {
@@ -72,19 +73,59 @@ __device__ __forceinline__ void chunk_scan(const float (&x)[kPer], double (&p)[k
   total = *bcast;
 }
 
-// Four consecutive fp32 of a row: one 16-byte access when the row allows it.
-__device__ __forceinline__ void load4(const float* row, int j0, int T, bool vec, float (&x)[kPer], float fill) {
+// Sum of p[0..n) in index order (bit-reproducible), same value in every thread of the workgroup.
+// One wave fetches 64 entries at a time in parallel and adds them up through lane broadcasts, so
+// the cost is one memory latency per 64 entries instead of one per entry.
+__device__ __forceinline__ double2 ordered_sum2(const double2* p, int n, double2* sm) {
+  if (threadIdx.x < 64) {
+    double2 acc = make_double2(0.0, 0.0);
+    for (int base = 0; base < n; base += 64) {
+      const int k = min(64, n - base);
+      double2 v = make_double2(0.0, 0.0);
+      if ((int)threadIdx.x < k) v = p[base + threadIdx.x];
+      for (int j = 0; j < k; ++j) {
+        acc.x += __shfl(v.x, j);
+        acc.y += __shfl(v.y, j);
+      }
+    }
+    if (threadIdx.x == 0) *sm = acc;
+  }
+  __syncthreads();
+  return *sm;
+}
+__device__ __forceinline__ double ordered_sum(const double* p, int n, double2* sm) {
+  if (threadIdx.x < 64) {
+    double acc = 0.0;
+    for (int base = 0; base < n; base += 64) {
+      const int k = min(64, n - base);
+      double v = 0.0;
+      if ((int)threadIdx.x < k) v = p[base + threadIdx.x];
+      for (int j = 0; j < k; ++j) acc += __shfl(v, j);
+    }
+    if (threadIdx.x == 0) sm->x = acc;
+  }
+  __syncthreads();
+  return sm->x;
+}
+
+// kPer consecutive fp32 of a row: 16-byte accesses when the row allows it.
+__device__ __forceinline__ void load_run(const float* row, int j0, int T, bool vec, float (&x)[kPer], float fill) {
   if (vec && j0 + kPer <= T) {
-    const float4 v = *reinterpret_cast<const float4*>(row + j0);
-    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+#pragma unroll
+    for (int q = 0; q < kPer / 4; ++q) {
+      const float4 v = *reinterpret_cast<const float4*>(row + j0 + 4 * q);
+      x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
+    }
   } else {
 #pragma unroll
     for (int i = 0; i < kPer; ++i) x[i] = (j0 + i < T) ? row[j0 + i] : fill;
   }
 }
-__device__ __forceinline__ void store4(float* row, int j0, int T, bool vec, const float (&x)[kPer]) {
+__device__ __forceinline__ void store_run(float* row, int j0, int T, bool vec, const float (&x)[kPer]) {
   if (vec && j0 + kPer <= T) {
-    *reinterpret_cast<float4*>(row + j0) = make_float4(x[0], x[1], x[2], x[3]);
+#pragma unroll
+    for (int q = 0; q < kPer / 4; ++q)
+      *reinterpret_cast<float4*>(row + j0 + 4 * q) = make_float4(x[4 * q], x[4 * q + 1], x[4 * q + 2], x[4 * q + 3]);
   } else {
 #pragma unroll
     for (int i = 0; i < kPer; ++i)
@@ -97,7 +138,8 @@ struct MsArgs {
   const int32_t* seq_lens;
   int n_chunks;      // chunks per unit (stride of the per-chunk arrays)
   int S;
-  double2* vc_part;  // [units][n_chunks]  (sum of max(u,0)+eps, sum of old credit)
+  double2* vc_part;  // [units][vc_stride] (sum of max(u,0)+eps, sum of old credit) per vc_tokens positions
+  int vc_stride, vc_tokens;
   double* mpart;     // [units][n_chunks]  chunk totals of m_used
   double* cpre;      // [units][S+1]       prefix at the cuts (negative = threshold never reached)
   int32_t* bounds;   // [units][S+1]
@@ -126,8 +168,8 @@ __global__ __launch_bounds__(kBlock) void vc_sums_kernel(MsArgs a, const float* 
   const float* credit = credit_all + (int64_t)unit * a.d.t_stride;
   double v = 0.0, c = 0.0;
   float ux[kPer], cx[kPer];
-  load4(u, j0, T, a.vec, ux, 0.f);
-  load4(credit, j0, T, a.vec, cx, 0.f);
+  load_run(u, j0, T, a.vec, ux, 0.f);
+  load_run(credit, j0, T, a.vec, cx, 0.f);
 #pragma unroll
   for (int i = 0; i < kPer; ++i)
     if (j0 + i < T) {
@@ -136,7 +178,7 @@ __global__ __launch_bounds__(kBlock) void vc_sums_kernel(MsArgs a, const float* 
     }
   v = block_sum(v, sm);
   c = block_sum(c, sm);
-  if (threadIdx.x == 0) a.vc_part[(int64_t)unit * a.n_chunks + chunk] = make_double2(v, c);
+  if (threadIdx.x == 0) a.vc_part[(int64_t)unit * a.vc_stride + chunk] = make_double2(v, c);
 }
 
 __global__ __launch_bounds__(kBlock) void mass_ema_kernel(MsArgs a, const float* u_all, float* credit_all,
@@ -150,22 +192,19 @@ __global__ __launch_bounds__(kBlock) void mass_ema_kernel(MsArgs a, const float*
   const int T = a.seq_lens[b];
   if (chunk * kChunk >= T) return;
   if (chunk == 0) init_cuts(a, unit, T);
-  const int nch = (T + kChunk - 1) / kChunk;
-  double Z = 0.0, c_old = 0.0;
-  for (int c = 0; c < nch; ++c) {
-    const double2 p = a.vc_part[(int64_t)unit * a.n_chunks + c];
-    Z += p.x;
-    c_old += p.y;
-  }
-  const double lam = (double)lambda, bet = (double)beta, eps = (double)eps_f;
-  const double inv_z = 1.0 / Z, inv_csum = 1.0 / (lam * c_old + (1.0 - lam));
+  __shared__ double2 sums;
   const float* u = u_all + (int64_t)unit * a.d.t_stride;
   float* credit = credit_all + (int64_t)unit * a.d.t_stride;
   float* m_used = m_used_all + (int64_t)unit * a.d.t_stride;
   const int j0 = chunk * kChunk + threadIdx.x * kPer;
   float mu[kPer], ux[kPer], cx[kPer];
-  load4(u, j0, T, a.vec, ux, 0.f);
-  load4(credit, j0, T, a.vec, cx, 0.f);
+  load_run(u, j0, T, a.vec, ux, 0.f);  // in flight while the normalisers are summed
+  load_run(credit, j0, T, a.vec, cx, 0.f);
+  const int nvc = (T + a.vc_tokens - 1) / a.vc_tokens;
+  const double2 zc = ordered_sum2(a.vc_part + (int64_t)unit * a.vc_stride, nvc, &sums);
+  const double Z = zc.x, c_old = zc.y;
+  const double lam = (double)lambda, bet = (double)beta, eps = (double)eps_f;
+  const double inv_z = 1.0 / Z, inv_csum = 1.0 / (lam * c_old + (1.0 - lam));
 #pragma unroll
   for (int i = 0; i < kPer; ++i) {
     mu[i] = 0.f;
@@ -180,8 +219,8 @@ __global__ __launch_bounds__(kBlock) void mass_ema_kernel(MsArgs a, const float*
       cx[i] = cn;
     }
   }
-  store4(credit, j0, T, a.vec, cx);
-  store4(m_used, j0, T, a.vec, mu);
+  store_run(credit, j0, T, a.vec, cx);
+  store_run(m_used, j0, T, a.vec, mu);
   double p[kPer], total;
   chunk_scan(mu, p, total, wave_tot, &bcast);
   if (threadIdx.x == 0) a.mpart[(int64_t)unit * a.n_chunks + chunk] = total;
@@ -199,18 +238,19 @@ __global__ __launch_bounds__(kBlock) void chunk_total_kernel(MsArgs a, const flo
   const float* m = m_all + (int64_t)unit * a.d.t_stride;
   const int j0 = chunk * kChunk + threadIdx.x * kPer;
   float x[kPer];
-  load4(m, j0, T, a.vec, x, 0.f);
+  load_run(m, j0, T, a.vec, x, 0.f);
   double p[kPer], total;
   chunk_scan(x, p, total, wave_tot, &bcast);
   if (threadIdx.x == 0) a.mpart[(int64_t)unit * a.n_chunks + chunk] = total;
 }
 
-// Number of thresholds k/S, k = 1..S-1, that are <= c.
-__device__ __forceinline__ int thresholds_reached(double c, int S) {
+// Number of thresholds k/S, k = 1..S-1, that are <= c.  thr[k] holds (double)k / (double)S, the
+// exact value the comparison is defined with; the table keeps divisions out of the per-thread path.
+__device__ __forceinline__ int thresholds_reached(double c, int S, const double* thr) {
   int f = (int)floor(c * (double)S);
   f = max(0, min(S - 1, f));
-  while (f < S - 1 && c >= (double)(f + 1) / (double)S) ++f;
-  while (f > 0 && c < (double)f / (double)S) --f;
+  while (f < S - 1 && c >= thr[f + 1]) ++f;
+  while (f > 0 && c < thr[f]) --f;
   return f;
 }
 
@@ -218,35 +258,37 @@ __global__ __launch_bounds__(kBlock) void segment_scan_kernel(MsArgs a, const fl
   __shared__ double wave_tot[kWaves];
   __shared__ double bcast;
   __shared__ double ends[kBlock];
+  __shared__ double thr[kMaxSegments + 1];
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T = a.seq_lens[b];
   if (chunk * kChunk >= T) return;
   const float* m = m_all + (int64_t)unit * a.d.t_stride;
-  double C = 0.0;  // prefix of everything before this chunk
-  for (int c = 0; c < chunk; ++c) C += a.mpart[(int64_t)unit * a.n_chunks + c];
+  __shared__ double2 sums;
+  for (int k = threadIdx.x; k <= a.S; k += kBlock) thr[k] = (double)k / (double)a.S;
   const int j0 = chunk * kChunk + threadIdx.x * kPer;
   float x[kPer];
-  load4(m, j0, T, a.vec, x, 0.f);
+  load_run(m, j0, T, a.vec, x, 0.f);
+  const double C = ordered_sum(a.mpart + (int64_t)unit * a.n_chunks, chunk, &sums);  // prefix before this chunk
   double p[kPer], total;
   chunk_scan(x, p, total, wave_tot, &bcast);
   ends[threadIdx.x] = C + p[kPer - 1];
   __syncthreads();
   const double prev_end = threadIdx.x > 0 ? ends[threadIdx.x - 1] : C;
-  int f_prev = thresholds_reached(prev_end, a.S);
+  int f_prev = thresholds_reached(prev_end, a.S, thr);
   int32_t* bounds = a.bounds + (int64_t)unit * (a.S + 1);
   double* cpre = a.cpre + (int64_t)unit * (a.S + 1);
   // most threads see no threshold between their neighbour's prefix and their own largest one
   double p_max = p[0];
 #pragma unroll
   for (int i = 1; i < kPer; ++i) p_max = fmax(p_max, p[i]);
-  if (thresholds_reached(C + p_max, a.S) <= f_prev) return;
+  if (thresholds_reached(C + p_max, a.S, thr) <= f_prev) return;
 #pragma unroll
   for (int i = 0; i < kPer; ++i) {
     if (j0 + i < T) {
       const double P = C + p[i];
-      const int f_cur = thresholds_reached(P, a.S);
+      const int f_cur = thresholds_reached(P, a.S, thr);
       for (int k = f_prev + 1; k <= f_cur; ++k) {  // position j0+i is the first to reach k/S
         atomicMin(&bounds[k], j0 + i + 1);
         cpre[k] = P;
@@ -280,6 +322,8 @@ MsArgs make_args(const ams_params* p, const Dims& d, const int32_t* seq_lens, ch
   a.n_chunks = wl.n_chunks4k;
   a.S = p->n_segments;
   a.vc_part = (double2*)(ws + wl.vc_part);
+  a.vc_stride = wl.n_chunks;
+  a.vc_tokens = kChunk;
   a.mpart = (double*)(ws + wl.mpart);
   a.cpre = (double*)(ws + wl.cpre);
   a.bounds = bounds;
@@ -290,13 +334,17 @@ MsArgs make_args(const ams_params* p, const Dims& d, const int32_t* seq_lens, ch
 }  // namespace
 
 hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
-                      float* credit, float* m_used, int32_t* bounds, char* ws, const WsLayout& wl,
-                      hipStream_t s) {
+                      float* credit, float* m_used, int32_t* bounds, bool have_vc_sums, char* ws,
+                      const WsLayout& wl, hipStream_t s) {
   MsArgs a = make_args(p, d, seq_lens, ws, wl, bounds);
   a.vec = d.t_stride % 4 == 0 && (((uintptr_t)u | (uintptr_t)credit | (uintptr_t)m_used) & 15) == 0;
   const dim3 grid(a.n_chunks, d.units);
-  prof_mark("vc_sums", s);
-  hipLaunchKernelGGL(vc_sums_kernel, grid, dim3(kBlock), 0, s, a, u, (const float*)credit, p->mass_eps);
+  if (have_vc_sums) {
+    a.vc_tokens = kScoreChunk;  // left by the scorer's second sweep
+  } else {
+    prof_mark("vc_sums", s);
+    hipLaunchKernelGGL(vc_sums_kernel, grid, dim3(kBlock), 0, s, a, u, (const float*)credit, p->mass_eps);
+  }
   prof_mark("mass_ema", s);
   hipLaunchKernelGGL(mass_ema_kernel, grid, dim3(kBlock), 0, s, a, u, credit, m_used, p->ema_lambda,
                      p->ema_beta, p->mass_eps);

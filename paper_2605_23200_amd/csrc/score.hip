@@ -16,10 +16,20 @@ namespace ams {
 namespace {
 
 // ---------------------------------------------------------------------------------------------
+// Both sweeps walk a 1024-token chunk in 32-token blocks per wave.  The keys of the next block are
+// requested before the current block is multiplied (two register buffers, used alternately), and
+// the query columns are processed in groups of kGroup<NB> blocks of 32 so that only that many
+// accumulator tiles are live at a time: more bytes in flight per wave at the same occupancy.
+// ---------------------------------------------------------------------------------------------
+template <int NB>
+constexpr int kGroup = (NB % 2 == 0 && NB >= 4) ? NB / 2 : NB;
+
+// ---------------------------------------------------------------------------------------------
 // Sweep 1: per chunk, per query (max, sum exp2) of the scaled logits.
 // ---------------------------------------------------------------------------------------------
 template <bool BF16, int NB>
-__global__ __launch_bounds__(kThreads) void score_stats_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? 3 : 2) void score_stats_kernel(ScoreArgs a) {
+  constexpr int NG = kGroup<NB>, QS = Tr<BF16>::kQStride, NBLK = kScoreChunk / 128;
   extern __shared__ __align__(16) char qlds[];
   __shared__ float2 xch[4][NB * 32];
   const int unit = blockIdx.y, chunk = blockIdx.x;
@@ -28,39 +38,56 @@ __global__ __launch_bounds__(kThreads) void score_stats_kernel(ScoreArgs a) {
   const int T = a.seq_lens[b];
   const int c0 = chunk * kScoreChunk;
   if (c0 >= T) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
+  uint4 av0[Tr<BF16>::kAVecs], av1[Tr<BF16>::kAVecs];
+  if (c0 + wave * 32 < T) load_a<BF16>(a, l, b, h, c0 + wave * 32, T, lane, av0);
   load_q<BF16, NB>(a, l, b, h, qlds);
   __syncthreads();
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
   float m[NB], z[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     m[nb] = kNegInit;
     z[nb] = 0.f;
   }
-  uint4 av[Tr<BF16>::kAVecs];
-  floatx16 acc[NB];
-  for (int blk = 0; blk < kScoreChunk / 128; ++blk) {
+  const float c2 = a.c2;
+  auto block = [&](const uint4 (&av)[Tr<BF16>::kAVecs], int t0) __attribute__((always_inline)) {
+    const bool ragged = t0 + 32 > T;
+    // the query fragments are re-read from LDS for every block: keeping them in registers across
+    // blocks would cost more registers than the reads cost time, so their address is made opaque
+    int qoff = 0;
+    asm volatile("" : "+s"(qoff));
+#pragma unroll
+    for (int g0 = 0; g0 < NB; g0 += NG) {
+      floatx16 acc[NG];
+      tile_mma<BF16, NG>(av, qlds + qoff + g0 * 32 * QS, lane, acc);
+#pragma unroll
+      for (int k = 0; k < NG; ++k) {
+        const int nb = g0 + k;
+        if (ragged) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[k][i] = (t0 + acc_row(i, hf) >= T) ? -INFINITY : acc[k][i];
+        }
+        float mr = acc[k][0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mr = fmaxf(mr, acc[k][i]);
+        const float mx = fmaxf(m[nb], mr * c2);  // c2 > 0: the maximum commutes with the scale
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[k][i], c2, -mx));
+        z[nb] = __builtin_fmaf(z[nb], __builtin_amdgcn_exp2f(m[nb] - mx), sum);
+        m[nb] = mx;
+      }
+    }
+  };
+#pragma unroll 1
+  for (int blk = 0; blk < NBLK; blk += 2) {
     const int t0 = c0 + (blk * 4 + wave) * 32;
     if (t0 >= T) break;
-    load_a<BF16>(a, l, b, h, t0, T, lane, av);
-    tile_mma<BF16, NB>(av, qlds, lane, acc);
-    const bool ragged = t0 + 32 > T;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      float x[16];
-      float mx = m[nb];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        x[i] = acc[nb][i] * a.c2;
-        if (ragged && t0 + acc_row(i, hf) >= T) x[i] = -INFINITY;
-        mx = fmaxf(mx, x[i]);
-      }
-      float s = 0.f;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s += __builtin_amdgcn_exp2f(x[i] - mx);
-      z[nb] = z[nb] * __builtin_amdgcn_exp2f(m[nb] - mx) + s;
-      m[nb] = mx;
-    }
+    if (t0 + 128 < T) load_a<BF16>(a, l, b, h, t0 + 128, T, lane, av1);
+    block(av0, t0);
+    if (t0 + 128 >= T) break;
+    if (blk + 2 < NBLK && t0 + 256 < T) load_a<BF16>(a, l, b, h, t0 + 256, T, lane, av0);
+    block(av1, t0 + 128);
   }
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
@@ -83,22 +110,40 @@ __global__ __launch_bounds__(kThreads) void score_stats_kernel(ScoreArgs a) {
   }
 }
 
-// Chunks merged in ascending order: M_n, and the per-query weights of the column sums.
-__global__ void score_reduce_kernel(ScoreArgs a) {
+// Chunk statistics merged per query: the 1024 threads split into (query, contiguous range of
+// chunks) pairs, the ranges are then combined in ascending order (fixed association) -> M_n and
+// the per-query weights of the column sums.
+constexpr int kReduceThreads = 1024;
+__global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs a) {
+  __shared__ float pm[kReduceThreads];
+  __shared__ double pz[kReduceThreads];
   const int unit = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T = a.seq_lens[b];
   const int nch = (T + kScoreChunk - 1) / kScoreChunk;
-  for (int n = threadIdx.x; n < a.n_pad; n += blockDim.x) {
+  const int parts = kReduceThreads / a.n_pad;
+  const int n = threadIdx.x % a.n_pad, part = threadIdx.x / a.n_pad;
+  if (part < parts) {
+    const int per = (nch + parts - 1) / parts;
+    const int c0 = part * per, c1 = min(nch, c0 + per);
     const float2* p = a.part + (int64_t)unit * a.n_chunks * a.n_pad + n;
     float M = kNegInit;
-    for (int c = 0; c < nch; ++c) M = fmaxf(M, p[(int64_t)c * a.n_pad].x);
+    for (int c = c0; c < c1; ++c) M = fmaxf(M, p[(int64_t)c * a.n_pad].x);
     double Z = 0.0;
-    for (int c = 0; c < nch; ++c) {
+    for (int c = c0; c < c1; ++c) {
       const float2 s = p[(int64_t)c * a.n_pad];
       Z += (double)s.y * (double)__builtin_amdgcn_exp2f(s.x - M);
     }
+    pm[threadIdx.x] = M;
+    pz[threadIdx.x] = Z;
+  }
+  __syncthreads();
+  if (threadIdx.x < a.n_pad) {
+    float M = kNegInit;
+    for (int q = 0; q < parts; ++q) M = fmaxf(M, pm[q * a.n_pad + n]);
+    double Z = 0.0;
+    for (int q = 0; q < parts; ++q) Z += pz[q * a.n_pad + n] * (double)__builtin_amdgcn_exp2f(pm[q * a.n_pad + n] - M);
     const bool real = n < a.d.N;
     const bool newest = real && (n % a.d.W) == a.d.W - 1;
     float4 f;
@@ -114,7 +159,10 @@ __global__ void score_reduce_kernel(ScoreArgs a) {
 // Sweep 2: u[t] = sum_n exp2(x[n][t] - M_n) / (N Z_n), and g for the softmax- or moment-based scorers.
 // ---------------------------------------------------------------------------------------------
 template <bool BF16, int NB, int MODE>
-__global__ __launch_bounds__(kThreads) void score_usage_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? 3 : 2) void score_usage_kernel(ScoreArgs a) {
+  // the moment-based scorer needs all N logits of a token twice: keep every column block live
+  constexpr int NG = (MODE == MODE_EXPECTED) ? NB : kGroup<NB>;
+  constexpr int QS = Tr<BF16>::kQStride, NBLK = kScoreChunk / 128;
   extern __shared__ __align__(16) char qlds[];
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
@@ -122,58 +170,105 @@ __global__ __launch_bounds__(kThreads) void score_usage_kernel(ScoreArgs a) {
   const int T = a.seq_lens[b];
   const int c0 = chunk * kScoreChunk;
   if (c0 >= T) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5, c = lane & 31;
+  uint4 av0[Tr<BF16>::kAVecs], av1[Tr<BF16>::kAVecs];
+  if (c0 + wave * 32 < T) load_a<BF16>(a, l, b, h, c0 + wave * 32, T, lane, av0);
   load_q<BF16, NB>(a, l, b, h, qlds);
   __syncthreads();
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5, c = lane & 31;
   float4 f[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) f[nb] = a.fin[(int64_t)unit * a.n_pad + nb * 32 + c];
   float* u_row = a.u + (int64_t)unit * a.d.t_stride;
   float* g_row = a.g ? a.g + (int64_t)unit * a.d.t_stride : nullptr;
-  const float inv_n = 1.f / (float)a.d.N;
-  uint4 av[Tr<BF16>::kAVecs];
-  floatx16 acc[NB];
-  for (int blk = 0; blk < kScoreChunk / 128; ++blk) {
-    const int t0 = c0 + (blk * 4 + wave) * 32;
-    if (t0 >= T) break;
-    load_a<BF16>(a, l, b, h, t0, T, lane, av);
-    tile_mma<BF16, NB>(av, qlds, lane, acc);
+  const float inv_n = 1.f / (float)a.d.N, c2 = a.c2;
+  const float* c_row = a.credit ? a.credit + (int64_t)unit * a.d.t_stride : nullptr;
+  float v_part = 0.f;  // this lane's share of sum(max(u,0)+eps): at most 8 terms
+  auto block = [&](const uint4 (&av)[Tr<BF16>::kAVecs], int t0) __attribute__((always_inline)) {
     float pu[16], pg[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) pu[i] = pg[i] = 0.f;
+    float rg = 0.f;
+    int qoff = 0;  // see the first sweep: the query fragments are re-read per block on purpose
+    asm volatile("" : "+s"(qoff));
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int g0 = 0; g0 < NB; g0 += NG) {
+      floatx16 acc[NG];
+      tile_mma<BF16, NG>(av, qlds + qoff + g0 * 32 * QS, lane, acc);
+      if (MODE == MODE_EXPECTED) {
+        // mean and centred second moment of the N logits of each token (padded queries add exact zeros)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float e = __builtin_amdgcn_exp2f(acc[nb][i] * a.c2 - f[nb].x);
-        pu[i] += f[nb].y * e;
-        if (MODE == MODE_LAST) pg[i] += f[nb].z * e;
-        if (MODE == MODE_EXPECTED) pg[i] += acc[nb][i] * a.inv_sqrt_d;  // padded queries add exact zeros
-      }
-    const float ru = reduce16_over32(pu, c);
-    float rg = ru;
-    if (MODE == MODE_LAST) rg = reduce16_over32(pg, c);
-    if (MODE == MODE_EXPECTED) {
-      // mean and centred second moment of the N logits of each token
-      const float mean_mine = reduce16_over32(pg, c) * inv_n;
-      float pv[16];
+        for (int k = 0; k < NG; ++k)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float mean_i = __shfl(mean_mine, 2 * i + 32 * hf);
-        float s2 = 0.f;
+          for (int i = 0; i < 16; ++i) pg[i] += acc[k][i] * a.inv_sqrt_d;
+        const float mean_mine = reduce16_over32(pg, c) * inv_n;
+        float pv[16];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-          const float dlt = acc[nb][i] * a.inv_sqrt_d - mean_i;
-          s2 += f[nb].w * dlt * dlt;
+        for (int i = 0; i < 16; ++i) {
+          const float mean_i = __shfl(mean_mine, 2 * i + 32 * hf);
+          float s2 = 0.f;
+#pragma unroll
+          for (int k = 0; k < NG; ++k) {
+            const float dlt = acc[k][i] * a.inv_sqrt_d - mean_i;
+            s2 += f[g0 + k].w * dlt * dlt;
+          }
+          pv[i] = s2;
         }
-        pv[i] = s2;
+        rg = mean_mine + 0.5f * reduce16_over32(pv, c) * inv_n;
       }
-      rg = mean_mine + 0.5f * reduce16_over32(pv, c) * inv_n;
+#pragma unroll
+      for (int k = 0; k < NG; ++k) {
+        const int nb = g0 + k;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[k][i], c2, -f[nb].x));
+          pu[i] = __builtin_fmaf(f[nb].y, e, pu[i]);
+          if (MODE == MODE_LAST) pg[i] = __builtin_fmaf(f[nb].z, e, pg[i]);
+        }
+      }
     }
+    const float ru = reduce16_over32(pu, c);
+    if (MODE == MODE_MEAN) rg = ru;
+    if (MODE == MODE_LAST) rg = reduce16_over32(pg, c);
     const int t = t0 + acc_row(c >> 1, hf);
     if ((c & 1) == 0 && t < T) {
       u_row[t] = ru;
       if (g_row) g_row[t] = rg;
+      v_part += fmaxf(ru, 0.f) + a.eps;
+    }
+  };
+#pragma unroll 1
+  for (int blk = 0; blk < NBLK; blk += 2) {
+    const int t0 = c0 + (blk * 4 + wave) * 32;
+    if (t0 >= T) break;
+    if (t0 + 128 < T) load_a<BF16>(a, l, b, h, t0 + 128, T, lane, av1);
+    block(av0, t0);
+    if (t0 + 128 >= T) break;
+    if (blk + 2 < NBLK && t0 + 256 < T) load_a<BF16>(a, l, b, h, t0 + 256, T, lane, av0);
+    block(av1, t0 + 128);
+  }
+  if (a.vc_part) {  // chunk sums in a fixed order: lanes, then waves
+    __shared__ double2 vc_sm[4];
+    double v_acc = (double)v_part, c_acc = 0.0;
+    if (c_row) {  // the chunk's credit, four positions per thread
+      const int j0 = c0 + threadIdx.x * 4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (j0 + i < T) c_acc += (double)c_row[j0 + i];
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      v_acc += __shfl_xor(v_acc, o);
+      c_acc += __shfl_xor(c_acc, o);
+    }
+    if (lane == 0) vc_sm[wave] = make_double2(v_acc, c_acc);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double2 t = vc_sm[0];
+      for (int w = 1; w < 4; ++w) {
+        t.x += vc_sm[w].x;
+        t.y += vc_sm[w].y;
+      }
+      a.vc_part[(int64_t)unit * a.n_chunks + chunk] = t;
     }
   }
 }
@@ -302,7 +397,7 @@ hipError_t run_softmax_sweeps(const ScoreArgs& a, int mode, hipStream_t s) {
   prof_mark("score_stats", s);
   hipLaunchKernelGGL((score_stats_kernel<BF16, NB>), grid, blk, lds, s, a);
   prof_mark("score_reduce", s);
-  hipLaunchKernelGGL(score_reduce_kernel, dim3(a.d.units), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(score_reduce_kernel, dim3(a.d.units), dim3(kReduceThreads), 0, s, a);
   prof_mark("score_usage", s);
   switch (mode) {
     case MODE_LAST:
@@ -335,8 +430,13 @@ hipError_t run_by_nb(const ScoreArgs& a, int nb, int mode, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
-                        const void* q, float* u, float* g, char* ws, const WsLayout& wl, hipStream_t s) {
+                        const void* q, float* u, float* g, const float* credit, bool* vc_emitted, char* ws,
+                        const WsLayout& wl, hipStream_t s) {
+  if (vc_emitted) *vc_emitted = false;
   ScoreArgs a;
+  a.vc_part = vc_emitted ? (double2*)(ws + wl.vc_part) : nullptr;
+  a.credit = credit;
+  a.eps = p->mass_eps;
   a.k = k;
   a.d = d;
   a.seq_lens = seq_lens;
@@ -358,7 +458,10 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
   bool onepass = false;
   hipError_t e = launch_score_onepass(p, d, k, seq_lens, q, u, g, ws, wl, s, &onepass);
   if (e != hipSuccess) return e;
-  if (!onepass) e = bf16 ? run_by_nb<true>(a, nb, mode, s) : run_by_nb<false>(a, nb, mode, s);
+  if (!onepass) {
+    e = bf16 ? run_by_nb<true>(a, nb, mode, s) : run_by_nb<false>(a, nb, mode, s);
+    if (vc_emitted) *vc_emitted = true;
+  }
   if (e != hipSuccess) return e;
   if (p->scorer == AMS_SCORER_KEYDIFF) {
     a.g = g;

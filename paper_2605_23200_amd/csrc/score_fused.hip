@@ -402,6 +402,9 @@ hipError_t launch_score_onepass(const ams_params* p, const Dims& d, const KvDev&
   a.s.seq_lens = seq_lens;
   a.s.q = (const char*)q;
   a.s.part = nullptr;
+  a.s.vc_part = nullptr;
+  a.s.credit = nullptr;
+  a.s.eps = p->mass_eps;
   a.s.fin = (float4*)(ws + wl.fin_stats);
   a.s.u = u;
   a.s.g = g_out;

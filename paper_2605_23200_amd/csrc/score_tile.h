@@ -28,6 +28,11 @@ struct ScoreArgs {
   int n_chunks, n_pad;
   float c2;          // log2(e) / sqrt(D)
   float inv_sqrt_d;  // 1 / sqrt(D)
+  // optional by-product of the second sweep for Eq. (1) and the EMA: per 1024-token chunk the sums
+  // of max(u,0)+eps and of the credit before the update (NULL: not wanted)
+  double2* vc_part;     // [units][n_chunks]
+  const float* credit;  // [units][t_stride]
+  float eps;
 };
 
 template <bool BF16>
@@ -61,15 +66,11 @@ template <bool BF16>
 __device__ __forceinline__ void load_a(const ScoreArgs& a, int l, int b, int h, int t0, int T,
                                        int lane, uint4 (&av)[Tr<BF16>::kAVecs]) {
   constexpr int NV = Tr<BF16>::kAVecs;
-  const int t = t0 + (lane & 31);
-  if (t < T) {
-    const uint4* p = (const uint4*)(kv_row(a.k, l, b, h, t) + (lane >> 5) * (Tr<BF16>::kRowBytes / 2));
+  // rows past the end re-read the last row (no divergent branch); their logits are masked later
+  const int t = min(t0 + (lane & 31), T - 1);
+  const uint4* p = (const uint4*)(kv_row(a.k, l, b, h, t) + (lane >> 5) * (Tr<BF16>::kRowBytes / 2));
 #pragma unroll
-    for (int i = 0; i < NV; ++i) av[i] = p[i];
-  } else {
-#pragma unroll
-    for (int i = 0; i < NV; ++i) av[i] = make_uint4(0, 0, 0, 0);
-  }
+  for (int i = 0; i < NV; ++i) av[i] = p[i];
 }
 
 // acc[nb][i] = s_raw[token 8*(i/4) + 4*hf + i%4][query nb*32 + lane%32]

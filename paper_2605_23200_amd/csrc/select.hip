@@ -81,10 +81,14 @@ __device__ __forceinline__ int quota_wave(int S, int bud, int q_min, const int32
   return quo;
 }
 
+// cpre_all / mpart_all (optional): prefix of the mass at the cuts and chunk totals as the prefix-sum
+// kernel left them; when given, the segment masses are formed here (and stored) instead of being read.
 __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_lens, int S, int budget,
                                                    int q_min, const int32_t* bounds_all,
-                                                   const float* seg_mass_all, int32_t* quota_all,
-                                                   int32_t* idx_all, int32_t* n_kept_all) {
+                                                   float* seg_mass_all, int32_t* quota_all,
+                                                   int32_t* idx_all, int32_t* n_kept_all,
+                                                   const double* cpre_all, const double* mpart_all,
+                                                   int n_chunks) {
   __shared__ int32_t len[kMaxSeg], room[kMaxSeg], quo[kMaxSeg];
   __shared__ double raw[kMaxSeg];
   __shared__ uint8_t active[kMaxSeg];
@@ -93,7 +97,24 @@ __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_le
   unit_coords(d, unit, l, b, h);
   const int T = seq_lens[b];
   const int32_t* bounds = bounds_all + (int64_t)unit * (S + 1);
-  const float* mass = seg_mass_all + (int64_t)unit * S;
+  float* mass = seg_mass_all + (int64_t)unit * S;
+  if (cpre_all) {
+    const int nch = (T + kChunk - 1) / kChunk;
+    double total = 0.0;  // chunk totals in index order
+    for (int base = 0; base < nch; base += 64) {
+      const int k = min(64, nch - base);
+      double v = 0.0;
+      if ((int)threadIdx.x < k) v = mpart_all[(int64_t)unit * n_chunks + base + threadIdx.x];
+      for (int j = 0; j < k; ++j) total += __shfl(v, j);
+    }
+    const double* cpre = cpre_all + (int64_t)unit * (S + 1);
+    for (int i = threadIdx.x; i < S; i += 64) {
+      const double lo = cpre[i] < 0.0 ? total : cpre[i];
+      const double hi = (i + 1 == S || cpre[i + 1] < 0.0) ? total : cpre[i + 1];
+      mass[i] = (float)(hi - lo);
+    }
+    __syncthreads();
+  }
   const int bud = min(budget, T);
   int32_t* quota = quota_all + (int64_t)unit * S;
   int32_t* idx = idx_all + (int64_t)unit * budget;
@@ -193,33 +214,15 @@ __device__ __forceinline__ uint32_t score_key(float x) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-constexpr int kSelBlock = 512;
+constexpr int kSelBlock = 256;
 constexpr int kSelWaves = kSelBlock / 64;
+constexpr int kSelCap = 4096;  // segment lengths up to this are selected from a copy of the keys in LDS
 
-__global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int budget, const float* g_all,
-                                                           const int32_t* bounds_all,
-                                                           const int32_t* quota_all, int32_t* idx_all) {
-  __shared__ int hist[256];
-  __shared__ uint32_t sel_prefix;
-  __shared__ int sel_rem;
-  __shared__ int2 wave_cnt[kSelWaves];
-  const int unit = blockIdx.y, seg = blockIdx.x;
-  const int32_t* bounds = bounds_all + (int64_t)unit * (S + 1);
-  const int32_t* quota = quota_all + (int64_t)unit * S;
-  const int a = bounds[seg], b = bounds[seg + 1], q = quota[seg];
-  if (q <= 0) return;
-  int out0 = 0;
-  for (int i = 0; i < seg; ++i) out0 += quota[i];
-  const float* g = g_all + (int64_t)unit * d.t_stride;
-  int32_t* out = idx_all + (int64_t)unit * budget + out0;
-  const int L = b - a;
-  if (q >= L) {  // whole segment kept
-    for (int j = threadIdx.x; j < L; j += kSelBlock) out[j] = a + j;
-    return;
-  }
+// Segment longer than the LDS staging area: the scores are re-read from memory for every pass.
+__device__ void select_from_memory(const float* g, int a, int b, int q, int32_t* out, int* hist,
+                                   uint32_t* sel_prefix, int* sel_rem, int2* wave_cnt) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-
-  // radix select of the q-th largest key
+  // radix select of the q-th largest key, 8 bits at a time from the top
   uint32_t prefix = 0, mask = 0;
   int rem = q;
   for (int shift = 24; shift >= 0; shift -= 8) {
@@ -245,15 +248,15 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int bu
 #pragma unroll
       for (int i = 3; i >= 0; --i) {
         if (cum < rem && rem <= cum + hb[i]) {
-          sel_prefix = prefix | ((uint32_t)(lane * 4 + i) << shift);
-          sel_rem = rem - cum;
+          *sel_prefix = prefix | ((uint32_t)(lane * 4 + i) << shift);
+          *sel_rem = rem - cum;
         }
         cum += hb[i];
       }
     }
     __syncthreads();
-    prefix = sel_prefix;
-    rem = sel_rem;
+    prefix = *sel_prefix;
+    rem = *sel_rem;
     mask |= 0xFFu << shift;
     __syncthreads();
   }
@@ -289,16 +292,157 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int bu
   }
 }
 
+__global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int budget, const float* g_all,
+                                                           const int32_t* bounds_all,
+                                                           const int32_t* quota_all, int32_t* idx_all) {
+  __shared__ uint32_t keys[kSelCap];
+  __shared__ int hist[kSelWaves][256];
+  __shared__ uint32_t sel_prefix;
+  __shared__ int sel_rem;
+  __shared__ int2 wave_cnt[kSelWaves];
+  __shared__ uint32_t red_and[kSelWaves], red_or[kSelWaves];
+  const int unit = blockIdx.y, seg = blockIdx.x;
+  const int32_t* bounds = bounds_all + (int64_t)unit * (S + 1);
+  const int32_t* quota = quota_all + (int64_t)unit * S;
+  const int a = bounds[seg], b = bounds[seg + 1], q = quota[seg];
+  if (q <= 0) return;
+  int out0 = 0;
+  for (int i = 0; i < seg; ++i) out0 += quota[i];
+  const float* g = g_all + (int64_t)unit * d.t_stride;
+  int32_t* out = idx_all + (int64_t)unit * budget + out0;
+  const int L = b - a;
+  if (q >= L) {  // whole segment kept
+    for (int j = threadIdx.x; j < L; j += kSelBlock) out[j] = a + j;
+    return;
+  }
+  if (L > kSelCap) {
+    select_from_memory(g, a, b, q, out, &hist[0][0], &sel_prefix, &sel_rem, wave_cnt);
+    return;
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  // keys of the segment -> LDS; bits that are the same in every key need no radix pass
+  uint32_t k_and = 0xFFFFFFFFu, k_or = 0;
+  for (int e = threadIdx.x; e < L; e += kSelBlock) {
+    const uint32_t k = score_key(g[a + e]);
+    keys[e] = k;
+    k_and &= k;
+    k_or |= k;
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    k_and &= __shfl_xor(k_and, o);
+    k_or |= __shfl_xor(k_or, o);
+  }
+  if (lane == 0) {
+    red_and[wave] = k_and;
+    red_or[wave] = k_or;
+  }
+  __syncthreads();
+  k_and = red_and[0] & red_and[1] & red_and[2] & red_and[3];
+  k_or = red_or[0] | red_or[1] | red_or[2] | red_or[3];
+  const uint32_t diff = k_and ^ k_or;
+  uint32_t thr = k_and;  // all keys equal: the threshold is that key
+  int rem = q;
+  if (diff != 0) {
+    const int hb = 31 - __clz(diff);  // highest bit in which two keys differ
+    uint32_t mask = hb == 31 ? 0u : ~((2u << hb) - 1u);  // bits known so far
+    uint32_t prefix = k_and & mask;
+    int shift = max(hb - 7, 0);
+    for (;;) {
+      for (int i = threadIdx.x; i < kSelWaves * 256; i += kSelBlock) (&hist[0][0])[i] = 0;
+      __syncthreads();
+      for (int e = threadIdx.x; e < L; e += kSelBlock) {
+        const uint32_t k = keys[e];
+        if ((k & mask) == prefix) atomicAdd(&hist[wave][(k >> shift) & 255], 1);
+      }
+      __syncthreads();
+      if (wave == 0) {
+        int hbin[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          hbin[i] = 0;
+#pragma unroll
+          for (int w = 0; w < kSelWaves; ++w) hbin[i] += hist[w][lane * 4 + i];
+        }
+        const int s = hbin[0] + hbin[1] + hbin[2] + hbin[3];
+        int incl = s;  // sum over lanes >= this one
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int v = __shfl_down(incl, o);
+          if (lane + o < 64) incl += v;
+        }
+        int cum = incl - s;  // keys in bins above this lane's
+#pragma unroll
+        for (int i = 3; i >= 0; --i) {
+          if (cum < rem && rem <= cum + hbin[i]) {
+            sel_prefix = (uint32_t)(lane * 4 + i);
+            sel_rem = rem - cum;
+          }
+          cum += hbin[i];
+        }
+      }
+      __syncthreads();
+      // the digit may overlap bits that are already known; OR-ing it in is then a no-op for those bits
+      prefix |= sel_prefix << shift;
+      rem = sel_rem;
+      mask = shift == 0 ? 0xFFFFFFFFu : ~((1u << shift) - 1u);
+      __syncthreads();
+      if (shift == 0) break;
+      shift = max(shift - 8, 0);
+    }
+    thr = prefix;
+  }
+  // thr = key of the q-th largest score; rem = how many of the keys equal to it are kept (the first
+  // rem in position order).  Every thread takes a contiguous run of positions, so one workgroup scan
+  // of the per-thread counts gives every kept position its place in the ascending output.
+  const int per = (L + kSelBlock - 1) / kSelBlock;
+  const int e0 = min(L, (int)threadIdx.x * per), e1 = min(L, e0 + per);
+  int c_gt = 0, c_eq = 0;
+  for (int e = e0; e < e1; ++e) {
+    const uint32_t k = keys[e];
+    c_gt += k > thr;
+    c_eq += k == thr;
+  }
+  int i_gt = c_gt, i_eq = c_eq;  // inclusive scans within the wave
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int vg = __shfl_up(i_gt, o), ve = __shfl_up(i_eq, o);
+    if (lane >= o) {
+      i_gt += vg;
+      i_eq += ve;
+    }
+  }
+  if (lane == 63) wave_cnt[wave] = make_int2(i_gt, i_eq);
+  __syncthreads();
+  int n_gt = i_gt - c_gt, n_eq = i_eq - c_eq;
+  for (int w = 0; w < wave; ++w) {
+    n_gt += wave_cnt[w].x;
+    n_eq += wave_cnt[w].y;
+  }
+  for (int e = e0; e < e1; ++e) {
+    const uint32_t k = keys[e];
+    if (k > thr) {
+      out[n_gt + min(n_eq, rem)] = a + e;
+      ++n_gt;
+    } else if (k == thr) {
+      if (n_eq < rem) out[n_gt + n_eq] = a + e;
+      ++n_eq;
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* g,
-                         const int32_t* bounds, const float* seg_mass, int32_t* quota, int32_t* idx,
-                         int32_t* n_kept, hipStream_t s) {
+                         const int32_t* bounds, float* seg_mass, int32_t* quota, int32_t* idx,
+                         int32_t* n_kept, const double* cpre, const double* mpart, int n_chunks,
+                         hipStream_t s) {
   const int S = p->n_segments;
   if (S > kMaxSeg) return hipErrorInvalidValue;
   prof_mark("quota", s);
   hipLaunchKernelGGL(quota_kernel, dim3(d.units), dim3(64), 0, s, d, seq_lens, S, p->budget, p->q_min,
-                     bounds, seg_mass, quota, idx, n_kept);
+                     bounds, seg_mass, quota, idx, n_kept, cpre, mpart, n_chunks);
   prof_mark("select", s);
   hipLaunchKernelGGL(select_kernel, dim3(S, d.units), dim3(kSelBlock), 0, s, d, S, p->budget, g, bounds,
                      quota, idx);
