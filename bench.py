@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload number (1 = the headline 32k configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=64, help="units of the workload the CPU oracle is timed on")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic) so that a counter run of this "
+                         "command can be scaled: see profiles/")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (units are independent; there is no multi-GPU path). "
@@ -112,8 +115,22 @@ def main():
     dom_bytes = kernel_bytes(dom, w)
     achieved = dom_bytes / (kern[dom] * 1e-3) / 1e9
 
+    if args.calibrate_copy:
+        src_c = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
+        dst_c = torch.empty_like(src_c)
+        for _ in range(3):
+            dst_c.copy_(src_c)
+        torch.cuda.synchronize()
+        del src_c, dst_c
+
     step_bytes = algorithmic_bytes(w) * w.units
     eff_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_config{args.config}.json")
+    if os.path.exists(tpath):          # HBM bytes per launch from rocprofv3 --pmc runs of this command
+        with open(tpath) as f:
+            traffic = json.load(f).get("kernels", {}).get(dom, {}).get("hbm_bytes_per_launch")
 
     out = {
         "metric": "ams_compress_steps_per_sec", "value": round(1e3 / ms_per_step, 3), "unit": "steps/s",
@@ -127,7 +144,7 @@ def main():
         "effective_GBps": round(eff_gbps, 1), "algorithmic_bytes_per_step": step_bytes,
         "hbm_peak_frac": round(eff_gbps / HBM_PEAK_GBPS, 4),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "kernel_ms": round(kern[dom], 4), "algorithmic_bytes_per_launch": dom_bytes},
         "kernel_ms": {k: round(v, 4) for k, v in kern.items()},
         "setup_s": round(setup_s, 1),

@@ -41,7 +41,7 @@ WsLayout ws_layout(const ams_params* p) {
   w.kbar = o;       o += align256(units * w.n_chunks * (size_t)p->head_dim * sizeof(double));
   w.fused = o;      o += align256(fused_score_ws_bytes((int64_t)units, p->t_max, w.n_pad, p->batch));
   w.n_chunks4k = div_up(p->t_max, kChunk);
-  w.vc_part = o;    o += align256(units * (size_t)w.n_chunks * 2 * sizeof(double));  // n_chunks >= n_chunks4k
+  w.vc_part = o;    o += align256(units * (size_t)div_up(p->t_max, 128) * 2 * sizeof(double));  // finest producer: 256 positions per entry
   w.mpart = o;      o += align256(units * w.n_chunks4k * sizeof(double));
   w.cpre = o;       o += align256(units * (size_t)(p->n_segments + 1) * sizeof(double));
   w.total = o;
@@ -224,7 +224,7 @@ int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u,
   const WsLayout wl = ws_layout(p);
   if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
   return hip_status(launch_ema(p, make_dims(p), seq_lens, u, credit, m_used, (int32_t*)((char*)ws + wl.bounds),
-                               false, (char*)ws, wl, (hipStream_t)stream), (hipStream_t)stream);
+                               VcInfo{false, 0, 0}, (char*)ws, wl, (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* m_used,
@@ -292,10 +292,10 @@ int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t
   float* seg_mass = (float*)(w + wl.seg_mass);
   int32_t* quota = (int32_t*)(w + wl.quota);
   hipError_t e;
-  bool have_vc = false;
-  if ((e = launch_score(p, d, make_kv(p, src, src->k), seq_lens, q, u, g, credit, &have_vc, w, wl, s)) != hipSuccess)
+  VcInfo vc{false, 0, 0};
+  if ((e = launch_score(p, d, make_kv(p, src, src->k), seq_lens, q, u, g, credit, &vc, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;
-  if ((e = launch_ema(p, d, seq_lens, u, credit, m_used, bounds, have_vc, w, wl, s)) != hipSuccess)
+  if ((e = launch_ema(p, d, seq_lens, u, credit, m_used, bounds, vc, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;
   if ((e = launch_segment(p, d, seq_lens, m_used, bounds, nullptr, true, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;

@@ -58,24 +58,32 @@ struct WsLayout {
 };
 WsLayout ws_layout(const ams_params* p);
 
+// Where the scorer left the per-chunk sums that Eq. (1) and the EMA need (have = false: nowhere).
+struct VcInfo {
+  bool have;
+  int stride;  // entries per unit row of ws + wl.vc_part
+  int tokens;  // positions covered by one entry
+};
+
 // Optional per-kernel timing: when collection is on, every launcher calls prof_mark(label, stream)
 // right before a kernel launch, which records a HIP event on that stream.  Off: a single branch.
 void prof_mark(const char* label, hipStream_t s);
 
 // ---- launchers (each returns hipGetLastError() of its launches) ----
-// credit (optional) and vc_emitted (optional): when vc_emitted is given and comes back true, the
-// per-chunk sums that launch_ema needs are already in the workspace (1024-token chunks).
+// credit and vc are optional: when vc is given, the scorer also leaves the per-chunk sums that
+// launch_ema needs in the workspace and describes them in *vc.
 hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
-                        const void* q, float* u, float* g, const float* credit, bool* vc_emitted, char* ws,
+                        const void* q, float* u, float* g, const float* credit, VcInfo* vc, char* ws,
                         const WsLayout& wl, hipStream_t s);
 size_t fused_score_ws_bytes(int64_t units, int t_max, int n_pad, int batch);
-hipError_t launch_score_onepass(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
-                                const void* q, float* u, float* g, char* ws, const WsLayout& wl,
+hipError_t launch_score_oneread(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
+                                const void* q, float* u, float* g, const float* credit, bool want_vc,
+                                int* vc_stride, int* vc_tokens, char* ws, const WsLayout& wl,
                                 hipStream_t s, bool* ran);
 // launch_ema also leaves the chunk totals of m_used in the workspace and resets `bounds` (scratch
 // or the caller's) for a following launch_segment(have_chunk_totals = true).
 hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
-                      float* credit, float* m_used, int32_t* bounds, bool have_vc_sums, char* ws,
+                      float* credit, float* m_used, int32_t* bounds, const VcInfo& vc, char* ws,
                       const WsLayout& wl, hipStream_t s);
 hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq_lens,
                           const float* m_used, int32_t* bounds, float* seg_mass, bool have_chunk_totals,

@@ -322,7 +322,7 @@ MsArgs make_args(const ams_params* p, const Dims& d, const int32_t* seq_lens, ch
   a.n_chunks = wl.n_chunks4k;
   a.S = p->n_segments;
   a.vc_part = (double2*)(ws + wl.vc_part);
-  a.vc_stride = wl.n_chunks;
+  a.vc_stride = wl.n_chunks4k;
   a.vc_tokens = kChunk;
   a.mpart = (double*)(ws + wl.mpart);
   a.cpre = (double*)(ws + wl.cpre);
@@ -334,13 +334,14 @@ MsArgs make_args(const ams_params* p, const Dims& d, const int32_t* seq_lens, ch
 }  // namespace
 
 hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
-                      float* credit, float* m_used, int32_t* bounds, bool have_vc_sums, char* ws,
+                      float* credit, float* m_used, int32_t* bounds, const VcInfo& vc, char* ws,
                       const WsLayout& wl, hipStream_t s) {
   MsArgs a = make_args(p, d, seq_lens, ws, wl, bounds);
   a.vec = d.t_stride % 4 == 0 && (((uintptr_t)u | (uintptr_t)credit | (uintptr_t)m_used) & 15) == 0;
   const dim3 grid(a.n_chunks, d.units);
-  if (have_vc_sums) {
-    a.vc_tokens = kScoreChunk;  // left by the scorer's second sweep
+  if (vc.have) {  // left by the scorer
+    a.vc_stride = vc.stride;
+    a.vc_tokens = vc.tokens;
   } else {
     prof_mark("vc_sums", s);
     hipLaunchKernelGGL(vc_sums_kernel, grid, dim3(kBlock), 0, s, a, u, (const float*)credit, p->mass_eps);

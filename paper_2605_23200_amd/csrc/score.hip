@@ -430,11 +430,11 @@ hipError_t run_by_nb(const ScoreArgs& a, int nb, int mode, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
-                        const void* q, float* u, float* g, const float* credit, bool* vc_emitted, char* ws,
+                        const void* q, float* u, float* g, const float* credit, VcInfo* vc, char* ws,
                         const WsLayout& wl, hipStream_t s) {
-  if (vc_emitted) *vc_emitted = false;
+  if (vc) vc->have = false;
   ScoreArgs a;
-  a.vc_part = vc_emitted ? (double2*)(ws + wl.vc_part) : nullptr;
+  a.vc_part = vc ? (double2*)(ws + wl.vc_part) : nullptr;
   a.credit = credit;
   a.eps = p->mass_eps;
   a.k = k;
@@ -455,14 +455,22 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
   if (p->scorer == AMS_SCORER_LAST_QUERY) { mode = MODE_LAST; a.g = g; }
   if (p->scorer == AMS_SCORER_EXPECTED) { mode = MODE_EXPECTED; a.g = g; }
   const int nb = wl.n_pad / 32;
-  bool onepass = false;
-  hipError_t e = launch_score_onepass(p, d, k, seq_lens, q, u, g, ws, wl, s, &onepass);
+  bool oneread = false;
+  int vc_stride = 0, vc_tokens = 0;
+  hipError_t e = launch_score_oneread(p, d, k, seq_lens, q, u, g, credit, vc != nullptr, &vc_stride, &vc_tokens,
+                                      ws, wl, s, &oneread);
   if (e != hipSuccess) return e;
-  if (!onepass) {
+  if (!oneread) {
     e = bf16 ? run_by_nb<true>(a, nb, mode, s) : run_by_nb<false>(a, nb, mode, s);
-    if (vc_emitted) *vc_emitted = true;
+    vc_stride = wl.n_chunks;
+    vc_tokens = kScoreChunk;
   }
   if (e != hipSuccess) return e;
+  if (vc) {
+    vc->have = true;
+    vc->stride = vc_stride;
+    vc->tokens = vc_tokens;
+  }
   if (p->scorer == AMS_SCORER_KEYDIFF) {
     a.g = g;
     double* ksum = (double*)(ws + wl.kbar);
