@@ -21,14 +21,20 @@ namespace {
 // the query columns are processed in groups of kGroup<NB> blocks of 32 so that only that many
 // accumulator tiles are live at a time: more bytes in flight per wave at the same occupancy.
 // ---------------------------------------------------------------------------------------------
+#ifndef AMS_SCORE_GROUP_DIV
+#define AMS_SCORE_GROUP_DIV 2   // column blocks of a wave are processed in this many groups (tuning knob)
+#endif
+#ifndef AMS_SCORE_MIN_WAVES
+#define AMS_SCORE_MIN_WAVES 3   // waves per SIMD the register allocation aims for (tuning knob)
+#endif
 template <int NB>
-constexpr int kGroup = (NB % 2 == 0 && NB >= 4) ? NB / 2 : NB;
+constexpr int kGroup = (NB % AMS_SCORE_GROUP_DIV == 0 && NB >= 4) ? NB / AMS_SCORE_GROUP_DIV : NB;
 
 // ---------------------------------------------------------------------------------------------
 // Sweep 1: per chunk, per query (max, sum exp2) of the scaled logits.
 // ---------------------------------------------------------------------------------------------
 template <bool BF16, int NB>
-__global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? 3 : 2) void score_stats_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES : 2) void score_stats_kernel(ScoreArgs a) {
   constexpr int NG = kGroup<NB>, QS = Tr<BF16>::kQStride, NBLK = kScoreChunk / 128;
   extern __shared__ __align__(16) char qlds[];
   __shared__ float2 xch[4][NB * 32];
@@ -159,7 +165,7 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
 // Sweep 2: u[t] = sum_n exp2(x[n][t] - M_n) / (N Z_n), and g for the softmax- or moment-based scorers.
 // ---------------------------------------------------------------------------------------------
 template <bool BF16, int NB, int MODE>
-__global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? 3 : 2) void score_usage_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES : 2) void score_usage_kernel(ScoreArgs a) {
   // the moment-based scorer needs all N logits of a token twice: keep every column block live
   constexpr int NG = (MODE == MODE_EXPECTED) ? NB : kGroup<NB>;
   constexpr int QS = Tr<BF16>::kQStride, NBLK = kScoreChunk / 128;
