@@ -276,3 +276,25 @@ def test_ema_zero_reproduces_raw_boundaries(oracle):
         m = oracle.mass(u[i], w.eps)
         assert_close_rel(to_host(inter.m_used)[i, :w.T], m, what="m_used == m_cur")
         np.testing.assert_array_equal(to_host(inter.bounds)[i], oracle.segment(to_host(inter.m_used)[i, :w.T], w.S)[0])
+
+
+def test_one_read_scorer_path(oracle, monkeypatch):
+    """The opt-in cooperative scorer that reads K once (AMS_SCORER=oneread) computes the same event:
+    ragged tail, several tiles per unit, mean-window and last-query scorers."""
+    monkeypatch.setenv("AMS_SCORER", "oneread")
+    for scorer in (B.SCORER_MEAN_WINDOW, B.SCORER_LAST_QUERY):
+        w = inputs.CONFIGS[1].scaled(L=2, H=3, T=5000, budget=512, S=8, n_spans=6, span_len=(32, 300))
+        host = inputs.dense_cache(w, n_threads=4)
+        job = Job(w, host, scorer=scorer)
+        B.ams_profile_begin()
+        job.step()
+        labels = [k for k, _ in B.ams_profile_end()]
+        assert "score_oneread" in labels and "score_stats" not in labels      # the path under test really ran
+        check_properties_all_units(job)
+        check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), list(range(w.units)), scorer=scorer)
+    monkeypatch.delenv("AMS_SCORER")
+    job = Job(w, host, scorer=scorer)
+    B.ams_profile_begin()
+    job.step()
+    labels = [k for k, _ in B.ams_profile_end()]
+    assert "score_stats" in labels and "score_usage" in labels               # default: the two sweeps
