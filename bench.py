@@ -54,7 +54,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="workload number (1 = the headline 32k configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-units", type=int, default=64, help="units of the workload the CPU oracle is timed on")
+    ap.add_argument("--cpu-units", type=int, default=256, help="units of the workload the CPU oracle is timed on")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that a counter run of this "
                          "command can be scaled: see profiles/")

@@ -45,7 +45,10 @@ __device__ __forceinline__ void unit_coords(const Dims& d, int unit, int& l, int
   l = lb / d.B;
 }
 
-constexpr int kScoreChunk = 1024;  // tokens per workgroup of the scoring kernels
+#ifndef AMS_SCORE_CHUNK
+#define AMS_SCORE_CHUNK 2048
+#endif
+constexpr int kScoreChunk = AMS_SCORE_CHUNK;  // tokens per workgroup of the scoring kernels
 constexpr int kChunk = 4096;       // positions per workgroup of the mass / prefix kernels
 
 inline int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }

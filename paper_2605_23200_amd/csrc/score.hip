@@ -255,10 +255,11 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   if (a.vc_part) {  // chunk sums in a fixed order: lanes, then waves
     __shared__ double2 vc_sm[4];
     double v_acc = (double)v_part, c_acc = 0.0;
-    if (c_row) {  // the chunk's credit, four positions per thread
-      const int j0 = c0 + threadIdx.x * 4;
+    if (c_row) {  // the chunk's credit, a few consecutive positions per thread
+      constexpr int PER = kScoreChunk / kThreads;
+      const int j0 = c0 + threadIdx.x * PER;
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < PER; ++i)
         if (j0 + i < T) c_acc += (double)c_row[j0 + i];
     }
 #pragma unroll

@@ -113,27 +113,43 @@ __device__ __forceinline__ int acc_row(int i, int hf) { return 8 * (i >> 2) + 4 
 
 // Sum of 16 per-lane values over the 32 lanes of a half wave, halving the number of live values
 // at every exchange.  Lane c ends up with the total of value index c >> 1.
+// Exchanges: rows of 16 lanes swap through v_permlane16_swap (bit 4 of the lane), then DPP
+// row_ror:8 (bit 3), row_half_mirror (lane <-> 7 - lane inside groups of 8: the partner has the
+// opposite bit 2), quad_perm xor 2 (bit 1) and xor 1; no LDS traffic.
+__device__ __forceinline__ float dpp_ror8(float x) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x128, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float dpp_half_mirror(float x) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x141, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float dpp_xor2(float x) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x4E, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float dpp_xor1(float x) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0xB1, 0xf, 0xf, true));
+}
 __device__ __forceinline__ float reduce16_over32(const float (&v)[16], int c) {
   float w8[8], w4[4], w2[2];
-  const bool b4 = c & 16, b3 = c & 8, b2 = c & 4, b1 = c & 2;
+  const bool b3 = c & 8, b2 = c & 4, b1 = c & 2;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const float keep = b4 ? v[j + 8] : v[j], send = b4 ? v[j] : v[j + 8];
-    w8[j] = keep + __shfl_xor(send, 16);
+    // even rows receive the partner row's v[j], odd rows the partner row's v[j + 8]
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v[j]), __float_as_uint(v[j + 8]), false, false);
+    w8[j] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const float keep = b3 ? w8[j + 4] : w8[j], send = b3 ? w8[j] : w8[j + 4];
-    w4[j] = keep + __shfl_xor(send, 8);
+    w4[j] = keep + dpp_ror8(send);
   }
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const float keep = b2 ? w4[j + 2] : w4[j], send = b2 ? w4[j] : w4[j + 2];
-    w2[j] = keep + __shfl_xor(send, 4);
+    w2[j] = keep + dpp_half_mirror(send);
   }
   const float keep = b1 ? w2[1] : w2[0], send = b1 ? w2[0] : w2[1];
-  const float w1 = keep + __shfl_xor(send, 2);
-  return w1 + __shfl_xor(w1, 1);
+  const float w1 = keep + dpp_xor2(send);
+  return w1 + dpp_xor1(w1);
 }
 
 }  // namespace ams
