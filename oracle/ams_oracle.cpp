@@ -27,18 +27,30 @@ extern "C" {
 //   s[n][t] = q_n . k_t / sqrt(D)
 //   p[n][t] = softmax over t of s[n][:]
 //   u[t]    = mean over the N = G*W (head, query) pairs of p[n][t]
+//
+// causal != 0 (App. A "Mass construction"): the window's queries sit at the last W
+// positions, query w at position T-W+w, and see the keys up to their own position
+// only; a query whose position would be negative does not exist.  A key among the
+// newest W-1 is therefore observed by fewer than N pairs; each missing observation
+// is replaced by the largest probability that key received from the pairs that do
+// see it.
 // ---------------------------------------------------------------------------
 int amso_score(const float* Q, const float* K, int G, int W, int T, int D,
-               int scorer, float* u, float* g) {
+               int scorer, int causal, float* u, float* g) {
   if (!Q || !K || !u || !g || G < 1 || W < 1 || T < 1 || D < 1) return -1;
   const int N = G * W;
   const double inv_sqrt_d = 1.0 / std::sqrt((double)D);
   std::vector<double> s((size_t)T), usage((size_t)T, 0.0), last((size_t)T, 0.0);
+  std::vector<double> seen_max((size_t)T, 0.0);
+  std::vector<int> seen((size_t)T, 0);
 
   for (int n = 0; n < N; ++n) {
     const float* q = Q + (size_t)n * D;
+    const int w = n % W;
+    const int visible = causal ? T - W + w + 1 : T;  // keys 0 .. visible-1
+    if (visible < 1) continue;
     double smax = -INFINITY;
-    for (int t = 0; t < T; ++t) {
+    for (int t = 0; t < visible; ++t) {
       const float* k = K + (size_t)t * D;
       double dot = 0.0;
       for (int d = 0; d < D; ++d) dot += (double)q[d] * (double)k[d];
@@ -46,18 +58,21 @@ int amso_score(const float* Q, const float* K, int G, int W, int T, int D,
       smax = std::max(smax, s[t]);
     }
     double z = 0.0;
-    for (int t = 0; t < T; ++t) {
+    for (int t = 0; t < visible; ++t) {
       s[t] = std::exp(s[t] - smax);
       z += s[t];
     }
-    const bool newest = (n % W) == W - 1;  // last query of this head's window
-    for (int t = 0; t < T; ++t) {
+    const bool newest = w == W - 1;  // last query of this head's window
+    for (int t = 0; t < visible; ++t) {
       const double p = s[t] / z;
       usage[t] += p;
+      seen[t] += 1;
+      seen_max[t] = std::max(seen_max[t], p);
       if (newest) last[t] += p;
     }
   }
-  for (int t = 0; t < T; ++t) u[t] = (float)(usage[t] / (double)N);
+  for (int t = 0; t < T; ++t)
+    u[t] = (float)((usage[t] + (double)(N - seen[t]) * seen_max[t]) / (double)N);
 
   switch (scorer) {
     case AMSO_SCORER_MEAN_WINDOW:
@@ -189,7 +204,7 @@ int amso_segment(const float* m_used, int T, int S, int32_t* bounds, float* seg_
 // segment above its length, total exactly min(budget, T).
 int amso_quota(const int32_t* bounds, const float* seg_mass, int S, int budget,
                int q_min, int32_t* quota) {
-  if (!bounds || !seg_mass || !quota || S < 1 || budget < 1 || q_min < 0) return -1;
+  if (!bounds || !seg_mass || !quota || S < 1 || budget < 0 || q_min < 0) return -1;
   const int T = bounds[S];
   const int64_t bud = std::min<int64_t>(budget, T);
   std::vector<int64_t> len((size_t)S), qlo((size_t)S), room((size_t)S);
@@ -291,6 +306,64 @@ int amso_select(const float* g, const int32_t* bounds, const int32_t* quota, int
   return 0;
 }
 
+// Sizes of the must-keep set (Sec. 3.3 "must-keep rules"): sinks come first and are never
+// given up, the recent suffix shrinks until both fit into the number of kept tokens, the
+// segments share what is left.
+int amso_must_keep(int T, int budget, int n_sink, int n_last, int* sink_eff, int* last_eff,
+                   int* seg_budget) {
+  if (T < 1 || budget < 1 || n_sink < 0 || n_last < 0 || !sink_eff || !last_eff || !seg_budget) return -1;
+  const int kept = std::min(budget, T);
+  *sink_eff = std::min(n_sink, kept);
+  *last_eff = std::min(n_last, kept - *sink_eff);
+  *seg_budget = kept - *sink_eff - *last_eff;
+  return 0;
+}
+
+// Alg. 1 step 5, second half: union of the in-segment picks with the must-keep positions
+// (the first sink_eff and the last last_eff of T), duplicates removed, ascending; while the
+// set is larger than target the lowest-scoring position outside the must-keep set leaves
+// (of equal scores the higher index first); while it is smaller the highest-scoring
+// position not yet in it joins (of equal scores the lower index first).
+int amso_finalize(const float* g, int T, const int32_t* seg_idx, int n_seg, int sink_eff,
+                  int last_eff, int target, int32_t* idx, int32_t* n_kept) {
+  if (!g || !idx || !n_kept || T < 1 || n_seg < 0 || (n_seg > 0 && !seg_idx)) return -1;
+  if (sink_eff < 0 || last_eff < 0 || sink_eff + last_eff > T || target < sink_eff + last_eff || target > T)
+    return -1;
+  std::vector<char> in((size_t)T, 0), must((size_t)T, 0);
+  for (int t = 0; t < sink_eff; ++t) must[(size_t)t] = 1;
+  for (int t = T - last_eff; t < T; ++t) must[(size_t)t] = 1;
+  for (int j = 0; j < n_seg; ++j) {
+    if (seg_idx[j] < 0 || seg_idx[j] >= T) return -1;
+    in[(size_t)seg_idx[j]] = 1;
+  }
+  int count = 0;
+  for (int t = 0; t < T; ++t) {
+    if (must[(size_t)t]) in[(size_t)t] = 1;
+    count += in[(size_t)t];
+  }
+  while (count > target) {
+    int worst = -1;
+    for (int t = 0; t < T; ++t)
+      if (in[(size_t)t] && !must[(size_t)t] && (worst < 0 || sel_value(g[t]) <= sel_value(g[worst]))) worst = t;
+    if (worst < 0) return -3;
+    in[(size_t)worst] = 0;
+    --count;
+  }
+  while (count < target) {
+    int best = -1;
+    for (int t = 0; t < T; ++t)
+      if (!in[(size_t)t] && (best < 0 || sel_value(g[t]) > sel_value(g[best]))) best = t;
+    if (best < 0) return -3;
+    in[(size_t)best] = 1;
+    ++count;
+  }
+  int out = 0;
+  for (int t = 0; t < T; ++t)
+    if (in[(size_t)t]) idx[out++] = t;
+  *n_kept = out;
+  return 0;
+}
+
 int amso_compact(const void* K, const void* V, const float* credit, int64_t row_bytes,
                  const int32_t* idx, int n_kept, void* K_out, void* V_out, float* credit_out) {
   if (!idx || n_kept < 0 || row_bytes < 1) return -1;
@@ -332,12 +405,19 @@ int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K
   std::vector<float> u_((size_t)T), g_((size_t)T), mc((size_t)T), mu((size_t)T), sm((size_t)S);
   std::vector<int32_t> bd((size_t)S + 1), qt((size_t)S);
   int rc;
-  if ((rc = amso_score(Q, K, p->G, p->W, T, p->D, p->scorer, u_.data(), g_.data()))) return rc;
+  if ((rc = amso_score(Q, K, p->G, p->W, T, p->D, p->scorer, p->causal, u_.data(), g_.data()))) return rc;
   if ((rc = amso_mass(u_.data(), T, p->eps, mc.data()))) return rc;
   if ((rc = amso_ema(mc.data(), credit, T, p->lambda, p->beta, mu.data()))) return rc;
   if ((rc = amso_segment(mu.data(), T, S, bd.data(), sm.data()))) return rc;
-  if ((rc = amso_quota(bd.data(), sm.data(), S, p->budget, p->q_min, qt.data()))) return rc;
-  if ((rc = amso_select(g_.data(), bd.data(), qt.data(), S, idx, n_kept))) return rc;
+  int sink_eff, last_eff, seg_budget;
+  if ((rc = amso_must_keep(T, p->budget, p->n_sink, p->n_last, &sink_eff, &last_eff, &seg_budget))) return rc;
+  if ((rc = amso_quota(bd.data(), sm.data(), S, seg_budget, p->q_min, qt.data()))) return rc;
+  std::vector<int32_t> seg_idx((size_t)std::max(seg_budget, 1));
+  int32_t n_seg = 0;
+  if ((rc = amso_select(g_.data(), bd.data(), qt.data(), S, seg_idx.data(), &n_seg))) return rc;
+  if ((rc = amso_finalize(g_.data(), T, seg_idx.data(), n_seg, sink_eff, last_eff, std::min(p->budget, T),
+                          idx, n_kept)))
+    return rc;
   if ((rc = amso_compact(K_rows, V_rows, credit, row_bytes, idx, *n_kept, K_out, V_out, credit_out)))
     return rc;
   if (u) std::memcpy(u, u_.data(), sizeof(float) * (size_t)T);

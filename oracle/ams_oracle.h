@@ -18,7 +18,10 @@
  * the G*W (head, query) pairs with scale 1/sqrt(D); the largest-remainder
  * reading of "round ... followed by a lightweight adjustment step"; credit of
  * gathered / appended tokens; population covariance and no value-norm term in
- * the expected-attention score; raw-key mean in the key-diversity score.
+ * the expected-attention score; raw-key mean in the key-diversity score; which
+ * probability stands in for a missing causal observation (the per-key maximum
+ * over the pairs that see the key); the order in which equal scores are
+ * trimmed or backfilled.
  */
 #ifndef AMS_ORACLE_H
 #define AMS_ORACLE_H
@@ -38,9 +41,13 @@ enum {
 
 /* Step 1 of Alg. 1 (usage) + the plug-in base score g (Sec. 3.3 "In-Segment
  * Selection").  Q is [G][W][D] (query heads of this KV head, then window
- * position), K is [T][D], both already widened to float.  u, g are [T]. */
+ * position), K is [T][D], both already widened to float.  u, g are [T].
+ * causal != 0 (App. A, "Mass construction"): query w of the window sits at
+ * position T-W+w and sees keys 0..T-W+w; for a key seen by fewer than N
+ * (head, query) pairs every missing observation counts as the largest
+ * probability the key received from the pairs that see it. */
 int amso_score(const float* Q, const float* K, int G, int W, int T, int D,
-               int scorer, float* u, float* g);
+               int scorer, int causal, float* u, float* g);
 
 /* Eq. (1): m_t = (max(u_t,0)+eps) / sum_v (max(u_v,0)+eps). */
 int amso_mass(const float* u, int T, float eps, float* m_cur);
@@ -57,15 +64,30 @@ int amso_ema(const float* m_cur, float* credit, int T, float lambda, float beta,
 int amso_segment(const float* m_used, int T, int S, int32_t* bounds, float* seg_mass);
 
 /* Alg. 1 step 4: minimum quota, proportional share of the remainder, clip to
- * the segment length, adjust so the quotas sum to min(budget, T). */
+ * the segment length, adjust so the quotas sum to min(budget, T).  budget may be
+ * 0 (a must-keep set that uses up everything): all quotas are 0 then. */
 int amso_quota(const int32_t* bounds, const float* seg_mass, int S, int budget,
                int q_min, int32_t* quota);
 
-/* Alg. 1 step 5 without a must-keep set: per segment the quota[i] largest g,
+/* Sec. 3.3 "must-keep rules": kept = min(budget, T); sink_eff = min(n_sink,
+ * kept); last_eff = min(n_last, kept - sink_eff) (the recent suffix gives way,
+ * sinks never do); seg_budget = kept - sink_eff - last_eff goes to amso_quota. */
+int amso_must_keep(int T, int budget, int n_sink, int n_last, int* sink_eff, int* last_eff,
+                   int* seg_budget);
+
+/* Alg. 1 step 5, in-segment part: per segment the quota[i] largest g,
  * equal scores resolved towards the lower index, result ascending.
  * idx has room for sum(quota); returns the number written in *n_kept. */
 int amso_select(const float* g, const int32_t* bounds, const int32_t* quota, int S,
                 int32_t* idx, int32_t* n_kept);
+
+/* Alg. 1 step 5, set part: union of seg_idx [n_seg] with the first sink_eff and
+ * the last last_eff positions, duplicates removed, ascending; trimmed (lowest g
+ * outside the must-keep set first, higher index first among equals) or
+ * backfilled (highest g not yet kept, lower index first among equals) to
+ * exactly target positions.  idx has room for target. */
+int amso_finalize(const float* g, int T, const int32_t* seg_idx, int n_seg, int sink_eff,
+                  int last_eff, int target, int32_t* idx, int32_t* n_kept);
 
 /* Alg. 1 step 6: row gather of K, V (row_bytes bytes per token) and credit. */
 int amso_compact(const void* K, const void* V, const float* credit, int64_t row_bytes,
@@ -88,6 +110,8 @@ typedef struct {
   int scorer;
   int budget, S, q_min;
   float lambda, beta, eps;
+  int n_sink, n_last; /* must-keep sizes; 0, 0 = none */
+  int causal;         /* see amso_score */
 } amso_unit_params;
 
 int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K,

@@ -19,7 +19,8 @@ _lib = None
 class _UnitParams(C.Structure):
     _fields_ = [("G", C.c_int), ("W", C.c_int), ("T", C.c_int), ("D", C.c_int),
                 ("scorer", C.c_int), ("budget", C.c_int), ("S", C.c_int), ("q_min", C.c_int),
-                ("lam", C.c_float), ("beta", C.c_float), ("eps", C.c_float)]
+                ("lam", C.c_float), ("beta", C.c_float), ("eps", C.c_float),
+                ("n_sink", C.c_int), ("n_last", C.c_int), ("causal", C.c_int)]
 
 
 def lib():
@@ -53,7 +54,7 @@ def _chk(rc, what):
         raise RuntimeError(f"oracle {what} failed with code {rc}")
 
 
-def score(Q, K, G, W, scorer=SCORER_MEAN_WINDOW):
+def score(Q, K, G, W, scorer=SCORER_MEAN_WINDOW, causal=False):
     """Q [G*W, D], K [T, D] -> (u [T], g [T]) float32."""
     Q = np.ascontiguousarray(widen(Q)).reshape(G * W, -1)
     K = np.ascontiguousarray(widen(K))
@@ -61,7 +62,7 @@ def score(Q, K, G, W, scorer=SCORER_MEAN_WINDOW):
     assert Q.shape == (G * W, D)
     u = np.empty(T, np.float32)
     g = np.empty(T, np.float32)
-    _chk(lib().amso_score(_f(Q), _f(K), G, W, T, D, int(scorer), _f(u), _f(g)), "score")
+    _chk(lib().amso_score(_f(Q), _f(K), G, W, T, D, int(scorer), int(bool(causal)), _f(u), _f(g)), "score")
     return u, g
 
 
@@ -108,6 +109,25 @@ def select(g, bounds, quota_):
     return idx[: n.value].copy()
 
 
+def must_keep(T, budget, n_sink, n_last):
+    """-> (sink_eff, last_eff, seg_budget)."""
+    a, b, c = C.c_int(0), C.c_int(0), C.c_int(0)
+    _chk(lib().amso_must_keep(int(T), int(budget), int(n_sink), int(n_last), C.byref(a), C.byref(b), C.byref(c)),
+         "must_keep")
+    return a.value, b.value, c.value
+
+
+def finalize(g, seg_idx, sink_eff, last_eff, target):
+    """Union with the must-keep positions, dedupe, sort, trim / backfill to target."""
+    g = np.ascontiguousarray(g, np.float32)
+    seg_idx = np.ascontiguousarray(seg_idx, np.int32)
+    idx = np.empty(max(int(target), 1), np.int32)
+    n = C.c_int32(0)
+    _chk(lib().amso_finalize(_f(g), len(g), _i(seg_idx), len(seg_idx), int(sink_eff), int(last_eff), int(target),
+                             _i(idx), C.byref(n)), "finalize")
+    return idx[: n.value].copy()
+
+
 def compact(K, V, credit, idx):
     """Row gather of K, V ([T, ...] any dtype) and credit [T]."""
     K = np.ascontiguousarray(K)
@@ -142,7 +162,7 @@ def compact_paged(K_pool, V_pool, src_table, K_pool_out, V_pool_out, dst_table, 
 
 
 def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_min=1,
-                  scorer=SCORER_MEAN_WINDOW):
+                  scorer=SCORER_MEAN_WINDOW, n_sink=0, n_last=0, causal=False):
     """One whole event for one unit.  K, V [T, D] in storage dtype (float32 or
     uint16 = bf16 bits).  Returns a dict with every intermediate."""
     Kf = np.ascontiguousarray(widen(K))
@@ -151,7 +171,8 @@ def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, 
     V = np.ascontiguousarray(V)
     T, D = Kf.shape
     kept = min(budget, T)
-    p = _UnitParams(G, W, T, D, int(scorer), int(budget), int(S), int(q_min), lam, beta, eps)
+    p = _UnitParams(G, W, T, D, int(scorer), int(budget), int(S), int(q_min), lam, beta, eps,
+                    int(n_sink), int(n_last), int(bool(causal)))
     c = np.array(credit, dtype=np.float32, copy=True)
     out = dict(u=np.empty(T, np.float32), g=np.empty(T, np.float32), m_used=np.empty(T, np.float32),
                bounds=np.empty(S + 1, np.int32), seg_mass=np.empty(S, np.float32),
@@ -171,7 +192,8 @@ def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, 
 
 
 def compress_many(Q, K, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_min=1,
-                  scorer=SCORER_MEAN_WINDOW, n_threads=0, want_scores=False, K_rows=None, V_rows=None):
+                  scorer=SCORER_MEAN_WINDOW, n_threads=0, want_scores=False, K_rows=None, V_rows=None,
+                  n_sink=0, n_last=0, causal=False):
     """Q [U, G*W, D], K [U, T, D] float32 (already widened), credit [U, T] (updated in
     place).  K_rows, V_rows [U, T, D] in the storage dtype: when given, the kept rows are
     gathered as well (whole event).  Returns (idx [U, budget], n_kept [U], threads_used[, u, g])."""
@@ -179,7 +201,8 @@ def compress_many(Q, K, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_m
     assert Q.shape == (U, G * W, D) and credit.shape == (U, T)
     for a in (Q, K, credit):
         assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"]
-    p = _UnitParams(G, W, T, D, int(scorer), int(budget), int(S), int(q_min), lam, beta, eps)
+    p = _UnitParams(G, W, T, D, int(scorer), int(budget), int(S), int(q_min), lam, beta, eps,
+                    int(n_sink), int(n_last), int(bool(causal)))
     idx = np.empty((U, budget), np.int32)
     n_kept = np.empty(U, np.int32)
     u = np.empty((U, T), np.float32) if want_scores else None
