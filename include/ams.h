@@ -77,6 +77,9 @@ typedef struct {
   float ema_beta;     /* mass mixing, 0 <= beta <= 1 (paper default 0.9)                   */
   float mass_eps;     /* epsilon of Eq. (1), > 0                                           */
   int32_t scorer;     /* ams_scorer                                                        */
+  int32_t n_sink;     /* must-keep: first n_sink positions always kept (Sec. 3.3); 0 = none */
+  int32_t n_last;     /* must-keep: last n_last positions always kept; 0 = none            */
+  int32_t causal;     /* 1: causal window with padded observations (App. A), see ams_score */
 } ams_params;
 
 /* A KV cache as the library sees it.  Plain data, [host]; k, v, block_table [dev]. */
@@ -157,15 +160,23 @@ int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* 
                      int32_t* bounds, float* seg_mass, void* ws, size_t ws_bytes, void* stream);
 
 /*
- * ams_select - segment quotas and in-segment top-k (Sec. 3.3 "Segment-wise Quota
- * Allocation", "In-Segment Selection"; Alg. 1 steps 4-5, no must-keep set).
+ * ams_select - segment quotas, in-segment top-k and the final kept set (Sec. 3.3
+ * "Segment-wise Quota Allocation", "In-Segment Selection", must-keep rules; Alg. 1
+ * steps 4-5).
+ *   kept = min(budget, T).  Must-keep set: the first min(n_sink, kept) positions and
+ *   the last min(n_last, kept - sinks) positions (the recent suffix gives way, sinks
+ *   never do).  The segments share seg_budget = kept - |must-keep|.
  *   quota: floor min(q_min, L_i), remainder shared in proportion to seg_mass,
- *   no quota above the segment length, sum = min(budget, T).
+ *   no quota above the segment length, sum = seg_budget.
  *   idx: per segment the quota[i] positions of largest g (equal scores: lower
- *   position first; NaN ranks below everything), ascending; entries from n_kept
- *   to budget are -1.
+ *   position first; NaN ranks below everything), united with the must-keep set,
+ *   duplicates removed, ascending; when the union is short of kept (a segment
+ *   picked a must-keep position) the highest-scoring positions not yet in it are
+ *   added, equal scores by lower position.  Entries from n_kept to budget are -1.
  *   quota [dev] int32 [units, S]; idx [dev] int32 [units, budget]; n_kept [dev] int32 [units]
- *   ws may be NULL (this stage needs no scratch)
+ *   ws: may be NULL when n_sink == n_last == 0 (no scratch needed); otherwise [dev]
+ *   scratch of at least ams_workspace_bytes(p), else AMS_ERR_INVALID_ARG /
+ *   AMS_ERR_WORKSPACE_TOO_SMALL.
  */
 int ams_select(const ams_params* p, const int32_t* seq_lens, const float* g, const int32_t* bounds,
                const float* seg_mass, int32_t* quota, int32_t* idx, int32_t* n_kept,

@@ -44,6 +44,8 @@ WsLayout ws_layout(const ams_params* p) {
   w.vc_part = o;    o += align256(units * (size_t)div_up(p->t_max, 128) * 2 * sizeof(double));  // finest producer: 256 positions per entry
   w.mpart = o;      o += align256(units * w.n_chunks4k * sizeof(double));
   w.cpre = o;       o += align256(units * (size_t)(p->n_segments + 1) * sizeof(double));
+  w.n_words = div_up(p->t_max, 32);
+  w.flags = o;      o += align256(units * (size_t)w.n_words * sizeof(uint32_t));
   w.total = o;
   return w;
 }
@@ -52,7 +54,7 @@ static int check_params(const ams_params* p) {
   if (!p) return AMS_ERR_INVALID_ARG;
   if (p->n_layers < 1 || p->batch < 1 || p->n_kv_heads < 1 || p->group < 1 || p->window < 1 ||
       p->head_dim < 1 || p->t_max < 1 || p->t_stride < p->t_max || p->budget < 1 || p->n_segments < 1 ||
-      p->q_min < 0)
+      p->q_min < 0 || p->n_sink < 0 || p->n_last < 0 || (p->causal != 0 && p->causal != 1))
     return AMS_ERR_INVALID_ARG;
   if (p->kv_dtype != AMS_F32 && p->kv_dtype != AMS_BF16) return AMS_ERR_INVALID_ARG;
   if (!(p->ema_lambda >= 0.f && p->ema_lambda < 1.f) || !(p->ema_beta >= 0.f && p->ema_beta <= 1.f) ||
@@ -241,14 +243,20 @@ int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* 
 int ams_select(const ams_params* p, const int32_t* seq_lens, const float* g, const int32_t* bounds,
                const float* seg_mass, int32_t* quota, int32_t* idx, int32_t* n_kept,
                void* ws, size_t ws_bytes, void* stream) {
-  (void)ws;
-  (void)ws_bytes;
   const int rc = check_params(p);
   if (rc) return rc;
   if (!seq_lens || !g || !bounds || !seg_mass || !quota || !idx || !n_kept) return AMS_ERR_INVALID_ARG;
+  uint32_t* flags = nullptr;
+  const WsLayout wl = ws_layout(p);
+  if (p->n_sink > 0 || p->n_last > 0) {  // the kept set is assembled in a bitmap
+    if (!ws) return AMS_ERR_INVALID_ARG;
+    if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
+    flags = (uint32_t*)((char*)ws + wl.flags);
+  }
   // seg_mass is only read here; the launcher's non-const pointer serves the fused path
   return hip_status(launch_select(p, make_dims(p), seq_lens, g, bounds, const_cast<float*>(seg_mass), quota, idx,
-                                  n_kept, nullptr, nullptr, 0, (hipStream_t)stream), (hipStream_t)stream);
+                                  n_kept, nullptr, nullptr, 0, flags, wl.n_words, (hipStream_t)stream),
+                    (hipStream_t)stream);
 }
 
 int ams_compact(const ams_params* p, const ams_kv_view* src, const int32_t* idx, const int32_t* n_kept,
@@ -300,7 +308,8 @@ int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t
   if ((e = launch_segment(p, d, seq_lens, m_used, bounds, nullptr, true, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;
   if ((e = launch_select(p, d, seq_lens, g, bounds, seg_mass, quota, idx, n_kept, (const double*)(w + wl.cpre),
-                         (const double*)(w + wl.mpart), wl.n_chunks4k, s)) != hipSuccess)
+                         (const double*)(w + wl.mpart), wl.n_chunks4k, (uint32_t*)(w + wl.flags), wl.n_words,
+                         s)) != hipSuccess)
     return AMS_ERR_HIP;
   if ((e = launch_compact(p, d, make_kv(p, src, src->k), make_kv(p, src, src->v), make_kv(p, dst, dst->k),
                           make_kv(p, dst, dst->v), idx, n_kept, credit, credit_dst, s)) != hipSuccess)

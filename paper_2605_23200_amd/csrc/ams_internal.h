@@ -55,9 +55,10 @@ inline int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 // Workspace carving (offsets in bytes, 256-byte aligned).
 struct WsLayout {
-  size_t part_stats, fin_stats, u, g, m_used, bounds, seg_mass, quota, kbar, fused, vc_part, mpart, cpre, total;
+  size_t part_stats, fin_stats, u, g, m_used, bounds, seg_mass, quota, kbar, fused, vc_part, mpart, cpre, flags, total;
   int n_chunks, n_pad;
   int n_chunks4k;  // chunks of kChunk positions per unit
+  int n_words;     // 32-position words of the kept-set bitmap per unit
 };
 WsLayout ws_layout(const ams_params* p);
 
@@ -92,11 +93,12 @@ hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq
                           const float* m_used, int32_t* bounds, float* seg_mass, bool have_chunk_totals,
                           char* ws, const WsLayout& wl, hipStream_t s);
 // cpre / mpart (optional, with n_chunks): the prefix-sum kernel's raw output; when given, seg_mass is
-// WRITTEN by the quota kernel instead of read.
+// WRITTEN by the quota kernel instead of read.  flags (n_words words per unit): bitmap of the kept set,
+// needed when a must-keep set is configured, else may be null.
 hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* g,
                          const int32_t* bounds, float* seg_mass, int32_t* quota, int32_t* idx,
                          int32_t* n_kept, const double* cpre, const double* mpart, int n_chunks,
-                         hipStream_t s);
+                         uint32_t* flags, int n_words, hipStream_t s);
 hipError_t launch_compact(const ams_params* p, const Dims& d, const KvDev& ks, const KvDev& vs,
                           const KvDev& kd, const KvDev& vd, const int32_t* idx, const int32_t* n_kept,
                           const float* credit_src, float* credit_dst, hipStream_t s);

@@ -1,5 +1,5 @@
-// Segment quotas and in-segment top-k (Sec. 3.3 "Segment-wise Quota Allocation" and "In-Segment
-// Selection"; Alg. 1 steps 4-5, without a must-keep set).
+// Segment quotas, in-segment top-k and the kept set (Sec. 3.3 "Segment-wise Quota Allocation",
+// "In-Segment Selection" and the must-keep rules; Alg. 1 steps 4-5).
 //
 // quota_kernel   one wave per unit; the arithmetic is a handful of double operations per segment
 //                and is done in index order so that it is reproducible bit for bit.
@@ -7,6 +7,11 @@
 //                digit first) of the quota-th largest score on an order-preserving integer image
 //                of the floats, then an ordered compaction that keeps everything above the
 //                threshold and the first few positions equal to it, ascending.
+// finalize_kernel  (only with a must-keep set) one workgroup per unit.  The segment picks arrive as
+//                bits of a per-unit bitmap, so the union with the must-keep positions and the removal
+//                of duplicates are one OR; what the duplicates leave open is filled with the best
+//                scores outside the set (another radix select, over the unset positions), and the
+//                ascending index list is read off the bitmap.
 #include "ams_internal.h"
 
 namespace ams {
@@ -88,7 +93,8 @@ __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_le
                                                    float* seg_mass_all, int32_t* quota_all,
                                                    int32_t* idx_all, int32_t* n_kept_all,
                                                    const double* cpre_all, const double* mpart_all,
-                                                   int n_chunks) {
+                                                   int n_chunks, int n_sink, int n_last,
+                                                   uint32_t* flags_all, int n_words) {
   __shared__ int32_t len[kMaxSeg], room[kMaxSeg], quo[kMaxSeg];
   __shared__ double raw[kMaxSeg];
   __shared__ uint8_t active[kMaxSeg];
@@ -115,12 +121,18 @@ __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_le
     }
     __syncthreads();
   }
-  const int bud = min(budget, T);
+  // must-keep positions go in first: sinks always, the recent suffix as far as it fits; the segments
+  // share what is left
+  const int kept = min(budget, T);
+  const int sinks = min(n_sink, kept);
+  const int bud = kept - sinks - min(n_last, kept - sinks);
   int32_t* quota = quota_all + (int64_t)unit * S;
   int32_t* idx = idx_all + (int64_t)unit * budget;
   // entries of idx beyond the kept count are -1
-  for (int j = bud + threadIdx.x; j < budget; j += 64) idx[j] = -1;
-  if (threadIdx.x == 0) n_kept_all[unit] = bud;
+  for (int j = kept + threadIdx.x; j < budget; j += 64) idx[j] = -1;
+  if (threadIdx.x == 0) n_kept_all[unit] = kept;
+  if (flags_all)
+    for (int j = threadIdx.x; j < n_words; j += 64) flags_all[(int64_t)unit * n_words + j] = 0u;
   if (S <= 64) {
     const int q = quota_wave(S, bud, q_min, bounds, mass);
     if (threadIdx.x < S) quota[threadIdx.x] = q;
@@ -214,12 +226,26 @@ __device__ __forceinline__ uint32_t score_key(float x) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
+// Where a selected position goes: slot `slot` of the ascending index list, or its bit of the bitmap.
+template <bool FLAGS>
+struct Emit {
+  int32_t* out;
+  uint32_t* flags;
+  __device__ __forceinline__ void operator()(int slot, int t) const {
+    if (FLAGS)
+      atomicOr(&flags[t >> 5], 1u << (t & 31));
+    else
+      out[slot] = t;
+  }
+};
+
 constexpr int kSelBlock = 256;
 constexpr int kSelWaves = kSelBlock / 64;
 constexpr int kSelCap = 4096;  // segment lengths up to this are selected from a copy of the keys in LDS
 
 // Segment longer than the LDS staging area: the scores are re-read from memory for every pass.
-__device__ void select_from_memory(const float* g, int a, int b, int q, int32_t* out, int* hist,
+template <bool FLAGS>
+__device__ void select_from_memory(const float* g, int a, int b, int q, const Emit<FLAGS>& emit, int* hist,
                                    uint32_t* sel_prefix, int* sel_rem, int2* wave_cnt) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // radix select of the q-th largest key, 8 bits at a time from the top
@@ -285,16 +311,18 @@ __device__ void select_from_memory(const float* g, int a, int b, int q, int32_t*
       tot_gt += c.x;
       tot_eq += c.y;
     }
-    if (gt || (eq && n_eq < rem)) out[n_gt + min(n_eq, rem)] = t;
+    if (gt || (eq && n_eq < rem)) emit(n_gt + min(n_eq, rem), t);
     base_gt += tot_gt;
     base_eq += tot_eq;
     __syncthreads();
   }
 }
 
+template <bool FLAGS>
 __global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int budget, const float* g_all,
                                                            const int32_t* bounds_all,
-                                                           const int32_t* quota_all, int32_t* idx_all) {
+                                                           const int32_t* quota_all, int32_t* idx_all,
+                                                           uint32_t* flags_all, int n_words) {
   __shared__ uint32_t keys[kSelCap];
   __shared__ int hist[kSelWaves][256];
   __shared__ uint32_t sel_prefix;
@@ -309,14 +337,15 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int bu
   int out0 = 0;
   for (int i = 0; i < seg; ++i) out0 += quota[i];
   const float* g = g_all + (int64_t)unit * d.t_stride;
-  int32_t* out = idx_all + (int64_t)unit * budget + out0;
+  const Emit<FLAGS> emit{idx_all + (int64_t)unit * budget + out0,
+                         FLAGS ? flags_all + (int64_t)unit * n_words : nullptr};
   const int L = b - a;
   if (q >= L) {  // whole segment kept
-    for (int j = threadIdx.x; j < L; j += kSelBlock) out[j] = a + j;
+    for (int j = threadIdx.x; j < L; j += kSelBlock) emit(j, a + j);
     return;
   }
   if (L > kSelCap) {
-    select_from_memory(g, a, b, q, out, &hist[0][0], &sel_prefix, &sel_rem, wave_cnt);
+    select_from_memory<FLAGS>(g, a, b, q, emit, &hist[0][0], &sel_prefix, &sel_rem, wave_cnt);
     return;
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -423,12 +452,164 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int bu
   for (int e = e0; e < e1; ++e) {
     const uint32_t k = keys[e];
     if (k > thr) {
-      out[n_gt + min(n_eq, rem)] = a + e;
+      emit(n_gt + min(n_eq, rem), a + e);
       ++n_gt;
     } else if (k == thr) {
-      if (n_eq < rem) out[n_gt + n_eq] = a + e;
+      if (n_eq < rem) emit(n_gt + n_eq, a + e);
       ++n_eq;
     }
+  }
+}
+
+// Bits of word w (positions 32w .. 32w+31) that lie in [lo, hi).
+__device__ __forceinline__ uint32_t range_bits(int w, int lo, int hi) {
+  const int a = max(lo - w * 32, 0), b = min(hi - w * 32, 32);
+  if (a >= b) return 0u;
+  const uint32_t upto_b = b == 32 ? 0xFFFFFFFFu : (1u << b) - 1u;
+  return upto_b & ~((1u << a) - 1u);
+}
+
+constexpr int kFinBlock = 256;
+constexpr int kFinWaves = kFinBlock / 64;
+
+__global__ __launch_bounds__(kFinBlock) void finalize_kernel(Dims d, const int32_t* seq_lens, int budget,
+                                                             int n_sink, int n_last, const float* g_all,
+                                                             uint32_t* flags_all, int n_words,
+                                                             int32_t* idx_all) {
+  __shared__ int hist[256];
+  __shared__ uint32_t sel_prefix;
+  __shared__ int sel_rem;
+  __shared__ int red[kFinWaves];
+  __shared__ int2 wave_cnt[kFinWaves];
+  const int unit = blockIdx.x;
+  int l, b, h;
+  unit_coords(d, unit, l, b, h);
+  const int T = seq_lens[b];
+  const int kept = min(budget, T);
+  const int sinks = min(n_sink, kept);
+  const int last = min(n_last, kept - sinks);
+  const float* g = g_all + (int64_t)unit * d.t_stride;
+  uint32_t* flags = flags_all + (int64_t)unit * n_words;
+  int32_t* idx = idx_all + (int64_t)unit * budget;
+  const int nw = (T + 31) >> 5;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  // union with the must-keep positions; size of the union
+  int cnt = 0;
+  for (int w = threadIdx.x; w < nw; w += kFinBlock) {
+    const uint32_t f = flags[w] | range_bits(w, 0, sinks) | range_bits(w, T - last, T);
+    flags[w] = f;
+    cnt += __popc(f);
+  }
+  cnt = wave_sum(cnt);
+  if (lane == 0) red[wave] = cnt;
+  __syncthreads();  // also orders the flag stores before the reads below
+  cnt = 0;
+#pragma unroll
+  for (int w = 0; w < kFinWaves; ++w) cnt += red[w];
+  const int deficit = kept - cnt;  // positions the duplicates left open; never negative
+  const bool fill = deficit > 0;
+
+  // key of the deficit-th largest score among the positions outside the set
+  uint32_t thr = 0xFFFFFFFFu;
+  int rem = 0;
+  if (fill) {
+    uint32_t prefix = 0, mask = 0;
+    rem = deficit;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      for (int i = threadIdx.x; i < 256; i += kFinBlock) hist[i] = 0;
+      __syncthreads();
+      for (int t = threadIdx.x; t < T; t += kFinBlock) {
+        if ((flags[t >> 5] >> (t & 31)) & 1u) continue;
+        const uint32_t k = score_key(g[t]);
+        if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+      }
+      __syncthreads();
+      if (wave == 0) {
+        int hb[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) hb[i] = hist[lane * 4 + i];
+        const int s = hb[0] + hb[1] + hb[2] + hb[3];
+        int incl = s;  // sum over lanes >= this one
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int v = __shfl_down(incl, o);
+          if (lane + o < 64) incl += v;
+        }
+        int cum = incl - s;  // keys in bins above this lane's
+#pragma unroll
+        for (int i = 3; i >= 0; --i) {
+          if (cum < rem && rem <= cum + hb[i]) {
+            sel_prefix = prefix | ((uint32_t)(lane * 4 + i) << shift);
+            sel_rem = rem - cum;
+          }
+          cum += hb[i];
+        }
+      }
+      __syncthreads();
+      prefix = sel_prefix;
+      rem = sel_rem;
+      mask |= 0xFFu << shift;
+      __syncthreads();
+    }
+    thr = prefix;
+  }
+
+  // ascending index list: every thread owns one word of 32 positions per round
+  int base_keep = 0, base_eq = 0;
+  for (int w0 = 0; w0 < nw; w0 += kFinBlock) {
+    const int w = w0 + threadIdx.x;
+    uint32_t f = 0u, gt = 0u, eq = 0u;
+    if (w < nw) {
+      f = flags[w];
+      if (fill) {
+        const int t_end = min(32, T - w * 32);
+        for (int j = 0; j < t_end; ++j) {
+          if ((f >> j) & 1u) continue;
+          const uint32_t k = score_key(g[w * 32 + j]);
+          gt |= (uint32_t)(k > thr) << j;
+          eq |= (uint32_t)(k == thr) << j;
+        }
+      }
+    }
+    const int c_keep = __popc(f | gt), c_eq = __popc(eq);
+    int i_keep = c_keep, i_eq = c_eq;  // inclusive scans within the wave
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int vk = __shfl_up(i_keep, o), ve = __shfl_up(i_eq, o);
+      if (lane >= o) {
+        i_keep += vk;
+        i_eq += ve;
+      }
+    }
+    if (lane == 63) wave_cnt[wave] = make_int2(i_keep, i_eq);
+    __syncthreads();
+    int n_keep = base_keep + i_keep - c_keep, n_eq = base_eq + i_eq - c_eq;
+    int tot_keep = 0, tot_eq = 0;
+#pragma unroll
+    for (int v = 0; v < kFinWaves; ++v) {
+      const int2 c = wave_cnt[v];
+      if (v < wave) {
+        n_keep += c.x;
+        n_eq += c.y;
+      }
+      tot_keep += c.x;
+      tot_eq += c.y;
+    }
+    for (uint32_t m = f | gt | eq; m; m &= m - 1) {
+      const int j = __ffs((int)m) - 1;
+      const int t = w * 32 + j;
+      if ((eq >> j) & 1u) {
+        if (n_eq < rem) idx[n_keep + n_eq] = t;
+        ++n_eq;
+      } else {
+        idx[n_keep + min(n_eq, rem)] = t;
+        ++n_keep;
+      }
+    }
+    base_keep += tot_keep;
+    base_eq += tot_eq;
+    __syncthreads();
   }
 }
 
@@ -437,15 +618,26 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int bu
 hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* g,
                          const int32_t* bounds, float* seg_mass, int32_t* quota, int32_t* idx,
                          int32_t* n_kept, const double* cpre, const double* mpart, int n_chunks,
-                         hipStream_t s) {
+                         uint32_t* flags, int n_words, hipStream_t s) {
   const int S = p->n_segments;
   if (S > kMaxSeg) return hipErrorInvalidValue;
+  const bool must = p->n_sink > 0 || p->n_last > 0;
+  if (must && !flags) return hipErrorInvalidValue;
   prof_mark("quota", s);
   hipLaunchKernelGGL(quota_kernel, dim3(d.units), dim3(64), 0, s, d, seq_lens, S, p->budget, p->q_min,
-                     bounds, seg_mass, quota, idx, n_kept, cpre, mpart, n_chunks);
+                     bounds, seg_mass, quota, idx, n_kept, cpre, mpart, n_chunks, p->n_sink, p->n_last,
+                     must ? flags : nullptr, n_words);
   prof_mark("select", s);
-  hipLaunchKernelGGL(select_kernel, dim3(S, d.units), dim3(kSelBlock), 0, s, d, S, p->budget, g, bounds,
-                     quota, idx);
+  if (!must) {
+    hipLaunchKernelGGL(select_kernel<false>, dim3(S, d.units), dim3(kSelBlock), 0, s, d, S, p->budget, g,
+                       bounds, quota, idx, nullptr, 0);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(select_kernel<true>, dim3(S, d.units), dim3(kSelBlock), 0, s, d, S, p->budget, g, bounds,
+                     quota, idx, flags, n_words);
+  prof_mark("finalize", s);
+  hipLaunchKernelGGL(finalize_kernel, dim3(d.units), dim3(kFinBlock), 0, s, d, seq_lens, p->budget, p->n_sink,
+                     p->n_last, g, flags, n_words, idx);
   return hipGetLastError();
 }
 

@@ -31,7 +31,8 @@ class Job:
                                head_dim=w.D, kv_dtype=B.F32 if w.dtype == "f32" else B.BF16,
                                t_max=self.t_max, t_stride=self.t_stride, budget=w.budget,
                                n_segments=w.S, q_min=w.q_min, ema_lambda=w.lam, ema_beta=w.beta,
-                               mass_eps=w.eps, scorer=scorer)
+                               mass_eps=w.eps, scorer=scorer, n_sink=w.n_sink, n_last=w.n_last,
+                               causal=w.causal)
         self.units = w.units
         self.keep = min(w.budget, self.t_max)
         self.lens = _dev(lens, device)

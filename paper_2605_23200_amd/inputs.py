@@ -50,6 +50,9 @@ class Workload:
     block: int = 16
     n_events: int = 1
     n_append: int = 0
+    n_sink: int = 0       # must-keep sizes (0, 0: none)
+    n_last: int = 0
+    causal: bool = False  # causal window with padded observations
 
     @property
     def N(self) -> int:

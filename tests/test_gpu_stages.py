@@ -172,6 +172,58 @@ def test_select_parity(oracle, T, S, budget):
         assert (idx[i, len(io):] == -1).all()
 
 
+@pytest.mark.parametrize("T,S,budget,n_sink,n_last", [
+    (4096, 8, 1024, 4, 32), (10000, 16, 2048, 4, 128), (70001, 64, 4096, 8, 16), (300, 8, 512, 4, 32),
+    (5000, 1, 700, 4, 64), (2000, 100, 60, 4, 16), (2000, 16, 60, 4, 100), (2000, 16, 60, 100, 7),
+    (40000, 4, 1, 4, 4), (33, 4, 20, 40, 40), (9000, 8, 600, 0, 50), (9000, 8, 600, 3, 0)])
+def test_select_must_keep_parity(oracle, T, S, budget, n_sink, n_last):
+    """Kept set with sinks and a recent suffix (Sec. 3.3 must-keep rules; Alg. 1 step 5): quotas for the
+    reduced budget, union, duplicates backfilled; heavy ties and special values included."""
+    rng = np.random.default_rng(T * 7 + S + n_sink)
+    units = 4
+    g = rng.standard_normal((units, T)).astype(np.float32)
+    g[0, :n_sink] += 8                        # sinks attract attention: the first segment picks them too
+    g[0, max(T - n_last, 0):] += 4
+    g[1] = np.round(g[1] * 2) / 2            # heavy ties
+    g[2] = 0.25                               # all equal: pure tie-break
+    g[3, ::7] = -0.0
+    g[3, 3::7] = 0.0
+    g[3, 5::11] = np.nan
+    g[3, 6::13] = -np.inf
+    m = np.stack([oracle.mass((rng.random(T) ** 8).astype(np.float32)) for _ in range(units)])
+    segs = [oracle.segment(m[i], S) for i in range(units)]
+    bounds = np.stack([s[0] for s in segs])
+    seg_mass = np.stack([s[1] for s in segs])
+    p = _vec_params(units, T, S=S, budget=budget)
+    p.n_sink, p.n_last = n_sink, n_last
+    ws = torch.empty(B.ams_workspace_bytes(p), dtype=torch.uint8, device=DEV)
+    quota = torch.zeros((units, S), dtype=torch.int32, device=DEV)
+    idx = torch.full((units, budget), -5, dtype=torch.int32, device=DEV)
+    n_kept = torch.zeros(units, dtype=torch.int32, device=DEV)
+    for _ in range(2):                        # twice: the bitmap in the workspace is cleared by the call itself
+        B.ams_select(p, to_dev(np.array([T], np.int32)), to_dev(g), to_dev(bounds), to_dev(seg_mass), quota, idx,
+                     n_kept, ws)
+    torch.cuda.synchronize()
+    quota, idx, n_kept = to_host(quota), to_host(idx), to_host(n_kept)
+    for i in range(units):
+        sinks, last, seg_budget = oracle.must_keep(T, budget, n_sink, n_last)
+        qo = oracle.quota(bounds[i], seg_mass[i], seg_budget, 1)
+        np.testing.assert_array_equal(quota[i], qo)
+        io = oracle.finalize(g[i], oracle.select(g[i], bounds[i], qo), sinks, last, min(budget, T))
+        assert n_kept[i] == len(io) == min(budget, T)
+        np.testing.assert_array_equal(idx[i, :len(io)], io)
+        assert (idx[i, len(io):] == -1).all()
+
+
+def test_select_must_keep_needs_workspace():
+    p = _vec_params(1, 100, S=2, budget=10)
+    p.n_sink = 2
+    z = torch.zeros(100, device=DEV)
+    zi = torch.zeros(16, dtype=torch.int32, device=DEV)
+    with pytest.raises(B.AmsError):
+        B.ams_select(p, zi, z, zi, z, zi, zi, zi, None)
+
+
 def test_select_single_segment_is_global_topk():
     T, k = 30000, 2048
     g = np.random.default_rng(0).standard_normal((2, T)).astype(np.float32)

@@ -49,7 +49,8 @@ def check_units(oracle, job, host, credit_before, units, scorer=B.SCORER_MEAN_WI
         T = int(lens[b])
         Kh, Vh = host["K"][l, b, h, :T], host["V"][l, b, h, :T]
         if check_scores:
-            uo, go = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), Kh, w.G, w.W, scorer)
+            uo, go = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), Kh, w.G, w.W, scorer,
+                                  causal=w.causal)
             assert_close_rel(u_g[j, :T], uo, what=f"u unit {i}")
             if scorer in (B.SCORER_MEAN_WINDOW, B.SCORER_LAST_QUERY):
                 assert_close_rel(g_g[j, :T], go, what=f"g unit {i}")
@@ -61,10 +62,11 @@ def check_units(oracle, job, host, credit_before, units, scorer=B.SCORER_MEAN_WI
         b_o, sm_o = oracle.segment(m_g[j, :T], w.S)
         np.testing.assert_array_equal(b_g[j], b_o, err_msg=f"bounds unit {i}")
         assert_close_rel(sm_g[j], sm_o, what=f"seg_mass unit {i}")
-        q_o = oracle.quota(b_g[j], sm_g[j], w.budget, w.q_min)
+        sinks, last, seg_budget = oracle.must_keep(T, w.budget, w.n_sink, w.n_last)
+        q_o = oracle.quota(b_g[j], sm_g[j], seg_budget, w.q_min)
         np.testing.assert_array_equal(q_g[j], q_o, err_msg=f"quota unit {i}")
-        i_o = oracle.select(g_g[j, :T], b_g[j], q_g[j])
         n = min(w.budget, T)
+        i_o = oracle.finalize(g_g[j, :T], oracle.select(g_g[j, :T], b_g[j], q_g[j]), sinks, last, n)
         assert nk_g[j] == n == len(i_o)
         np.testing.assert_array_equal(idx_g[j, :n], i_o, err_msg=f"idx unit {i}")
         assert (idx_g[j, n:] == -1).all()
@@ -86,10 +88,22 @@ def check_properties_all_units(job):
     assert bool((idx[~valid] == -1).all())
     inc = (idx[:, 1:] > idx[:, :-1]) | ~valid[:, 1:]
     assert bool(inc.all())                                                  # strictly ascending
-    assert bool((inter.quota.long().sum(1) == keep).all())
+    sinks = torch.clamp(keep, max=w.n_sink)
+    last = torch.minimum(keep - sinks, torch.tensor(w.n_last, device=job.device))
+    assert bool((inter.quota.long().sum(1) == keep - sinks - last).all())
     seg_of = torch.searchsorted(inter.bounds[:, 1:].contiguous().long(), idx.clamp(min=0), right=True)
     for s in range(w.S):                                                    # every segment holds its quota
-        assert torch.equal(((seg_of == s) & valid).sum(1), inter.quota[:, s].long())
+        held = ((seg_of == s) & valid).sum(1)
+        if w.n_sink or w.n_last:                                            # must-keep and backfill only add
+            assert bool((held >= inter.quota[:, s].long()).all())
+        else:
+            assert torch.equal(held, inter.quota[:, s].long())
+    if w.n_sink or w.n_last:                                                # the must-keep positions are in
+        kept_mask = torch.zeros((job.units, job.t_stride + 1), dtype=torch.bool, device=job.device)
+        kept_mask.scatter_(1, torch.where(valid, idx, torch.tensor(job.t_stride, device=job.device)), True)
+        pos = torch.arange(job.t_stride, device=job.device)[None, :]
+        must = (pos < sinks[:, None]) | ((pos >= (lens - last)[:, None]) & (pos < lens[:, None]))
+        assert bool((kept_mask[:, :-1] | ~must).all())
     T = job.t_max
     tmask = torch.arange(job.t_stride, device=job.device)[None, :] < lens[:, None]
     usum = (inter.u.double() * tmask).sum(1)
@@ -276,6 +290,28 @@ def test_ema_zero_reproduces_raw_boundaries(oracle):
         m = oracle.mass(u[i], w.eps)
         assert_close_rel(to_host(inter.m_used)[i, :w.T], m, what="m_used == m_cur")
         np.testing.assert_array_equal(to_host(inter.bounds)[i], oracle.segment(to_host(inter.m_used)[i, :w.T], w.S)[0])
+
+
+@pytest.mark.parametrize("n_sink,n_last", [(4, 32), (0, 128), (4, 0), (4, 3000), (600, 0)])
+def test_must_keep_step(oracle, n_sink, n_last):
+    """Sinks and a recent suffix always kept, budget shared by the segments reduced first, duplicates
+    backfilled (Sec. 3.3 must-keep rules): whole step against the oracle, bf16, several units."""
+    w = inputs.CONFIGS[1].scaled(L=2, H=3, T=6000, budget=512, S=8, n_spans=6, span_len=(32, 300),
+                                 n_sink=n_sink, n_last=n_last)
+    host = inputs.dense_cache(w, n_threads=4)
+    job = Job(w, host)
+    job.step()
+    check_properties_all_units(job)
+    check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), list(range(w.units)))
+
+
+def test_must_keep_paged_ragged(oracle):
+    w = inputs.CONFIGS[2].scaled(L=1, B=8, H=4, n_sink=4, n_last=64)
+    host = inputs.dense_cache(w, n_threads=8)
+    job = Job(w, host)
+    job.step()
+    check_properties_all_units(job)
+    check_units(oracle, job, host, np.zeros((w.units, job.t_max), np.float32), [0, 1, w.units // 2, w.units - 1])
 
 
 def test_one_read_scorer_path(oracle, monkeypatch):
