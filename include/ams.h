@@ -129,6 +129,12 @@ int ams_profile_end(void* stream, int max_entries, const char** labels, float* m
  *   p = softmax over t, u[t] = mean_n p[n][t]; g per p->scorer (g may equal u
  *   as a pointer only for AMS_SCORER_MEAN_WINDOW; for AMS_SCORER_EXTERNAL g is
  *   left untouched).
+ *   p->causal == 1 (App. A "Mass construction"): query w of the window sits at
+ *   position T-W+w and sees keys 0..T-W+w only (a query before position 0 does
+ *   not exist); for a key seen by fewer than N (head, query) pairs every missing
+ *   observation counts as the largest probability the key received from the
+ *   pairs that see it.  The last-query, key-diversity and moment-based g are not
+ *   affected (the newest query sees every key; the other two use no softmax).
  *   q  [dev] [layers, batch, kv_heads*group, window, head_dim], kv_dtype
  *   seq_lens [dev] [batch] int32, each in [1, t_max]
  *   u, g [dev] fp32 [units, t_stride], written

@@ -30,7 +30,7 @@ WsLayout ws_layout(const ams_params* p) {
   w.n_pad = padded_queries(p->group * p->window, p->kv_dtype == AMS_BF16);
   const size_t vec = align256(units * (size_t)p->t_stride * sizeof(float));
   size_t o = 0;
-  w.part_stats = o; o += align256(units * w.n_chunks * (size_t)w.n_pad * sizeof(float2));
+  w.part_stats = o; o += align256(units * (w.n_chunks + 1) * (size_t)w.n_pad * sizeof(float2));
   w.fin_stats = o;  o += align256(units * (size_t)w.n_pad * sizeof(float4));
   w.u = o;          o += vec;
   w.g = o;          o += vec;

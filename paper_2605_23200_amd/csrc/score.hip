@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = max(a.seq_lens[b] - a.t_cut, 0);
   const int c0 = chunk * kScoreChunk;
   if (c0 >= T) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
     float Z = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) Z += xch[w][n].y * __builtin_amdgcn_exp2f(xch[w][n].x - M);
-    a.part[((int64_t)unit * a.n_chunks + chunk) * a.n_pad + n] = make_float2(M, Z);
+    a.part[((int64_t)unit * (a.n_chunks + 1) + chunk) * a.n_pad + n] = make_float2(M, Z);
   }
 }
 
@@ -126,14 +126,16 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
   const int unit = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
-  const int nch = (T + kScoreChunk - 1) / kScoreChunk;
+  const int T_all = a.seq_lens[b];
+  const int T = max(T_all - a.t_cut, 0);
+  // with a causal window one more entry follows the chunks: the statistics over the newest keys
+  const int nch = (T + kScoreChunk - 1) / kScoreChunk + (a.t_cut > 0 ? 1 : 0);
   const int parts = kReduceThreads / a.n_pad;
   const int n = threadIdx.x % a.n_pad, part = threadIdx.x / a.n_pad;
   if (part < parts) {
     const int per = (nch + parts - 1) / parts;
     const int c0 = part * per, c1 = min(nch, c0 + per);
-    const float2* p = a.part + (int64_t)unit * a.n_chunks * a.n_pad + n;
+    const float2* p = a.part + (int64_t)unit * (a.n_chunks + 1) * a.n_pad + n;
     float M = kNegInit;
     for (int c = c0; c < c1; ++c) M = fmaxf(M, p[(int64_t)c * a.n_pad].x);
     double Z = 0.0;
@@ -151,10 +153,12 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
     double Z = 0.0;
     for (int q = 0; q < parts; ++q) Z += pz[q * a.n_pad + n] * (double)__builtin_amdgcn_exp2f(pm[q * a.n_pad + n] - M);
     const bool real = n < a.d.N;
-    const bool newest = real && (n % a.d.W) == a.d.W - 1;
+    // causal window on a cache shorter than the window: a query before position 0 does not exist
+    const bool exists = real && (a.t_cut == 0 || T_all - a.d.W + (n % a.d.W) >= 0);
+    const bool newest = exists && (n % a.d.W) == a.d.W - 1;
     float4 f;
     f.x = M;
-    f.y = real ? (float)(1.0 / ((double)a.d.N * Z)) : 0.f;
+    f.y = exists ? (float)(1.0 / ((double)a.d.N * Z)) : 0.f;
     f.z = newest ? (float)(1.0 / ((double)a.d.G * Z)) : 0.f;
     f.w = real ? 1.f : 0.f;
     a.fin[(int64_t)unit * a.n_pad + n] = f;
@@ -173,7 +177,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = max(a.seq_lens[b] - a.t_cut, 0);
   const int c0 = chunk * kScoreChunk;
   if (c0 >= T) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5, c = lane & 31;
@@ -390,9 +394,149 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Causal window (App. A "Mass construction"): query w of the window sits at position T-W+w and sees
+// the keys up to its own position.  The keys up to T-W are seen by every query and go through the
+// two sweeps above; the W-1 newest keys are few, each seen by a different set of queries, and are
+// handled here with one thread per query: their contribution to every query's (max, sum), and then
+// their usage, where each observation a key is missing counts as the largest probability it got.
+// ---------------------------------------------------------------------------------------------
+template <bool BF16>
+__device__ __forceinline__ void load_q_rows(const ScoreArgs& a, int l, int b, int h, char* qlds) {
+  constexpr int RB = Tr<BF16>::kRowBytes, QS = Tr<BF16>::kQStride, CPR = RB / 16;
+  const char* src = a.q + ((((int64_t)l * a.d.B + b) * a.d.H + h) * a.d.G) * (int64_t)a.d.W * RB;
+  for (int ch = threadIdx.x; ch < a.d.N * CPR; ch += kThreads) {
+    const int n = ch / CPR, col = ch % CPR;
+    *(uint4*)(qlds + n * QS + col * 16) = *(const uint4*)(src + (int64_t)n * RB + col * 16);
+  }
+}
+
+// q . k over the 128 channels, fp32 accumulation in four interleaved partial sums
+template <bool BF16>
+__device__ __forceinline__ float dot_qk(const char* qrow, const char* krow) {
+  float s[4] = {0.f, 0.f, 0.f, 0.f};
+  constexpr int NV = Tr<BF16>::kRowBytes / 16;
+#pragma unroll 4
+  for (int i = 0; i < NV; ++i) {
+    const uint4 kv = *(const uint4*)(krow + i * 16), qv = *(const uint4*)(qrow + i * 16);
+    float kx[8], qx[8];
+    int n;
+    widen8<BF16>(kv, kx, n);
+    widen8<BF16>(qv, qx, n);
+#pragma unroll
+    for (int e = 0; e < (BF16 ? 8 : 4); ++e) s[e & 3] = __builtin_fmaf(qx[e], kx[e], s[e & 3]);
+  }
+  return (s[0] + s[1]) + (s[2] + s[3]);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void score_tail_stats_kernel(ScoreArgs a) {
+  extern __shared__ __align__(16) char qlds[];
+  const int unit = blockIdx.x, n = threadIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b], W = a.d.W;
+  const int t_first = max(T - a.t_cut, 0);
+  load_q_rows<BF16>(a, l, b, h, qlds);
+  __syncthreads();
+  float m = kNegInit, z = 0.f;
+  if (n < a.d.N) {
+    const int pos = T - W + (n % W);  // newest key this query sees
+    for (int t = t_first; t <= pos; ++t) {
+      const float x = dot_qk<BF16>(qlds + n * Tr<BF16>::kQStride, kv_row(a.k, l, b, h, t)) * a.c2;
+      const float mx = fmaxf(m, x);
+      z = __builtin_fmaf(z, __builtin_amdgcn_exp2f(m - mx), __builtin_amdgcn_exp2f(x - mx));
+      m = mx;
+    }
+  }
+  const int slot = (t_first + kScoreChunk - 1) / kScoreChunk;  // right after the chunks of the sweeps
+  if (n < a.n_pad) a.part[((int64_t)unit * (a.n_chunks + 1) + slot) * a.n_pad + n] = make_float2(m, z);
+}
+
+template <bool BF16, int MODE>
+__global__ __launch_bounds__(kThreads) void score_tail_usage_kernel(ScoreArgs a) {
+  extern __shared__ __align__(16) char qlds[];
+  __shared__ float4 red[4];
+  __shared__ float red2[4];
+  const int unit = blockIdx.x, n = threadIdx.x, lane = n & 63, wave = n >> 6;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b], W = a.d.W, N = a.d.N;
+  const int t_first = max(T - a.t_cut, 0);
+  load_q_rows<BF16>(a, l, b, h, qlds);
+  __syncthreads();
+  const bool real = n < N;
+  const int pos = real ? T - W + (n % W) : -1;
+  const float4 f = n < a.n_pad ? a.fin[(int64_t)unit * a.n_pad + n] : make_float4(0.f, 0.f, 0.f, 0.f);
+  float* u_row = a.u + (int64_t)unit * a.d.t_stride;
+  float* g_row = a.g ? a.g + (int64_t)unit * a.d.t_stride : nullptr;
+  const float inv_n = 1.f / (float)N;
+  for (int t = t_first; t < T; ++t) {
+    const float x = real ? dot_qk<BF16>(qlds + n * Tr<BF16>::kQStride, kv_row(a.k, l, b, h, t)) : 0.f;
+    const bool sees = pos >= t;
+    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(x, a.c2, -f.x));
+    // x: share of this (query, key) pair in u, y: the same for the maximum, z: share in the
+    // last-query score, w: logit for the moment-based score
+    float4 v = make_float4(sees ? e * f.y : 0.f, sees ? e * f.y : 0.f, sees ? e * f.z : 0.f,
+                           real ? x * a.inv_sqrt_d : 0.f);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      v.x += __shfl_xor(v.x, o);
+      v.y = fmaxf(v.y, __shfl_xor(v.y, o));
+      v.z += __shfl_xor(v.z, o);
+      v.w += __shfl_xor(v.w, o);
+    }
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    const float sum_p = (red[0].x + red[1].x) + (red[2].x + red[3].x);
+    const float max_p = fmaxf(fmaxf(red[0].y, red[1].y), fmaxf(red[2].y, red[3].y));
+    const float sum_last = (red[0].z + red[1].z) + (red[2].z + red[3].z);
+    const float mean = ((red[0].w + red[1].w) + (red[2].w + red[3].w)) * inv_n;
+    float var = 0.f;
+    if (MODE == MODE_EXPECTED) {
+      const float dlt = x * a.inv_sqrt_d - mean;
+      float s2 = real ? dlt * dlt : 0.f;
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) s2 += __shfl_xor(s2, o);
+      if (lane == 0) red2[wave] = s2;
+      __syncthreads();
+      var = ((red2[0] + red2[1]) + (red2[2] + red2[3])) * inv_n;
+    }
+    if (n == 0) {
+      const int seen = a.d.G * min(W, T - t);  // pairs that see key t
+      const float ru = sum_p + (float)(N - seen) * max_p;
+      u_row[t] = ru;
+      if (g_row) g_row[t] = MODE == MODE_MEAN ? ru : MODE == MODE_LAST ? sum_last : mean + 0.5f * var;
+    }
+    __syncthreads();
+  }
+}
+
 template <typename K>
 hipError_t set_lds(K kernel, int bytes) {
   return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+template <bool BF16>
+hipError_t run_tail_usage(const ScoreArgs& a, int mode, hipStream_t s) {
+  const int lds = a.d.N * Tr<BF16>::kQStride;
+  const dim3 grid(a.d.units), blk(kThreads);
+  hipError_t e;
+  prof_mark("score_tail_usage", s);
+  switch (mode) {
+    case MODE_LAST:
+      if ((e = set_lds(score_tail_usage_kernel<BF16, MODE_LAST>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL((score_tail_usage_kernel<BF16, MODE_LAST>), grid, blk, lds, s, a);
+      break;
+    case MODE_EXPECTED:
+      if ((e = set_lds(score_tail_usage_kernel<BF16, MODE_EXPECTED>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL((score_tail_usage_kernel<BF16, MODE_EXPECTED>), grid, blk, lds, s, a);
+      break;
+    default:
+      if ((e = set_lds(score_tail_usage_kernel<BF16, MODE_MEAN>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL((score_tail_usage_kernel<BF16, MODE_MEAN>), grid, blk, lds, s, a);
+  }
+  return hipGetLastError();
 }
 
 template <bool BF16, int NB>
@@ -403,6 +547,12 @@ hipError_t run_softmax_sweeps(const ScoreArgs& a, int mode, hipStream_t s) {
   if ((e = set_lds(score_stats_kernel<BF16, NB>, lds)) != hipSuccess) return e;
   prof_mark("score_stats", s);
   hipLaunchKernelGGL((score_stats_kernel<BF16, NB>), grid, blk, lds, s, a);
+  if (a.t_cut > 0) {
+    const int tail_lds = a.d.N * Tr<BF16>::kQStride;
+    if ((e = set_lds(score_tail_stats_kernel<BF16>, tail_lds)) != hipSuccess) return e;
+    prof_mark("score_tail_stats", s);
+    hipLaunchKernelGGL(score_tail_stats_kernel<BF16>, dim3(a.d.units), blk, tail_lds, s, a);
+  }
   prof_mark("score_reduce", s);
   hipLaunchKernelGGL(score_reduce_kernel, dim3(a.d.units), dim3(kReduceThreads), 0, s, a);
   prof_mark("score_usage", s);
@@ -419,7 +569,8 @@ hipError_t run_softmax_sweeps(const ScoreArgs& a, int mode, hipStream_t s) {
       if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_MEAN>, lds)) != hipSuccess) return e;
       hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_MEAN>), grid, blk, lds, s, a);
   }
-  return hipGetLastError();
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  return a.t_cut > 0 ? run_tail_usage<BF16>(a, mode, s) : hipSuccess;
 }
 
 template <bool BF16>
@@ -441,6 +592,11 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
                         const WsLayout& wl, hipStream_t s) {
   if (vc) vc->have = false;
   ScoreArgs a;
+  // with a causal window the chunk sums of the second sweep would miss the newest keys: the
+  // mass kernels then form their own sums
+  const bool causal = p->causal != 0 && d.W > 1;
+  if (causal) vc = nullptr;
+  a.t_cut = causal ? d.W - 1 : 0;
   a.vc_part = vc ? (double2*)(ws + wl.vc_part) : nullptr;
   a.credit = credit;
   a.eps = p->mass_eps;
@@ -464,8 +620,10 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
   const int nb = wl.n_pad / 32;
   bool oneread = false;
   int vc_stride = 0, vc_tokens = 0;
-  hipError_t e = launch_score_oneread(p, d, k, seq_lens, q, u, g, credit, vc != nullptr, &vc_stride, &vc_tokens,
-                                      ws, wl, s, &oneread);
+  hipError_t e = hipSuccess;
+  if (!causal)
+    e = launch_score_oneread(p, d, k, seq_lens, q, u, g, credit, vc != nullptr, &vc_stride, &vc_tokens, ws, wl, s,
+                             &oneread);
   if (e != hipSuccess) return e;
   if (!oneread) {
     e = bf16 ? run_by_nb<true>(a, nb, mode, s) : run_by_nb<false>(a, nb, mode, s);

@@ -21,7 +21,8 @@ struct ScoreArgs {
   Dims d;
   const int32_t* seq_lens;
   const char* q;
-  float2* part;  // [units][n_chunks][n_pad]  (max, sum) in the log2 domain
+  float2* part;  // [units][n_chunks + 1][n_pad]  (max, sum) in the log2 domain; the extra slot takes
+                 // the keys of the causal window
   float4* fin;   // [units][n_pad]  (M, weight for u, weight for g, query is real)
   float* u;
   float* g;
@@ -33,6 +34,9 @@ struct ScoreArgs {
   double2* vc_part;     // [units][n_chunks]
   const float* credit;  // [units][t_stride]
   float eps;
+  // causal window (App. A): the two sweeps stop t_cut = W - 1 keys before the end (those keys are
+  // not seen by every query and are handled by the tail kernels); 0 when the window is not causal
+  int t_cut;
 };
 
 template <bool BF16>

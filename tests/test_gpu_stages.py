@@ -50,6 +50,36 @@ def test_score_parity(oracle, dtype, G, W, T, scorer):
             assert_close_norm(g_h[i], go, what=f"g unit {i}")
 
 
+@pytest.mark.parametrize("dtype,G,W,T", [("bf16", 4, 32, 5000), ("bf16", 4, 32, 2048 + 31), ("bf16", 4, 32, 2048 + 32),
+                                          ("f32", 2, 20, 2500), ("bf16", 3, 5, 1), ("bf16", 2, 16, 10),
+                                          ("f32", 1, 8, 8), ("bf16", 8, 32, 1300), ("bf16", 7, 32, 2085),
+                                          ("f32", 4, 32, 31), ("bf16", 1, 256, 700)])
+@pytest.mark.parametrize("scorer", list(SCORERS))
+def test_score_causal_parity(oracle, dtype, G, W, T, scorer):
+    """Causal window with padded observations (App. A): keys older than the window through the two
+    sweeps, the newest W-1 keys through the tail kernels; caches shorter than the window included."""
+    w = _workload(dtype, G, W, T, causal=True)
+    host = inputs.dense_cache(w, n_threads=4)
+    p = params_for(w, scorer=SCORERS[scorer])
+    assert p.causal == 1
+    ws = workspace(p)
+    K, Q = to_dev(host["K"]), to_dev(host["Q"])
+    lens = to_dev(host["seq_lens"])
+    u = torch.full((p.units, w.T), -7.0, device=DEV)
+    g = torch.full((p.units, w.T), -7.0, device=DEV)
+    B.ams_score(p, B.dense_view(K, None), lens, Q, u, g, ws)
+    torch.cuda.synchronize()
+    u_h, g_h = to_host(u), to_host(g)
+    for i, (l, b, h) in enumerate(unit_list(w)):
+        uo, go = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), host["K"][l, b, h, :T],
+                              w.G, w.W, SCORERS[scorer], causal=True)
+        assert_close_rel(u_h[i], uo, what=f"u unit {i}")
+        if scorer in ("mean", "last"):
+            assert_close_rel(g_h[i], go, what=f"g unit {i}")
+        else:
+            assert_close_norm(g_h[i], go, what=f"g unit {i}")
+
+
 def test_score_ragged_batch_paged(oracle):
     # ragged batch in a paged layout: lengths that are not multiples of 16 or 32, permuted blocks
     w = inputs.CONFIGS[2].scaled(L=2, B=3, H=2, T=1500, T_min=300, n_spans=3, span_len=(16, 64), budget=128)

@@ -107,7 +107,10 @@ def check_properties_all_units(job):
     T = job.t_max
     tmask = torch.arange(job.t_stride, device=job.device)[None, :] < lens[:, None]
     usum = (inter.u.double() * tmask).sum(1)
-    assert float((usum - 1).abs().max()) < 1e-4                             # usage is a distribution
+    if w.causal:                                                            # padded observations only add
+        assert float(usum.min()) > 1 - 1e-4 and float(usum.max()) < 1 + w.W
+    else:
+        assert float((usum - 1).abs().max()) < 1e-4                         # usage is a distribution
     msum = (inter.m_used.double() * tmask).sum(1)
     assert float((msum - 1).abs().max()) < 1e-5
     if not job.paged:                                                       # K' = K[idx], V' = V[idx] everywhere
@@ -303,6 +306,28 @@ def test_must_keep_step(oracle, n_sink, n_last):
     job.step()
     check_properties_all_units(job)
     check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), list(range(w.units)))
+
+
+@pytest.mark.parametrize("scorer", ["mean", "last"])
+def test_causal_must_keep_step(oracle, scorer):
+    """The decoder-facing configuration: causal window, sinks and recent suffix, whole step."""
+    sc = {"mean": B.SCORER_MEAN_WINDOW, "last": B.SCORER_LAST_QUERY}[scorer]
+    w = inputs.CONFIGS[1].scaled(L=2, H=3, T=6000, budget=512, S=8, n_spans=6, span_len=(32, 300),
+                                 n_sink=4, n_last=32, causal=True)
+    host = inputs.dense_cache(w, n_threads=4)
+    job = Job(w, host, scorer=sc)
+    job.step()
+    check_properties_all_units(job)
+    check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), list(range(w.units)), scorer=sc)
+
+
+def test_causal_paged_ragged(oracle):
+    w = inputs.CONFIGS[2].scaled(L=1, B=8, H=4, causal=True)
+    host = inputs.dense_cache(w, n_threads=8)
+    job = Job(w, host)
+    job.step()
+    check_properties_all_units(job)
+    check_units(oracle, job, host, np.zeros((w.units, job.t_max), np.float32), [0, 1, w.units // 2, w.units - 1])
 
 
 def test_must_keep_paged_ragged(oracle):
