@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload number (1 = the headline 32k configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=256, help="units of the workload the CPU oracle is timed on")
+    ap.add_argument("--n-sink", type=int, default=0, help="must-keep sinks (not part of the headline workload)")
+    ap.add_argument("--n-last", type=int, default=0, help="must-keep recent suffix (not part of the headline workload)")
+    ap.add_argument("--causal", action="store_true", help="causal query window (not part of the headline workload)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that a counter run of this "
                          "command can be scaled: see profiles/")
@@ -72,7 +75,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     B.lib()                                   # fails loudly if the HIP library is not built
-    w = inputs.CONFIGS[args.config]
+    w = inputs.CONFIGS[args.config].scaled(n_sink=args.n_sink, n_last=args.n_last, causal=args.causal)
     if w.paged or w.T_min is not None:
         sys.exit("bench.py: only dense single-length workloads are benchmark lines")
     t0 = time.time()
@@ -139,7 +142,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config{args.config}: {w.L}L x {w.H} KV heads, group {w.G}, D {w.D}, {w.dtype}, "
                                f"T {w.T}, window {w.W}, budget {w.budget}, S {w.S}, lambda {w.lam}, "
-                               f"{w.n_spans} planted spans, seed {w.seed}; steady-state events at full T",
+                               f"{w.n_spans} planted spans, seed {w.seed}; steady-state events at full T"
+                               + (f"; must-keep {w.n_sink}+{w.n_last}" if w.n_sink or w.n_last else "")
+                               + ("; causal window" if w.causal else ""),
                    "units": w.units, "scorer": "mean_window"},
         "effective_GBps": round(eff_gbps, 1), "algorithmic_bytes_per_step": step_bytes,
         "hbm_peak_frac": round(eff_gbps / HBM_PEAK_GBPS, 4),
@@ -163,7 +168,8 @@ def main():
         t0 = time.perf_counter()
         _, _, used = O.compress_many(np.ascontiguousarray(Qf), np.ascontiguousarray(Kf), credit, G=w.G, W=w.W,
                                      budget=w.budget, S=w.S, lam=w.lam, beta=w.beta, eps=w.eps, q_min=w.q_min,
-                                     n_threads=n_threads, K_rows=Kr, V_rows=Vr)
+                                     n_threads=n_threads, K_rows=Kr, V_rows=Vr, n_sink=w.n_sink, n_last=w.n_last,
+                                     causal=w.causal)
         cpu_s = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(n_units / cpu_s / w.units, 5), "unit": "steps/s", "cores": used,
                                "kind": "oracle",

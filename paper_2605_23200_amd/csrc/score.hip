@@ -33,7 +33,17 @@ constexpr int kGroup = (NB % AMS_SCORE_GROUP_DIV == 0 && NB >= 4) ? NB / AMS_SCO
 // ---------------------------------------------------------------------------------------------
 // Sweep 1: per chunk, per query (max, sum exp2) of the scaled logits.
 // ---------------------------------------------------------------------------------------------
-template <bool BF16, int NB>
+//
+// Causal window (App. A "Mass construction"): query w of the window sits at position T-W+w and sees
+// the keys up to its own position.  The 32-token blocks that lie entirely before the newest W-1 keys
+// are seen by every query and run through the plain kernels, which then stop at t_end; the few
+// blocks from t_end on go through the TAIL instantiation of the same kernels (one workgroup per
+// unit), where a (query, key) pair the mask hides is left out.
+__device__ __forceinline__ int causal_t_end(const ScoreArgs& a, int T) {
+  return a.causal ? max(0, (T - a.d.W + 1) / 32 * 32) : T;
+}
+
+template <bool BF16, int NB, bool TAIL>
 __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES : 2) void score_stats_kernel(ScoreArgs a) {
   constexpr int NG = kGroup<NB>, QS = Tr<BF16>::kQStride, NBLK = kScoreChunk / 128;
   extern __shared__ __align__(16) char qlds[];
@@ -41,10 +51,12 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = max(a.seq_lens[b] - a.t_cut, 0);
-  const int c0 = chunk * kScoreChunk;
+  const int T_all = a.seq_lens[b], t_end = causal_t_end(a, T_all);
+  const int T = TAIL ? T_all : t_end;
+  const int c0 = TAIL ? t_end : chunk * kScoreChunk;
   if (c0 >= T) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
+  const int t_vis0 = T_all - a.d.W;  // newest key visible to the oldest query of the window
   uint4 av0[Tr<BF16>::kAVecs], av1[Tr<BF16>::kAVecs];
   if (c0 + wave * 32 < T) load_a<BF16>(a, l, b, h, c0 + wave * 32, T, lane, av0);
   load_q<BF16, NB>(a, l, b, h, qlds);
@@ -69,7 +81,12 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
 #pragma unroll
       for (int k = 0; k < NG; ++k) {
         const int nb = g0 + k;
-        if (ragged) {
+        if (TAIL) {
+          // this column's query sees the keys up to lim (< T, so rows past the end are covered too)
+          const int lim = t_vis0 + (nb * 32 + (lane & 31)) % a.d.W;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[k][i] = (t0 + acc_row(i, hf) > lim) ? -INFINITY : acc[k][i];
+        } else if (ragged) {
 #pragma unroll
           for (int i = 0; i < 16; ++i) acc[k][i] = (t0 + acc_row(i, hf) >= T) ? -INFINITY : acc[k][i];
         }
@@ -112,7 +129,9 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
     float Z = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) Z += xch[w][n].y * __builtin_amdgcn_exp2f(xch[w][n].x - M);
-    a.part[((int64_t)unit * (a.n_chunks + 1) + chunk) * a.n_pad + n] = make_float2(M, Z);
+    // the tail's entry follows those of the chunks
+    const int slot = TAIL ? (t_end + kScoreChunk - 1) / kScoreChunk : chunk;
+    a.part[((int64_t)unit * (a.n_chunks + 1) + slot) * a.n_pad + n] = make_float2(M, Z);
   }
 }
 
@@ -126,10 +145,8 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
   const int unit = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T_all = a.seq_lens[b];
-  const int T = max(T_all - a.t_cut, 0);
-  // with a causal window one more entry follows the chunks: the statistics over the newest keys
-  const int nch = (T + kScoreChunk - 1) / kScoreChunk + (a.t_cut > 0 ? 1 : 0);
+  const int T = a.seq_lens[b];
+  const int nch = (causal_t_end(a, T) + kScoreChunk - 1) / kScoreChunk + (a.causal ? 1 : 0);
   const int parts = kReduceThreads / a.n_pad;
   const int n = threadIdx.x % a.n_pad, part = threadIdx.x / a.n_pad;
   if (part < parts) {
@@ -154,7 +171,7 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
     for (int q = 0; q < parts; ++q) Z += pz[q * a.n_pad + n] * (double)__builtin_amdgcn_exp2f(pm[q * a.n_pad + n] - M);
     const bool real = n < a.d.N;
     // causal window on a cache shorter than the window: a query before position 0 does not exist
-    const bool exists = real && (a.t_cut == 0 || T_all - a.d.W + (n % a.d.W) >= 0);
+    const bool exists = real && (!a.causal || T - a.d.W + (n % a.d.W) >= 0);
     const bool newest = exists && (n % a.d.W) == a.d.W - 1;
     float4 f;
     f.x = M;
@@ -168,7 +185,9 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
 // ---------------------------------------------------------------------------------------------
 // Sweep 2: u[t] = sum_n exp2(x[n][t] - M_n) / (N Z_n), and g for the softmax- or moment-based scorers.
 // ---------------------------------------------------------------------------------------------
-template <bool BF16, int NB, int MODE>
+// TAIL (causal window, blocks from t_end on): a (query, key) pair the mask hides adds nothing, and
+// every observation a key is missing counts as the largest share it got.
+template <bool BF16, int NB, int MODE, bool TAIL>
 __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES : 2) void score_usage_kernel(ScoreArgs a) {
   // the moment-based scorer needs all N logits of a token twice: keep every column block live
   constexpr int NG = (MODE == MODE_EXPECTED) ? NB : kGroup<NB>;
@@ -177,10 +196,12 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = max(a.seq_lens[b] - a.t_cut, 0);
-  const int c0 = chunk * kScoreChunk;
+  const int T_all = a.seq_lens[b], t_end = causal_t_end(a, T_all);
+  const int T = TAIL ? T_all : t_end;
+  const int c0 = TAIL ? t_end : chunk * kScoreChunk;
   if (c0 >= T) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5, c = lane & 31;
+  const int t_vis0 = T_all - a.d.W;  // newest key visible to the oldest query of the window
   uint4 av0[Tr<BF16>::kAVecs], av1[Tr<BF16>::kAVecs];
   if (c0 + wave * 32 < T) load_a<BF16>(a, l, b, h, c0 + wave * 32, T, lane, av0);
   load_q<BF16, NB>(a, l, b, h, qlds);
@@ -194,10 +215,11 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   const float* c_row = a.credit ? a.credit + (int64_t)unit * a.d.t_stride : nullptr;
   float v_part = 0.f;  // this lane's share of sum(max(u,0)+eps): at most 8 terms
   auto block = [&](const uint4 (&av)[Tr<BF16>::kAVecs], int t0) __attribute__((always_inline)) {
-    float pu[16], pg[16];
+    float pu[16], pg[16], pm[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) pu[i] = pg[i] = 0.f;
+    for (int i = 0; i < 16; ++i) pu[i] = pg[i] = pm[i] = 0.f;
     float rg = 0.f;
+    constexpr bool masked = TAIL;
     int qoff = 0;  // see the first sweep: the query fragments are re-read per block on purpose
     asm volatile("" : "+s"(qoff));
 #pragma unroll
@@ -228,18 +250,35 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
 #pragma unroll
       for (int k = 0; k < NG; ++k) {
         const int nb = g0 + k;
+        if (masked) {
+          const int lim = t_vis0 + (nb * 32 + c) % a.d.W;  // newest key this column's query sees
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[k][i], c2, -f[nb].x));
-          pu[i] = __builtin_fmaf(f[nb].y, e, pu[i]);
-          if (MODE == MODE_LAST) pg[i] = __builtin_fmaf(f[nb].z, e, pg[i]);
+          for (int i = 0; i < 16; ++i) {
+            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[k][i], c2, -f[nb].x));
+            const bool sees = t0 + acc_row(i, hf) <= lim;
+            const float share = sees ? f[nb].y * e : 0.f;
+            pu[i] += share;
+            pm[i] = fmaxf(pm[i], share);
+            if (MODE == MODE_LAST) pg[i] += sees ? f[nb].z * e : 0.f;
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[k][i], c2, -f[nb].x));
+            pu[i] = __builtin_fmaf(f[nb].y, e, pu[i]);
+            if (MODE == MODE_LAST) pg[i] = __builtin_fmaf(f[nb].z, e, pg[i]);
+          }
         }
       }
     }
-    const float ru = reduce16_over32(pu, c);
+    const int t = t0 + acc_row(c >> 1, hf);
+    float ru = reduce16_over32(pu, c);
+    if (masked) {
+      const int seen = a.d.G * min(a.d.W, T - t);  // (head, query) pairs that see key t
+      ru += (float)(a.d.N - seen) * reduce16_over32<true>(pm, c);
+    }
     if (MODE == MODE_MEAN) rg = ru;
     if (MODE == MODE_LAST) rg = reduce16_over32(pg, c);
-    const int t = t0 + acc_row(c >> 1, hf);
     if ((c & 1) == 0 && t < T) {
       u_row[t] = ru;
       if (g_row) g_row[t] = rg;
@@ -394,147 +433,27 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Causal window (App. A "Mass construction"): query w of the window sits at position T-W+w and sees
-// the keys up to its own position.  The keys up to T-W are seen by every query and go through the
-// two sweeps above; the W-1 newest keys are few, each seen by a different set of queries, and are
-// handled here with one thread per query: their contribution to every query's (max, sum), and then
-// their usage, where each observation a key is missing counts as the largest probability it got.
-// ---------------------------------------------------------------------------------------------
-template <bool BF16>
-__device__ __forceinline__ void load_q_rows(const ScoreArgs& a, int l, int b, int h, char* qlds) {
-  constexpr int RB = Tr<BF16>::kRowBytes, QS = Tr<BF16>::kQStride, CPR = RB / 16;
-  const char* src = a.q + ((((int64_t)l * a.d.B + b) * a.d.H + h) * a.d.G) * (int64_t)a.d.W * RB;
-  for (int ch = threadIdx.x; ch < a.d.N * CPR; ch += kThreads) {
-    const int n = ch / CPR, col = ch % CPR;
-    *(uint4*)(qlds + n * QS + col * 16) = *(const uint4*)(src + (int64_t)n * RB + col * 16);
-  }
-}
-
-// q . k over the 128 channels, fp32 accumulation in four interleaved partial sums
-template <bool BF16>
-__device__ __forceinline__ float dot_qk(const char* qrow, const char* krow) {
-  float s[4] = {0.f, 0.f, 0.f, 0.f};
-  constexpr int NV = Tr<BF16>::kRowBytes / 16;
-#pragma unroll 4
-  for (int i = 0; i < NV; ++i) {
-    const uint4 kv = *(const uint4*)(krow + i * 16), qv = *(const uint4*)(qrow + i * 16);
-    float kx[8], qx[8];
-    int n;
-    widen8<BF16>(kv, kx, n);
-    widen8<BF16>(qv, qx, n);
-#pragma unroll
-    for (int e = 0; e < (BF16 ? 8 : 4); ++e) s[e & 3] = __builtin_fmaf(qx[e], kx[e], s[e & 3]);
-  }
-  return (s[0] + s[1]) + (s[2] + s[3]);
-}
-
-template <bool BF16>
-__global__ __launch_bounds__(kThreads) void score_tail_stats_kernel(ScoreArgs a) {
-  extern __shared__ __align__(16) char qlds[];
-  const int unit = blockIdx.x, n = threadIdx.x;
-  int l, b, h;
-  unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b], W = a.d.W;
-  const int t_first = max(T - a.t_cut, 0);
-  load_q_rows<BF16>(a, l, b, h, qlds);
-  __syncthreads();
-  float m = kNegInit, z = 0.f;
-  if (n < a.d.N) {
-    const int pos = T - W + (n % W);  // newest key this query sees
-    for (int t = t_first; t <= pos; ++t) {
-      const float x = dot_qk<BF16>(qlds + n * Tr<BF16>::kQStride, kv_row(a.k, l, b, h, t)) * a.c2;
-      const float mx = fmaxf(m, x);
-      z = __builtin_fmaf(z, __builtin_amdgcn_exp2f(m - mx), __builtin_amdgcn_exp2f(x - mx));
-      m = mx;
-    }
-  }
-  const int slot = (t_first + kScoreChunk - 1) / kScoreChunk;  // right after the chunks of the sweeps
-  if (n < a.n_pad) a.part[((int64_t)unit * (a.n_chunks + 1) + slot) * a.n_pad + n] = make_float2(m, z);
-}
-
-template <bool BF16, int MODE>
-__global__ __launch_bounds__(kThreads) void score_tail_usage_kernel(ScoreArgs a) {
-  extern __shared__ __align__(16) char qlds[];
-  __shared__ float4 red[4];
-  __shared__ float red2[4];
-  const int unit = blockIdx.x, n = threadIdx.x, lane = n & 63, wave = n >> 6;
-  int l, b, h;
-  unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b], W = a.d.W, N = a.d.N;
-  const int t_first = max(T - a.t_cut, 0);
-  load_q_rows<BF16>(a, l, b, h, qlds);
-  __syncthreads();
-  const bool real = n < N;
-  const int pos = real ? T - W + (n % W) : -1;
-  const float4 f = n < a.n_pad ? a.fin[(int64_t)unit * a.n_pad + n] : make_float4(0.f, 0.f, 0.f, 0.f);
-  float* u_row = a.u + (int64_t)unit * a.d.t_stride;
-  float* g_row = a.g ? a.g + (int64_t)unit * a.d.t_stride : nullptr;
-  const float inv_n = 1.f / (float)N;
-  for (int t = t_first; t < T; ++t) {
-    const float x = real ? dot_qk<BF16>(qlds + n * Tr<BF16>::kQStride, kv_row(a.k, l, b, h, t)) : 0.f;
-    const bool sees = pos >= t;
-    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(x, a.c2, -f.x));
-    // x: share of this (query, key) pair in u, y: the same for the maximum, z: share in the
-    // last-query score, w: logit for the moment-based score
-    float4 v = make_float4(sees ? e * f.y : 0.f, sees ? e * f.y : 0.f, sees ? e * f.z : 0.f,
-                           real ? x * a.inv_sqrt_d : 0.f);
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-      v.x += __shfl_xor(v.x, o);
-      v.y = fmaxf(v.y, __shfl_xor(v.y, o));
-      v.z += __shfl_xor(v.z, o);
-      v.w += __shfl_xor(v.w, o);
-    }
-    if (lane == 0) red[wave] = v;
-    __syncthreads();
-    const float sum_p = (red[0].x + red[1].x) + (red[2].x + red[3].x);
-    const float max_p = fmaxf(fmaxf(red[0].y, red[1].y), fmaxf(red[2].y, red[3].y));
-    const float sum_last = (red[0].z + red[1].z) + (red[2].z + red[3].z);
-    const float mean = ((red[0].w + red[1].w) + (red[2].w + red[3].w)) * inv_n;
-    float var = 0.f;
-    if (MODE == MODE_EXPECTED) {
-      const float dlt = x * a.inv_sqrt_d - mean;
-      float s2 = real ? dlt * dlt : 0.f;
-#pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) s2 += __shfl_xor(s2, o);
-      if (lane == 0) red2[wave] = s2;
-      __syncthreads();
-      var = ((red2[0] + red2[1]) + (red2[2] + red2[3])) * inv_n;
-    }
-    if (n == 0) {
-      const int seen = a.d.G * min(W, T - t);  // pairs that see key t
-      const float ru = sum_p + (float)(N - seen) * max_p;
-      u_row[t] = ru;
-      if (g_row) g_row[t] = MODE == MODE_MEAN ? ru : MODE == MODE_LAST ? sum_last : mean + 0.5f * var;
-    }
-    __syncthreads();
-  }
-}
-
 template <typename K>
 hipError_t set_lds(K kernel, int bytes) {
   return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-template <bool BF16>
-hipError_t run_tail_usage(const ScoreArgs& a, int mode, hipStream_t s) {
-  const int lds = a.d.N * Tr<BF16>::kQStride;
-  const dim3 grid(a.d.units), blk(kThreads);
+template <bool BF16, int NB, bool TAIL>
+hipError_t launch_usage(const ScoreArgs& a, int mode, dim3 grid, int lds, hipStream_t s) {
+  const dim3 blk(kThreads);
   hipError_t e;
-  prof_mark("score_tail_usage", s);
   switch (mode) {
     case MODE_LAST:
-      if ((e = set_lds(score_tail_usage_kernel<BF16, MODE_LAST>, lds)) != hipSuccess) return e;
-      hipLaunchKernelGGL((score_tail_usage_kernel<BF16, MODE_LAST>), grid, blk, lds, s, a);
+      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_LAST, TAIL>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_LAST, TAIL>), grid, blk, lds, s, a);
       break;
     case MODE_EXPECTED:
-      if ((e = set_lds(score_tail_usage_kernel<BF16, MODE_EXPECTED>, lds)) != hipSuccess) return e;
-      hipLaunchKernelGGL((score_tail_usage_kernel<BF16, MODE_EXPECTED>), grid, blk, lds, s, a);
+      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_EXPECTED, TAIL>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_EXPECTED, TAIL>), grid, blk, lds, s, a);
       break;
     default:
-      if ((e = set_lds(score_tail_usage_kernel<BF16, MODE_MEAN>, lds)) != hipSuccess) return e;
-      hipLaunchKernelGGL((score_tail_usage_kernel<BF16, MODE_MEAN>), grid, blk, lds, s, a);
+      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_MEAN, TAIL>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_MEAN, TAIL>), grid, blk, lds, s, a);
   }
   return hipGetLastError();
 }
@@ -544,33 +463,23 @@ hipError_t run_softmax_sweeps(const ScoreArgs& a, int mode, hipStream_t s) {
   const int lds = NB * 32 * Tr<BF16>::kQStride;
   const dim3 grid(a.n_chunks, a.d.units), blk(kThreads);
   hipError_t e;
-  if ((e = set_lds(score_stats_kernel<BF16, NB>, lds)) != hipSuccess) return e;
+  if ((e = set_lds(score_stats_kernel<BF16, NB, false>, lds)) != hipSuccess) return e;
   prof_mark("score_stats", s);
-  hipLaunchKernelGGL((score_stats_kernel<BF16, NB>), grid, blk, lds, s, a);
-  if (a.t_cut > 0) {
-    const int tail_lds = a.d.N * Tr<BF16>::kQStride;
-    if ((e = set_lds(score_tail_stats_kernel<BF16>, tail_lds)) != hipSuccess) return e;
-    prof_mark("score_tail_stats", s);
-    hipLaunchKernelGGL(score_tail_stats_kernel<BF16>, dim3(a.d.units), blk, tail_lds, s, a);
+  hipLaunchKernelGGL((score_stats_kernel<BF16, NB, false>), grid, blk, lds, s, a);
+  if (a.causal) {
+    if ((e = set_lds(score_stats_kernel<BF16, NB, true>, lds)) != hipSuccess) return e;
+    prof_mark("score_stats_tail", s);
+    hipLaunchKernelGGL((score_stats_kernel<BF16, NB, true>), dim3(1, a.d.units), blk, lds, s, a);
   }
   prof_mark("score_reduce", s);
   hipLaunchKernelGGL(score_reduce_kernel, dim3(a.d.units), dim3(kReduceThreads), 0, s, a);
   prof_mark("score_usage", s);
-  switch (mode) {
-    case MODE_LAST:
-      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_LAST>, lds)) != hipSuccess) return e;
-      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_LAST>), grid, blk, lds, s, a);
-      break;
-    case MODE_EXPECTED:
-      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_EXPECTED>, lds)) != hipSuccess) return e;
-      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_EXPECTED>), grid, blk, lds, s, a);
-      break;
-    default:
-      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_MEAN>, lds)) != hipSuccess) return e;
-      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_MEAN>), grid, blk, lds, s, a);
+  if ((e = launch_usage<BF16, NB, false>(a, mode, grid, lds, s)) != hipSuccess) return e;
+  if (a.causal) {
+    prof_mark("score_usage_tail", s);
+    if ((e = launch_usage<BF16, NB, true>(a, mode, dim3(1, a.d.units), lds, s)) != hipSuccess) return e;
   }
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  return a.t_cut > 0 ? run_tail_usage<BF16>(a, mode, s) : hipSuccess;
+  return hipSuccess;
 }
 
 template <bool BF16>
@@ -592,11 +501,10 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
                         const WsLayout& wl, hipStream_t s) {
   if (vc) vc->have = false;
   ScoreArgs a;
-  // with a causal window the chunk sums of the second sweep would miss the newest keys: the
-  // mass kernels then form their own sums
-  const bool causal = p->causal != 0 && d.W > 1;
+  const bool causal = p->causal != 0 && d.W > 1;  // a window of one query sees everything anyway
+  a.causal = causal;
+  // the chunk sums of the second sweep would miss the tail blocks: the mass kernels form their own
   if (causal) vc = nullptr;
-  a.t_cut = causal ? d.W - 1 : 0;
   a.vc_part = vc ? (double2*)(ws + wl.vc_part) : nullptr;
   a.credit = credit;
   a.eps = p->mass_eps;

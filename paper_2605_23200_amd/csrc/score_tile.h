@@ -21,8 +21,8 @@ struct ScoreArgs {
   Dims d;
   const int32_t* seq_lens;
   const char* q;
-  float2* part;  // [units][n_chunks + 1][n_pad]  (max, sum) in the log2 domain; the extra slot takes
-                 // the keys of the causal window
+  float2* part;  // [units][n_chunks + 1][n_pad]  (max, sum) in the log2 domain; the last entry of a
+                 // unit takes the tail blocks of a causal window
   float4* fin;   // [units][n_pad]  (M, weight for u, weight for g, query is real)
   float* u;
   float* g;
@@ -34,9 +34,7 @@ struct ScoreArgs {
   double2* vc_part;     // [units][n_chunks]
   const float* credit;  // [units][t_stride]
   float eps;
-  // causal window (App. A): the two sweeps stop t_cut = W - 1 keys before the end (those keys are
-  // not seen by every query and are handled by the tail kernels); 0 when the window is not causal
-  int t_cut;
+  bool causal;  // causal window (App. A): query w of the window sees keys 0 .. T-W+w
 };
 
 template <bool BF16>
@@ -115,7 +113,7 @@ __device__ __forceinline__ void tile_mma(const uint4 (&av)[Tr<BF16>::kAVecs], co
 
 __device__ __forceinline__ int acc_row(int i, int hf) { return 8 * (i >> 2) + 4 * hf + (i & 3); }
 
-// Sum of 16 per-lane values over the 32 lanes of a half wave, halving the number of live values
+// Sum (or maximum) of 16 per-lane values over the 32 lanes of a half wave, halving the number of live values
 // at every exchange.  Lane c ends up with the total of value index c >> 1.
 // Exchanges: rows of 16 lanes swap through v_permlane16_swap (bit 4 of the lane), then DPP
 // row_ror:8 (bit 3), row_half_mirror (lane <-> 7 - lane inside groups of 8: the partner has the
@@ -132,28 +130,30 @@ __device__ __forceinline__ float dpp_xor2(float x) {
 __device__ __forceinline__ float dpp_xor1(float x) {
   return __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0xB1, 0xf, 0xf, true));
 }
+template <bool MAX = false>
 __device__ __forceinline__ float reduce16_over32(const float (&v)[16], int c) {
+  auto op = [](float x, float y) __attribute__((always_inline)) { return MAX ? fmaxf(x, y) : x + y; };
   float w8[8], w4[4], w2[2];
   const bool b3 = c & 8, b2 = c & 4, b1 = c & 2;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     // even rows receive the partner row's v[j], odd rows the partner row's v[j + 8]
     const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v[j]), __float_as_uint(v[j + 8]), false, false);
-    w8[j] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    w8[j] = op(__uint_as_float(r[0]), __uint_as_float(r[1]));
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const float keep = b3 ? w8[j + 4] : w8[j], send = b3 ? w8[j] : w8[j + 4];
-    w4[j] = keep + dpp_ror8(send);
+    w4[j] = op(keep, dpp_ror8(send));
   }
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const float keep = b2 ? w4[j + 2] : w4[j], send = b2 ? w4[j] : w4[j + 2];
-    w2[j] = keep + dpp_half_mirror(send);
+    w2[j] = op(keep, dpp_half_mirror(send));
   }
   const float keep = b1 ? w2[1] : w2[0], send = b1 ? w2[0] : w2[1];
-  const float w1 = keep + dpp_xor2(send);
-  return w1 + dpp_xor1(w1);
+  const float w1 = op(keep, dpp_xor2(send));
+  return op(w1, dpp_xor1(w1));
 }
 
 }  // namespace ams

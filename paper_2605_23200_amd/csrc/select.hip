@@ -469,14 +469,14 @@ __device__ __forceinline__ uint32_t range_bits(int w, int lo, int hi) {
   return upto_b & ~((1u << a) - 1u);
 }
 
-constexpr int kFinBlock = 256;
+constexpr int kFinBlock = 1024;
 constexpr int kFinWaves = kFinBlock / 64;
 
 __global__ __launch_bounds__(kFinBlock) void finalize_kernel(Dims d, const int32_t* seq_lens, int budget,
                                                              int n_sink, int n_last, const float* g_all,
                                                              uint32_t* flags_all, int n_words,
                                                              int32_t* idx_all) {
-  __shared__ int hist[256];
+  __shared__ int hist[4][256];
   __shared__ uint32_t sel_prefix;
   __shared__ int sel_rem;
   __shared__ int red[kFinWaves];
@@ -517,18 +517,19 @@ __global__ __launch_bounds__(kFinBlock) void finalize_kernel(Dims d, const int32
     uint32_t prefix = 0, mask = 0;
     rem = deficit;
     for (int shift = 24; shift >= 0; shift -= 8) {
-      for (int i = threadIdx.x; i < 256; i += kFinBlock) hist[i] = 0;
+      (&hist[0][0])[threadIdx.x] = 0;
       __syncthreads();
       for (int t = threadIdx.x; t < T; t += kFinBlock) {
         if ((flags[t >> 5] >> (t & 31)) & 1u) continue;
         const uint32_t k = score_key(g[t]);
-        if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+        if ((k & mask) == prefix) atomicAdd(&hist[wave & 3][(k >> shift) & 255], 1);
       }
       __syncthreads();
       if (wave == 0) {
         int hb[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) hb[i] = hist[lane * 4 + i];
+        for (int i = 0; i < 4; ++i)
+          hb[i] = (hist[0][lane * 4 + i] + hist[1][lane * 4 + i]) + (hist[2][lane * 4 + i] + hist[3][lane * 4 + i]);
         const int s = hb[0] + hb[1] + hb[2] + hb[3];
         int incl = s;  // sum over lanes >= this one
 #pragma unroll
@@ -555,36 +556,25 @@ __global__ __launch_bounds__(kFinBlock) void finalize_kernel(Dims d, const int32
     thr = prefix;
   }
 
-  // ascending index list: every thread owns one word of 32 positions per round
+  // ascending index list, one position per thread and round; a position is kept when its bit is set
+  // or its score is above the threshold, and the first rem positions equal to the threshold join
   int base_keep = 0, base_eq = 0;
-  for (int w0 = 0; w0 < nw; w0 += kFinBlock) {
-    const int w = w0 + threadIdx.x;
-    uint32_t f = 0u, gt = 0u, eq = 0u;
-    if (w < nw) {
-      f = flags[w];
-      if (fill) {
-        const int t_end = min(32, T - w * 32);
-        for (int j = 0; j < t_end; ++j) {
-          if ((f >> j) & 1u) continue;
-          const uint32_t k = score_key(g[w * 32 + j]);
-          gt |= (uint32_t)(k > thr) << j;
-          eq |= (uint32_t)(k == thr) << j;
-        }
+  const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  for (int t0 = 0; t0 < T; t0 += kFinBlock) {
+    const int t = t0 + threadIdx.x;
+    bool keep = false, eq = false;
+    if (t < T) {
+      keep = (flags[t >> 5] >> (t & 31)) & 1u;
+      if (fill && !keep) {
+        const uint32_t k = score_key(g[t]);
+        keep = k > thr;
+        eq = k == thr;
       }
     }
-    const int c_keep = __popc(f | gt), c_eq = __popc(eq);
-    int i_keep = c_keep, i_eq = c_eq;  // inclusive scans within the wave
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int vk = __shfl_up(i_keep, o), ve = __shfl_up(i_eq, o);
-      if (lane >= o) {
-        i_keep += vk;
-        i_eq += ve;
-      }
-    }
-    if (lane == 63) wave_cnt[wave] = make_int2(i_keep, i_eq);
+    const uint64_t bk = __ballot(keep), be = __ballot(eq);
+    if (lane == 0) wave_cnt[wave] = make_int2(__popcll(bk), __popcll(be));
     __syncthreads();
-    int n_keep = base_keep + i_keep - c_keep, n_eq = base_eq + i_eq - c_eq;
+    int n_keep = base_keep + __popcll(bk & below), n_eq = base_eq + __popcll(be & below);
     int tot_keep = 0, tot_eq = 0;
 #pragma unroll
     for (int v = 0; v < kFinWaves; ++v) {
@@ -596,17 +586,10 @@ __global__ __launch_bounds__(kFinBlock) void finalize_kernel(Dims d, const int32
       tot_keep += c.x;
       tot_eq += c.y;
     }
-    for (uint32_t m = f | gt | eq; m; m &= m - 1) {
-      const int j = __ffs((int)m) - 1;
-      const int t = w * 32 + j;
-      if ((eq >> j) & 1u) {
-        if (n_eq < rem) idx[n_keep + n_eq] = t;
-        ++n_eq;
-      } else {
-        idx[n_keep + min(n_eq, rem)] = t;
-        ++n_keep;
-      }
-    }
+    if (keep)
+      idx[n_keep + min(n_eq, rem)] = t;
+    else if (eq && n_eq < rem)
+      idx[n_keep + n_eq] = t;
     base_keep += tot_keep;
     base_eq += tot_eq;
     __syncthreads();
