@@ -471,16 +471,19 @@ __device__ __forceinline__ uint32_t range_bits(int w, int lo, int hi) {
 
 constexpr int kFinBlock = 1024;
 constexpr int kFinWaves = kFinBlock / 64;
+constexpr int kFinPer = 32;  // positions per thread whose keys stay in registers (T <= 32768)
 
 __global__ __launch_bounds__(kFinBlock) void finalize_kernel(Dims d, const int32_t* seq_lens, int budget,
                                                              int n_sink, int n_last, const float* g_all,
                                                              uint32_t* flags_all, int n_words,
                                                              int32_t* idx_all) {
-  __shared__ int hist[4][256];
-  __shared__ uint32_t sel_prefix;
+  __shared__ int hist[kFinWaves][256];
+  __shared__ uint32_t sel_digit;
   __shared__ int sel_rem;
   __shared__ int red[kFinWaves];
+  __shared__ uint32_t red_and[kFinWaves], red_or[kFinWaves];
   __shared__ int2 wave_cnt[kFinWaves];
+  __shared__ uint32_t bm[kFinBlock];  // the bitmap of a sequence of up to 32768 positions
   const int unit = blockIdx.x;
   int l, b, h;
   unit_coords(d, unit, l, b, h);
@@ -493,12 +496,19 @@ __global__ __launch_bounds__(kFinBlock) void finalize_kernel(Dims d, const int32
   int32_t* idx = idx_all + (int64_t)unit * budget;
   const int nw = (T + 31) >> 5;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // Up to 32768 positions the bitmap is worked on in LDS and the keys are read once into registers;
+  // longer sequences keep the bitmap in memory and re-read the scores in every pass.
+  const bool inreg = T <= kFinBlock * kFinPer;
 
   // union with the must-keep positions; size of the union
   int cnt = 0;
+  if (inreg) bm[threadIdx.x] = 0u;
   for (int w = threadIdx.x; w < nw; w += kFinBlock) {
     const uint32_t f = flags[w] | range_bits(w, 0, sinks) | range_bits(w, T - last, T);
-    flags[w] = f;
+    if (inreg)
+      bm[w] = f;
+    else
+      flags[w] = f;
     cnt += __popc(f);
   }
   cnt = wave_sum(cnt);
@@ -510,56 +520,183 @@ __global__ __launch_bounds__(kFinBlock) void finalize_kernel(Dims d, const int32
   const int deficit = kept - cnt;  // positions the duplicates left open; never negative
   const bool fill = deficit > 0;
 
+  // Keys of the positions outside the set (0 = in the set or past the end; no score maps to 0).
+  uint32_t kreg[kFinPer];
+  auto key_at = [&](int t) __attribute__((always_inline)) -> uint32_t {
+    if (t >= T) return 0u;
+    const uint32_t word = inreg ? bm[t >> 5] : flags[t >> 5];
+    return ((word >> (t & 31)) & 1u) ? 0u : score_key(g[t]);
+  };
+  if (fill && inreg) {
+#pragma unroll
+    for (int j = 0; j < kFinPer; ++j) kreg[j] = key_at(threadIdx.x + j * kFinBlock);
+  }
+
   // key of the deficit-th largest score among the positions outside the set
   uint32_t thr = 0xFFFFFFFFu;
   int rem = 0;
   if (fill) {
-    uint32_t prefix = 0, mask = 0;
-    rem = deficit;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-      (&hist[0][0])[threadIdx.x] = 0;
-      __syncthreads();
+    // bits that are the same in every key need no radix pass
+    uint32_t k_and = 0xFFFFFFFFu, k_or = 0u;
+    if (inreg) {
+#pragma unroll
+      for (int j = 0; j < kFinPer; ++j)
+        if (kreg[j]) {
+          k_and &= kreg[j];
+          k_or |= kreg[j];
+        }
+    } else {
       for (int t = threadIdx.x; t < T; t += kFinBlock) {
-        if ((flags[t >> 5] >> (t & 31)) & 1u) continue;
-        const uint32_t k = score_key(g[t]);
-        if ((k & mask) == prefix) atomicAdd(&hist[wave & 3][(k >> shift) & 255], 1);
-      }
-      __syncthreads();
-      if (wave == 0) {
-        int hb[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          hb[i] = (hist[0][lane * 4 + i] + hist[1][lane * 4 + i]) + (hist[2][lane * 4 + i] + hist[3][lane * 4 + i]);
-        const int s = hb[0] + hb[1] + hb[2] + hb[3];
-        int incl = s;  // sum over lanes >= this one
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          const int v = __shfl_down(incl, o);
-          if (lane + o < 64) incl += v;
-        }
-        int cum = incl - s;  // keys in bins above this lane's
-#pragma unroll
-        for (int i = 3; i >= 0; --i) {
-          if (cum < rem && rem <= cum + hb[i]) {
-            sel_prefix = prefix | ((uint32_t)(lane * 4 + i) << shift);
-            sel_rem = rem - cum;
-          }
-          cum += hb[i];
+        const uint32_t k = key_at(t);
+        if (k) {
+          k_and &= k;
+          k_or |= k;
         }
       }
-      __syncthreads();
-      prefix = sel_prefix;
-      rem = sel_rem;
-      mask |= 0xFFu << shift;
-      __syncthreads();
     }
-    thr = prefix;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      k_and &= __shfl_xor(k_and, o);
+      k_or |= __shfl_xor(k_or, o);
+    }
+    if (lane == 0) {
+      red_and[wave] = k_and;
+      red_or[wave] = k_or;
+    }
+    __syncthreads();
+    k_and = 0xFFFFFFFFu;
+    k_or = 0u;
+#pragma unroll
+    for (int w = 0; w < kFinWaves; ++w) {
+      k_and &= red_and[w];
+      k_or |= red_or[w];
+    }
+    const uint32_t diff = k_and ^ k_or;
+    thr = k_and;  // all keys equal: the threshold is that key
+    rem = deficit;
+    if (diff != 0) {
+      const int hb = 31 - __clz(diff);  // highest bit in which two keys differ
+      uint32_t mask = hb == 31 ? 0u : ~((2u << hb) - 1u);  // bits known so far
+      uint32_t prefix = k_and & mask;
+      int shift = max(hb - 7, 0);
+      for (;;) {
+        for (int i = threadIdx.x; i < kFinWaves * 256; i += kFinBlock) (&hist[0][0])[i] = 0;
+        __syncthreads();
+        if (inreg) {
+#pragma unroll
+          for (int j = 0; j < kFinPer; ++j) {
+            const uint32_t k = kreg[j];
+            if (k && (k & mask) == prefix) atomicAdd(&hist[wave][(k >> shift) & 255], 1);
+          }
+        } else {
+          for (int t = threadIdx.x; t < T; t += kFinBlock) {
+            const uint32_t k = key_at(t);
+            if (k && (k & mask) == prefix) atomicAdd(&hist[wave][(k >> shift) & 255], 1);
+          }
+        }
+        __syncthreads();
+        if (wave == 0) {
+          int hbin[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            hbin[i] = 0;
+#pragma unroll
+            for (int w = 0; w < kFinWaves; ++w) hbin[i] += hist[w][lane * 4 + i];
+          }
+          const int s = hbin[0] + hbin[1] + hbin[2] + hbin[3];
+          int incl = s;  // sum over lanes >= this one
+#pragma unroll
+          for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_down(incl, o);
+            if (lane + o < 64) incl += v;
+          }
+          int cum = incl - s;  // keys in bins above this lane's
+#pragma unroll
+          for (int i = 3; i >= 0; --i) {
+            if (cum < rem && rem <= cum + hbin[i]) {
+              sel_digit = (uint32_t)(lane * 4 + i);
+              sel_rem = rem - cum;
+            }
+            cum += hbin[i];
+          }
+        }
+        __syncthreads();
+        // the digit may overlap bits that are already known; OR-ing it in is then a no-op for those bits
+        prefix |= sel_digit << shift;
+        rem = sel_rem;
+        mask = shift == 0 ? 0xFFFFFFFFu : ~((1u << shift) - 1u);
+        __syncthreads();
+        if (shift == 0) break;
+        shift = max(shift - 8, 0);
+      }
+      thr = prefix;
+    }
   }
 
-  // ascending index list, one position per thread and round; a position is kept when its bit is set
-  // or its score is above the threshold, and the first rem positions equal to the threshold join
-  int base_keep = 0, base_eq = 0;
   const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  if (inreg) {
+    // the positions that fill the gap get their bits: everything above the threshold, and of the
+    // positions equal to it the first rem in index order
+    if (fill) {
+      int c_eq = 0;
+#pragma unroll
+      for (int j = 0; j < kFinPer; ++j) c_eq += kreg[j] == thr;
+      c_eq = wave_sum(c_eq);
+      if (lane == 0) red[wave] = c_eq;
+      __syncthreads();
+      c_eq = 0;
+#pragma unroll
+      for (int w = 0; w < kFinWaves; ++w) c_eq += red[w];
+      const bool all_eq = c_eq == rem;  // no choice to make among equal scores
+#pragma unroll
+      for (int j = 0; j < kFinPer; ++j) {
+        const int t = threadIdx.x + j * kFinBlock;
+        if (kreg[j] > thr || (all_eq && kreg[j] == thr)) atomicOr(&bm[t >> 5], 1u << (t & 31));
+      }
+      if (!all_eq) {
+        int base_eq = 0;  // equal scores met so far, in index order (round j covers 1024 consecutive positions)
+#pragma unroll
+        for (int j = 0; j < kFinPer; ++j) {
+          if (j * kFinBlock < T && base_eq < rem) {
+            const int t = threadIdx.x + j * kFinBlock;
+            const bool eq = kreg[j] == thr;
+            const uint64_t be = __ballot(eq);
+            if (lane == 0) red[wave] = __popcll(be);
+            __syncthreads();
+            int n_eq = base_eq + __popcll(be & below), tot = 0;
+#pragma unroll
+            for (int v = 0; v < kFinWaves; ++v) {
+              if (v < wave) n_eq += red[v];
+              tot += red[v];
+            }
+            if (eq && n_eq < rem) atomicOr(&bm[t >> 5], 1u << (t & 31));
+            base_eq += tot;
+            __syncthreads();
+          }
+        }
+      }
+      __syncthreads();
+    }
+    // ascending index list read off the bitmap: one word per thread
+    const uint32_t f = bm[threadIdx.x];
+    const int c = __popc(f);
+    int incl = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o);
+      if (lane >= o) incl += v;
+    }
+    if (lane == 63) wave_cnt[wave].x = incl;
+    __syncthreads();
+    int slot = incl - c;
+    for (int v = 0; v < wave; ++v) slot += wave_cnt[v].x;
+    for (uint32_t m = f; m; m &= m - 1) idx[slot++] = threadIdx.x * 32 + __ffs((int)m) - 1;
+    return;
+  }
+
+  // long sequences: one position per thread and round; a position is kept when its bit is set or its
+  // score is above the threshold, and the first rem positions equal to the threshold join
+  int base_keep = 0, base_eq = 0;
   for (int t0 = 0; t0 < T; t0 += kFinBlock) {
     const int t = t0 + threadIdx.x;
     bool keep = false, eq = false;
