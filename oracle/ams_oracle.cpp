@@ -200,6 +200,91 @@ int amso_segment(const float* m_used, int T, int S, int32_t* bounds, float* seg_
   return 0;
 }
 
+// 1-D average pooling of the usage scores (App. A "Mass construction"; Alg. 1 step 1
+// "optionally smooth"): window of `kernel` positions centred on t, cut at the ends of
+// the sequence (the mean is over the positions that exist).
+int amso_pool(const float* u, int T, int kernel, float* out) {
+  if (!u || !out || T < 1 || kernel < 1 || kernel % 2 == 0) return -1;
+  const int r = kernel / 2;
+  for (int t = 0; t < T; ++t) {
+    const int lo = std::max(0, t - r), hi = std::min(T - 1, t + r);
+    double sum = 0.0;
+    for (int j = lo; j <= hi; ++j) sum += (double)u[j];
+    out[t] = (float)(sum / (double)(hi - lo + 1));
+  }
+  return 0;
+}
+
+// Alg. 1 step 3 as printed (Sec. 3.3 "Mass-based adaptive segmentation"): cut points at the
+// thresholds k*delta (every k >= 1 with k*delta < 1), then one pass over the initial segments,
+// left to right: a segment longer than l_max is split into ceil(L / l_max) parts whose lengths
+// differ by at most one (the longer parts first); a segment shorter than l_min is merged into
+// its left neighbour (the segment produced last), the very first one into its right neighbour
+// (it is prepended to the next initial segment before that one is looked at); empty initial
+// segments vanish.  l_max == 0 / l_min == 0 switch the respective rule off.
+// bounds has cap+1 entries, seg_mass cap; entries past the *n_seg segments are T and 0.
+int amso_segment_adaptive(const float* m_used, int T, float delta, int l_min, int l_max, int cap,
+                          int32_t* bounds, float* seg_mass, int32_t* n_seg) {
+  if (!m_used || !bounds || !seg_mass || !n_seg || T < 1 || cap < 1) return -1;
+  if (!(delta > 0.0f) || l_min < 0 || l_max < 0 || (l_max > 0 && l_min > l_max)) return -1;
+  // initial cut points
+  std::vector<int> cuts;
+  cuts.push_back(0);
+  {
+    int k = 1;
+    double c = 0.0;
+    for (int t = 0; t < T; ++t) {
+      c += (double)m_used[t];
+      while ((double)k * (double)delta < 1.0 && c >= (double)k * (double)delta) {
+        cuts.push_back(t + 1);  // the crossing token closes the earlier segment
+        ++k;
+      }
+    }
+    // thresholds below 1 that the curve never reached close empty segments at the end
+    cuts.push_back(T);
+  }
+  std::vector<int> out;  // ends of the final segments
+  int start = 0;         // start of the segment being formed (moves left of an initial start only
+                         // for a too-short first segment)
+  bool have_left = false;
+  for (size_t i = 0; i + 1 < cuts.size(); ++i) {
+    const int b = cuts[i + 1];
+    const int L = b - start;
+    if (L == 0) continue;
+    if (l_max > 0 && L > l_max) {
+      const int n = (L + l_max - 1) / l_max, base = L / n, extra = L % n;
+      int e = start;
+      for (int j = 0; j < n; ++j) {
+        e += base + (j < extra ? 1 : 0);
+        out.push_back(e);
+      }
+      have_left = true;
+      start = b;
+    } else if (l_min > 0 && L < l_min) {
+      if (have_left) {
+        out.back() = b;  // into the left neighbour
+        start = b;
+      }
+      // else: first segment, kept open; the next initial segment starts at `start`
+    } else {
+      out.push_back(b);
+      have_left = true;
+      start = b;
+    }
+  }
+  if (start < T) out.push_back(T);  // the whole sequence was one too-short segment
+  if ((int)out.size() > cap) return -5;
+  *n_seg = (int32_t)out.size();
+  bounds[0] = 0;
+  for (int i = 0; i < cap; ++i) bounds[i + 1] = i < (int)out.size() ? out[(size_t)i] : T;
+  for (int i = 0; i < cap; ++i) {
+    double m = 0.0;
+    for (int t = bounds[i]; t < bounds[i + 1]; ++t) m += (double)m_used[t];
+    seg_mass[i] = (float)m;
+  }
+  return 0;
+}
+
 // Quotas: floor q_min, remainder shared in proportion to segment mass, no
 // segment above its length, total exactly min(budget, T).
 int amso_quota(const int32_t* bounds, const float* seg_mass, int S, int budget,
@@ -406,9 +491,20 @@ int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K
   std::vector<int32_t> bd((size_t)S + 1), qt((size_t)S);
   int rc;
   if ((rc = amso_score(Q, K, p->G, p->W, T, p->D, p->scorer, p->causal, u_.data(), g_.data()))) return rc;
-  if ((rc = amso_mass(u_.data(), T, p->eps, mc.data()))) return rc;
+  std::vector<float> up;  // smoothed usage feeds the mass only; the base score keeps the raw one
+  if (p->pool_kernel > 1) {
+    up.resize((size_t)T);
+    if ((rc = amso_pool(u_.data(), T, p->pool_kernel, up.data()))) return rc;
+  }
+  if ((rc = amso_mass(up.empty() ? u_.data() : up.data(), T, p->eps, mc.data()))) return rc;
   if ((rc = amso_ema(mc.data(), credit, T, p->lambda, p->beta, mu.data()))) return rc;
-  if ((rc = amso_segment(mu.data(), T, S, bd.data(), sm.data()))) return rc;
+  if (p->delta > 0.0f) {  // S is the capacity of the segment arrays
+    int32_t n_seg = 0;
+    if ((rc = amso_segment_adaptive(mu.data(), T, p->delta, p->l_min, p->l_max, S, bd.data(), sm.data(), &n_seg)))
+      return rc;
+  } else if ((rc = amso_segment(mu.data(), T, S, bd.data(), sm.data()))) {
+    return rc;
+  }
   int sink_eff, last_eff, seg_budget;
   if ((rc = amso_must_keep(T, p->budget, p->n_sink, p->n_last, &sink_eff, &last_eff, &seg_budget))) return rc;
   if ((rc = amso_quota(bd.data(), sm.data(), S, seg_budget, p->q_min, qt.data()))) return rc;

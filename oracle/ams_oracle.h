@@ -21,7 +21,9 @@
  * the expected-attention score; raw-key mean in the key-diversity score; which
  * probability stands in for a missing causal observation (the per-key maximum
  * over the pairs that see the key); the order in which equal scores are
- * trimmed or backfilled.
+ * trimmed or backfilled; the split / merge rules of amso_segment_adaptive
+ * (the paper says "roughly equal" and "a neighboring segment") and the edge
+ * handling of amso_pool.
  */
 #ifndef AMS_ORACLE_H
 #define AMS_ORACLE_H
@@ -62,6 +64,19 @@ int amso_ema(const float* m_cur, float* credit, int T, float lambda, float beta,
  * bounds[S]=T, bounds[k] = 1 + first 0-based j whose inclusive prefix sum
  * reaches k/S (T if none).  seg_mass[i] = sum of m over [bounds[i],bounds[i+1]). */
 int amso_segment(const float* m_used, int T, int S, int32_t* bounds, float* seg_mass);
+
+/* Alg. 1 step 1 "optionally smooth" / App. A: mean of u over the `kernel` (odd)
+ * positions centred on t that exist. */
+int amso_pool(const float* u, int T, int kernel, float* out);
+
+/* Alg. 1 step 3 as printed: thresholds k*delta (k*delta < 1), then split
+ * (> l_max: ceil(L/l_max) near-equal parts, longer parts first) and merge
+ * (< l_min: into the left neighbour; the first one into the right) in one pass
+ * from the left; 0 switches a rule off.  bounds [cap+1], seg_mass [cap]; unused
+ * entries are T and 0; *n_seg = number of segments (all non-empty).  -5 if cap
+ * is too small. */
+int amso_segment_adaptive(const float* m_used, int T, float delta, int l_min, int l_max, int cap,
+                          int32_t* bounds, float* seg_mass, int32_t* n_seg);
 
 /* Alg. 1 step 4: minimum quota, proportional share of the remainder, clip to
  * the segment length, adjust so the quotas sum to min(budget, T).  budget may be
@@ -112,6 +127,9 @@ typedef struct {
   float lambda, beta, eps;
   int n_sink, n_last; /* must-keep sizes; 0, 0 = none */
   int causal;         /* see amso_score */
+  float delta;        /* > 0: amso_segment_adaptive with S as the capacity; 0: amso_segment(S) */
+  int l_min, l_max;   /* with delta > 0 */
+  int pool_kernel;    /* > 1: amso_pool before Eq. (1) */
 } amso_unit_params;
 
 int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K,

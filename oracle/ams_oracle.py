@@ -20,7 +20,8 @@ class _UnitParams(C.Structure):
     _fields_ = [("G", C.c_int), ("W", C.c_int), ("T", C.c_int), ("D", C.c_int),
                 ("scorer", C.c_int), ("budget", C.c_int), ("S", C.c_int), ("q_min", C.c_int),
                 ("lam", C.c_float), ("beta", C.c_float), ("eps", C.c_float),
-                ("n_sink", C.c_int), ("n_last", C.c_int), ("causal", C.c_int)]
+                ("n_sink", C.c_int), ("n_last", C.c_int), ("causal", C.c_int),
+                ("delta", C.c_float), ("l_min", C.c_int), ("l_max", C.c_int), ("pool_kernel", C.c_int)]
 
 
 def lib():
@@ -88,6 +89,24 @@ def segment(m_used, S):
     seg_mass = np.empty(S, np.float32)
     _chk(lib().amso_segment(_f(m_used), len(m_used), S, _i(bounds), _f(seg_mass)), "segment")
     return bounds, seg_mass
+
+
+def pool(u, kernel):
+    u = np.ascontiguousarray(u, np.float32)
+    out = np.empty_like(u)
+    _chk(lib().amso_pool(_f(u), len(u), int(kernel), _f(out)), "pool")
+    return out
+
+
+def segment_adaptive(m_used, delta, l_min, l_max, cap):
+    """-> (bounds [cap+1], seg_mass [cap], n_seg)."""
+    m_used = np.ascontiguousarray(m_used, np.float32)
+    bounds = np.empty(cap + 1, np.int32)
+    seg_mass = np.empty(cap, np.float32)
+    n = C.c_int32(0)
+    _chk(lib().amso_segment_adaptive(_f(m_used), len(m_used), C.c_float(delta), int(l_min), int(l_max), int(cap),
+                                     _i(bounds), _f(seg_mass), C.byref(n)), "segment_adaptive")
+    return bounds, seg_mass, n.value
 
 
 def quota(bounds, seg_mass, budget, q_min=1):
@@ -162,7 +181,8 @@ def compact_paged(K_pool, V_pool, src_table, K_pool_out, V_pool_out, dst_table, 
 
 
 def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_min=1,
-                  scorer=SCORER_MEAN_WINDOW, n_sink=0, n_last=0, causal=False):
+                  scorer=SCORER_MEAN_WINDOW, n_sink=0, n_last=0, causal=False, delta=0.0, l_min=0, l_max=0,
+                  pool_kernel=0):
     """One whole event for one unit.  K, V [T, D] in storage dtype (float32 or
     uint16 = bf16 bits).  Returns a dict with every intermediate."""
     Kf = np.ascontiguousarray(widen(K))
@@ -172,7 +192,7 @@ def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, 
     T, D = Kf.shape
     kept = min(budget, T)
     p = _UnitParams(G, W, T, D, int(scorer), int(budget), int(S), int(q_min), lam, beta, eps,
-                    int(n_sink), int(n_last), int(bool(causal)))
+                    int(n_sink), int(n_last), int(bool(causal)), delta, int(l_min), int(l_max), int(pool_kernel))
     c = np.array(credit, dtype=np.float32, copy=True)
     out = dict(u=np.empty(T, np.float32), g=np.empty(T, np.float32), m_used=np.empty(T, np.float32),
                bounds=np.empty(S + 1, np.int32), seg_mass=np.empty(S, np.float32),
@@ -193,7 +213,7 @@ def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, 
 
 def compress_many(Q, K, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_min=1,
                   scorer=SCORER_MEAN_WINDOW, n_threads=0, want_scores=False, K_rows=None, V_rows=None,
-                  n_sink=0, n_last=0, causal=False):
+                  n_sink=0, n_last=0, causal=False, delta=0.0, l_min=0, l_max=0, pool_kernel=0):
     """Q [U, G*W, D], K [U, T, D] float32 (already widened), credit [U, T] (updated in
     place).  K_rows, V_rows [U, T, D] in the storage dtype: when given, the kept rows are
     gathered as well (whole event).  Returns (idx [U, budget], n_kept [U], threads_used[, u, g])."""
@@ -202,7 +222,7 @@ def compress_many(Q, K, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_m
     for a in (Q, K, credit):
         assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"]
     p = _UnitParams(G, W, T, D, int(scorer), int(budget), int(S), int(q_min), lam, beta, eps,
-                    int(n_sink), int(n_last), int(bool(causal)))
+                    int(n_sink), int(n_last), int(bool(causal)), delta, int(l_min), int(l_max), int(pool_kernel))
     idx = np.empty((U, budget), np.int32)
     n_kept = np.empty(U, np.int32)
     u = np.empty((U, T), np.float32) if want_scores else None
