@@ -80,6 +80,13 @@ typedef struct {
   int32_t n_sink;     /* must-keep: first n_sink positions always kept (Sec. 3.3); 0 = none */
   int32_t n_last;     /* must-keep: last n_last positions always kept; 0 = none            */
   int32_t causal;     /* 1: causal window with padded observations (App. A), see ams_score */
+  float seg_delta;    /* 0: exactly n_segments segments of target mass 1/n_segments.
+                         > 0: target mass Delta as printed (Sec. 3.3), variable number of
+                         segments; n_segments is then the CAPACITY of the per-unit segment
+                         arrays, see ams_mass_segment                                      */
+  int32_t l_min;      /* seg_delta > 0: segments shorter than this are merged (0 = off)    */
+  int32_t l_max;      /* seg_delta > 0: segments longer than this are split (0 = off)      */
+  int32_t pool_kernel;/* odd k > 1: Eq. (1) sees the k-point centred mean of u (App. A); 0/1 = off */
 } ams_params;
 
 /* A KV cache as the library sees it.  Plain data, [host]; k, v, block_table [dev]. */
@@ -145,7 +152,9 @@ int ams_score(const ams_params* p, const ams_kv_view* src, const int32_t* seq_le
 /*
  * ams_ema_update - Eq. (1) followed by the EMA credit (Sec. 3.3 "EMA Credit for
  * Temporal Stability"; Alg. 1 step 2):
- *   m = normalize(max(u,0)+eps); credit <- lambda*credit + (1-lambda)*m;
+ *   m = normalize(max(u',0)+eps), u' = u or, with pool_kernel = k > 1, the mean of u
+ *   over the k positions centred on t that exist (App. A; Alg. 1 step 1);
+ *   credit <- lambda*credit + (1-lambda)*m;
  *   m_used = normalize(beta*m + (1-beta)*normalize(credit)).
  * lambda == 0: m_used = m and credit <- m.
  *   u [dev] in; credit [dev] in/out; m_used [dev] out; all fp32 [units, t_stride]
@@ -156,9 +165,18 @@ int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u,
 
 /*
  * ams_mass_segment - prefix sum of the mass and cut points (Sec. 3.3
- * "Mass-based adaptive segmentation"; Alg. 1 step 3) with Delta = 1/S:
+ * "Mass-based adaptive segmentation"; Alg. 1 step 3).
+ * seg_delta == 0 (Delta = 1/S, no length rules, exactly S = n_segments segments):
  *   bounds[0] = 0, bounds[S] = T, bounds[k] = 1 + min{ j : c(j) >= k/S } (T if the
  *   threshold is never reached); seg_mass[i] = sum of m_used over segment i.
+ * seg_delta > 0 (as printed): cut points at the thresholds k*Delta (every k >= 1 with
+ *   k*Delta < 1), then one pass over the initial segments from the left: a segment
+ *   longer than l_max is split into ceil(L/l_max) parts whose lengths differ by at most
+ *   one (longer parts first); a segment shorter than l_min joins its left neighbour,
+ *   the very first one its right neighbour; empty segments vanish.  All resulting
+ *   segments are non-empty; entries of bounds / seg_mass past them are T / 0.
+ *   n_segments must be at least ceil(1/Delta) + t_max / l_max (AMS_ERR_INVALID_ARG
+ *   otherwise), Delta at least 1/1024.
  *   bounds [dev] int32 [units, S+1]; seg_mass [dev] fp32 [units, S]
  *   ws [dev] scratch of at least ams_workspace_bytes(p)
  */

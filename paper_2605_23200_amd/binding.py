@@ -39,7 +39,8 @@ class Params(C.Structure):
                 ("kv_dtype", C.c_int32), ("t_max", C.c_int32), ("t_stride", C.c_int64),
                 ("budget", C.c_int32), ("n_segments", C.c_int32), ("q_min", C.c_int32),
                 ("ema_lambda", C.c_float), ("ema_beta", C.c_float), ("mass_eps", C.c_float),
-                ("scorer", C.c_int32), ("n_sink", C.c_int32), ("n_last", C.c_int32), ("causal", C.c_int32)]
+                ("scorer", C.c_int32), ("n_sink", C.c_int32), ("n_last", C.c_int32), ("causal", C.c_int32),
+                ("seg_delta", C.c_float), ("l_min", C.c_int32), ("l_max", C.c_int32), ("pool_kernel", C.c_int32)]
 
     @property
     def units(self) -> int:
@@ -113,10 +114,12 @@ def _check(rc: int, what: str):
 
 def make_params(*, n_layers, batch, n_kv_heads, group, window, head_dim=128, kv_dtype=BF16, t_max,
                 t_stride=None, budget, n_segments, q_min=1, ema_lambda=0.9, ema_beta=0.9, mass_eps=1e-6,
-                scorer=SCORER_MEAN_WINDOW, n_sink=0, n_last=0, causal=False) -> Params:
+                scorer=SCORER_MEAN_WINDOW, n_sink=0, n_last=0, causal=False, seg_delta=0.0, l_min=0, l_max=0,
+                pool_kernel=0) -> Params:
     return Params(n_layers, batch, n_kv_heads, group, head_dim, window, kv_dtype, t_max,
                   t_stride if t_stride is not None else t_max, budget, n_segments, q_min,
-                  ema_lambda, ema_beta, mass_eps, scorer, int(n_sink), int(n_last), int(bool(causal)))
+                  ema_lambda, ema_beta, mass_eps, scorer, int(n_sink), int(n_last), int(bool(causal)),
+                  float(seg_delta), int(l_min), int(l_max), int(pool_kernel))
 
 
 def dense_view(k: torch.Tensor, v: Optional[torch.Tensor]) -> KvView:

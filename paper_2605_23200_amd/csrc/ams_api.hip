@@ -57,6 +57,15 @@ static int check_params(const ams_params* p) {
       p->q_min < 0 || p->n_sink < 0 || p->n_last < 0 || (p->causal != 0 && p->causal != 1))
     return AMS_ERR_INVALID_ARG;
   if (p->kv_dtype != AMS_F32 && p->kv_dtype != AMS_BF16) return AMS_ERR_INVALID_ARG;
+  if (!(p->seg_delta >= 0.f) || p->l_min < 0 || p->l_max < 0 || p->pool_kernel < 0) return AMS_ERR_INVALID_ARG;
+  if (p->pool_kernel > 1 && (p->pool_kernel % 2 == 0 || p->pool_kernel > 63)) return AMS_ERR_INVALID_ARG;
+  if (p->seg_delta == 0.f && (p->l_min != 0 || p->l_max != 0)) return AMS_ERR_INVALID_ARG;
+  if (p->seg_delta > 0.f) {
+    if (p->seg_delta < 1.f / 1024.f || (p->l_max > 0 && p->l_min > p->l_max)) return AMS_ERR_INVALID_ARG;
+    // room for every segment the split / merge pass can produce
+    const int64_t most = (int64_t)initial_segments(p->seg_delta) + (p->l_max > 0 ? p->t_max / p->l_max : 0);
+    if (p->n_segments < most) return AMS_ERR_INVALID_ARG;
+  }
   if (!(p->ema_lambda >= 0.f && p->ema_lambda < 1.f) || !(p->ema_beta >= 0.f && p->ema_beta <= 1.f) ||
       !(p->mass_eps > 0.f) || isinf(p->mass_eps))
     return AMS_ERR_INVALID_ARG;
@@ -305,11 +314,16 @@ int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t
     return AMS_ERR_HIP;
   if ((e = launch_ema(p, d, seq_lens, u, credit, m_used, bounds, vc, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;
-  if ((e = launch_segment(p, d, seq_lens, m_used, bounds, nullptr, true, w, wl, s)) != hipSuccess)
+  // exactly-S mode: the quota kernel forms the segment masses from the scan's prefix at the cuts;
+  // Delta mode: the cuts move in the split / merge pass and the masses are summed per segment
+  const bool adaptive = p->seg_delta > 0.f;
+  if ((e = launch_segment(p, d, seq_lens, m_used, bounds, adaptive ? seg_mass : nullptr, true, w, wl, s)) !=
+      hipSuccess)
     return AMS_ERR_HIP;
-  if ((e = launch_select(p, d, seq_lens, g, bounds, seg_mass, quota, idx, n_kept, (const double*)(w + wl.cpre),
-                         (const double*)(w + wl.mpart), wl.n_chunks4k, (uint32_t*)(w + wl.flags), wl.n_words,
-                         s)) != hipSuccess)
+  if ((e = launch_select(p, d, seq_lens, g, bounds, seg_mass, quota, idx, n_kept,
+                         adaptive ? nullptr : (const double*)(w + wl.cpre),
+                         adaptive ? nullptr : (const double*)(w + wl.mpart), wl.n_chunks4k,
+                         (uint32_t*)(w + wl.flags), wl.n_words, s)) != hipSuccess)
     return AMS_ERR_HIP;
   if ((e = launch_compact(p, d, make_kv(p, src, src->k), make_kv(p, src, src->v), make_kv(p, dst, dst->k),
                           make_kv(p, dst, dst->v), idx, n_kept, credit, credit_dst, s)) != hipSuccess)

@@ -51,6 +51,13 @@ __device__ __forceinline__ void unit_coords(const Dims& d, int unit, int& l, int
 constexpr int kScoreChunk = AMS_SCORE_CHUNK;  // tokens per workgroup of the scoring kernels
 constexpr int kChunk = 4096;       // positions per workgroup of the mass / prefix kernels
 
+// Segments the thresholds k*delta (every k >= 1 with k*delta < 1) cut the unit interval into.
+inline int initial_segments(float delta) {
+  int k = 1;
+  while (k <= 4096 && (double)k * (double)delta < 1.0) ++k;
+  return k;
+}
+
 inline int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 // Workspace carving (offsets in bytes, 256-byte aligned).

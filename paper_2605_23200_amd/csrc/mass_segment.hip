@@ -1,5 +1,6 @@
 // Eq. (1) + EMA credit (Sec. 3.2, 3.3; Alg. 1 steps 1-2) and the mass prefix sum with its cut
-// points (Sec. 3.3 "Mass-based adaptive segmentation"; Alg. 1 step 3, Delta = 1/S).
+// points (Sec. 3.3 "Mass-based adaptive segmentation"; Alg. 1 step 3): thresholds k/S for exactly S
+// segments, or k*Delta followed by the split / merge pass over the segment lengths.
 //
 // All of it is elementwise work plus a few sums over T, so every unit is cut into chunks of 4096
 // positions and each (chunk, unit) is one workgroup: the chip is filled even with few units.
@@ -9,6 +10,8 @@
 //   chunk_total_kernel   (stand-alone segmentation only) chunk totals of a given m_used
 //   segment_scan_kernel  inclusive prefix P(j) and the first j with P(j) >= k/S for every k
 //   segment_finalize_kernel  segment masses from the prefix at the cuts
+//   resegment_kernel     (Delta mode) split above L_max / merge below L_min, one pass from the left
+//   segment_mass_kernel  (Delta mode) segment masses by summing m_used over the final segments
 //
 // Normalisers: Z is the actual sum of max(u,0)+eps.  The credit normaliser sum(c_new) is taken as
 // lambda * sum(c_old) + (1 - lambda) and the outer normaliser as 1: both identities hold exactly in
@@ -137,7 +140,11 @@ struct MsArgs {
   Dims d;
   const int32_t* seq_lens;
   int n_chunks;      // chunks per unit (stride of the per-chunk arrays)
-  int S;
+  int S;             // entries of the per-unit segment arrays
+  int K;             // initial segments: thresholds k = 1..K-1 (K == S unless delta > 0)
+  double delta;      // > 0: thresholds k*delta; 0: thresholds k/S
+  int l_min, l_max;  // delta > 0 only: length rules of the split / merge pass (0 = off)
+  int pool_r;        // radius of the average pooling of u before Eq. (1) (0 = off)
   double2* vc_part;  // [units][vc_stride] (sum of max(u,0)+eps, sum of old credit) per vc_tokens positions
   int vc_stride, vc_tokens;
   double* mpart;     // [units][n_chunks]  chunk totals of m_used
@@ -152,6 +159,21 @@ __device__ __forceinline__ void init_cuts(const MsArgs& a, int unit, int T) {
   for (int k = threadIdx.x; k <= a.S; k += kBlock) {
     bounds[k] = (k == 0) ? 0 : T;
     cpre[k] = (k == 0) ? 0.0 : -1.0;
+  }
+}
+
+// Usage as Eq. (1) sees it: with pooling (App. A; Alg. 1 step 1 "optionally smooth") the mean of u
+// over the positions t-r .. t+r that exist, rounded to fp32 like a stored intermediate.
+__device__ __forceinline__ void pool_run(const float* u, int j0, int T, int r, float (&x)[kPer]) {
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) {
+    const int t = j0 + i;
+    if (t < T) {
+      const int lo = max(0, t - r), hi = min(T - 1, t + r);
+      double sum = 0.0;
+      for (int j = lo; j <= hi; ++j) sum += (double)u[j];
+      x[i] = (float)(sum / (double)(hi - lo + 1));
+    }
   }
 }
 
@@ -170,6 +192,7 @@ __global__ __launch_bounds__(kBlock) void vc_sums_kernel(MsArgs a, const float* 
   float ux[kPer], cx[kPer];
   load_run(u, j0, T, a.vec, ux, 0.f);
   load_run(credit, j0, T, a.vec, cx, 0.f);
+  if (a.pool_r > 0) pool_run(u, j0, T, a.pool_r, ux);
 #pragma unroll
   for (int i = 0; i < kPer; ++i)
     if (j0 + i < T) {
@@ -200,6 +223,7 @@ __global__ __launch_bounds__(kBlock) void mass_ema_kernel(MsArgs a, const float*
   float mu[kPer], ux[kPer], cx[kPer];
   load_run(u, j0, T, a.vec, ux, 0.f);  // in flight while the normalisers are summed
   load_run(credit, j0, T, a.vec, cx, 0.f);
+  if (a.pool_r > 0) pool_run(u, j0, T, a.pool_r, ux);
   const int nvc = (T + a.vc_tokens - 1) / a.vc_tokens;
   const double2 zc = ordered_sum2(a.vc_part + (int64_t)unit * a.vc_stride, nvc, &sums);
   const double Z = zc.x, c_old = zc.y;
@@ -244,10 +268,11 @@ __global__ __launch_bounds__(kBlock) void chunk_total_kernel(MsArgs a, const flo
   if (threadIdx.x == 0) a.mpart[(int64_t)unit * a.n_chunks + chunk] = total;
 }
 
-// Number of thresholds k/S, k = 1..S-1, that are <= c.  thr[k] holds (double)k / (double)S, the
-// exact value the comparison is defined with; the table keeps divisions out of the per-thread path.
-__device__ __forceinline__ int thresholds_reached(double c, int S, const double* thr) {
-  int f = (int)floor(c * (double)S);
+// Number of thresholds thr[k], k = 1..S-1, that are <= c.  thr[k] holds (double)k / (double)S (or
+// (double)k * delta), the exact value the comparison is defined with; the table keeps divisions out
+// of the per-thread path.  scale (S or 1/delta) only gives the first guess.
+__device__ __forceinline__ int thresholds_reached(double c, int S, const double* thr, double scale) {
+  int f = (int)floor(c * scale);
   f = max(0, min(S - 1, f));
   while (f < S - 1 && c >= thr[f + 1]) ++f;
   while (f > 0 && c < thr[f]) --f;
@@ -266,7 +291,9 @@ __global__ __launch_bounds__(kBlock) void segment_scan_kernel(MsArgs a, const fl
   if (chunk * kChunk >= T) return;
   const float* m = m_all + (int64_t)unit * a.d.t_stride;
   __shared__ double2 sums;
-  for (int k = threadIdx.x; k <= a.S; k += kBlock) thr[k] = (double)k / (double)a.S;
+  const int K = a.K;
+  const double scale = a.delta > 0.0 ? 1.0 / a.delta : (double)a.S;
+  for (int k = threadIdx.x; k <= K; k += kBlock) thr[k] = a.delta > 0.0 ? (double)k * a.delta : (double)k / (double)a.S;
   const int j0 = chunk * kChunk + threadIdx.x * kPer;
   float x[kPer];
   load_run(m, j0, T, a.vec, x, 0.f);
@@ -276,19 +303,19 @@ __global__ __launch_bounds__(kBlock) void segment_scan_kernel(MsArgs a, const fl
   ends[threadIdx.x] = C + p[kPer - 1];
   __syncthreads();
   const double prev_end = threadIdx.x > 0 ? ends[threadIdx.x - 1] : C;
-  int f_prev = thresholds_reached(prev_end, a.S, thr);
+  int f_prev = thresholds_reached(prev_end, K, thr, scale);
   int32_t* bounds = a.bounds + (int64_t)unit * (a.S + 1);
   double* cpre = a.cpre + (int64_t)unit * (a.S + 1);
   // most threads see no threshold between their neighbour's prefix and their own largest one
   double p_max = p[0];
 #pragma unroll
   for (int i = 1; i < kPer; ++i) p_max = fmax(p_max, p[i]);
-  if (thresholds_reached(C + p_max, a.S, thr) <= f_prev) return;
+  if (thresholds_reached(C + p_max, K, thr, scale) <= f_prev) return;
 #pragma unroll
   for (int i = 0; i < kPer; ++i) {
     if (j0 + i < T) {
       const double P = C + p[i];
-      const int f_cur = thresholds_reached(P, a.S, thr);
+      const int f_cur = thresholds_reached(P, K, thr, scale);
       for (int k = f_prev + 1; k <= f_cur; ++k) {  // position j0+i is the first to reach k/S
         atomicMin(&bounds[k], j0 + i + 1);
         cpre[k] = P;
@@ -314,6 +341,70 @@ __global__ void segment_finalize_kernel(MsArgs a, float* seg_mass_all) {
   }
 }
 
+// Delta mode, after the cut points: one pass over the initial segments from the left (Alg. 1 step 3,
+// the loop over segments).  Longer than l_max: ceil(L / l_max) parts whose lengths differ by at most
+// one, the longer ones first.  Shorter than l_min: joins the segment to its left; the first one
+// stays open and the next initial segment starts where it started.  Empty initial segments vanish.
+// The pass is a short serial chain (at most K steps) and runs on one lane per unit; the new bounds
+// are staged in LDS because they overwrite the old ones.
+__global__ __launch_bounds__(64) void resegment_kernel(MsArgs a) {
+  __shared__ int32_t out[kMaxSegments + 1];
+  __shared__ int n_out;
+  const int unit = blockIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  int32_t* bounds = a.bounds + (int64_t)unit * (a.S + 1);
+  if (threadIdx.x == 0) {
+    int n = 0, start = 0;
+    bool have_left = false;
+    for (int i = 1; i <= a.K; ++i) {
+      const int e = i == a.K ? T : bounds[i];
+      const int L = e - start;
+      if (L == 0) continue;
+      if (a.l_max > 0 && L > a.l_max) {
+        const int parts = (L + a.l_max - 1) / a.l_max, base = L / parts, extra = L % parts;
+        int pos = start;
+        for (int j = 0; j < parts && n < a.S; ++j) {
+          pos += base + (j < extra ? 1 : 0);
+          out[n++] = pos;
+        }
+        have_left = true;
+        start = e;
+      } else if (a.l_min > 0 && L < a.l_min) {
+        if (have_left) {
+          out[n - 1] = e;
+          start = e;
+        }
+      } else {
+        if (n < a.S) out[n++] = e;
+        have_left = true;
+        start = e;
+      }
+    }
+    if (start < T && n < a.S) out[n++] = T;  // the whole sequence was one too-short segment
+    if (n > 0) out[n - 1] = T;               // (only matters if the capacity cut the list short)
+    n_out = n;
+  }
+  __syncthreads();
+  const int n = n_out;
+  for (int i = threadIdx.x; i < a.S; i += 64) bounds[i + 1] = i < n ? out[i] : T;
+}
+
+// Mass of every final segment: one wave per (segment, unit), strided partial sums in double, then
+// a fixed tree over the lanes.
+__global__ __launch_bounds__(64) void segment_mass_kernel(MsArgs a, const float* m_all, float* seg_mass_all) {
+  const int unit = blockIdx.y, seg = blockIdx.x;
+  const int32_t* bounds = a.bounds + (int64_t)unit * (a.S + 1);
+  const int lo = bounds[seg], hi = bounds[seg + 1];
+  const float* m = m_all + (int64_t)unit * a.d.t_stride;
+  double s = 0.0;
+  for (int t = lo + threadIdx.x; t < hi; t += 64) s += (double)m[t];
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
+  if (threadIdx.x == 0) seg_mass_all[(int64_t)unit * a.S + seg] = (float)s;
+}
+
 MsArgs make_args(const ams_params* p, const Dims& d, const int32_t* seq_lens, char* ws, const WsLayout& wl,
                  int32_t* bounds) {
   MsArgs a;
@@ -321,6 +412,11 @@ MsArgs make_args(const ams_params* p, const Dims& d, const int32_t* seq_lens, ch
   a.seq_lens = seq_lens;
   a.n_chunks = wl.n_chunks4k;
   a.S = p->n_segments;
+  a.delta = (double)p->seg_delta;
+  a.K = p->seg_delta > 0.f ? initial_segments(p->seg_delta) : p->n_segments;
+  a.l_min = p->l_min;
+  a.l_max = p->l_max;
+  a.pool_r = p->pool_kernel > 1 ? p->pool_kernel / 2 : 0;
   a.vc_part = (double2*)(ws + wl.vc_part);
   a.vc_stride = wl.n_chunks4k;
   a.vc_tokens = kChunk;
@@ -339,7 +435,7 @@ hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_len
   MsArgs a = make_args(p, d, seq_lens, ws, wl, bounds);
   a.vec = d.t_stride % 4 == 0 && (((uintptr_t)u | (uintptr_t)credit | (uintptr_t)m_used) & 15) == 0;
   const dim3 grid(a.n_chunks, d.units);
-  if (vc.have) {  // left by the scorer
+  if (vc.have && a.pool_r == 0) {  // left by the scorer (sums of the unsmoothed usage)
     a.vc_stride = vc.stride;
     a.vc_tokens = vc.tokens;
   } else {
@@ -364,6 +460,14 @@ hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq
   }
   prof_mark("segment_scan", s);
   hipLaunchKernelGGL(segment_scan_kernel, grid, dim3(kBlock), 0, s, a, m_used);
+  if (a.delta > 0.0) {  // the cuts move, so the masses cannot come from the prefix at the cuts
+    if (!seg_mass) return hipErrorInvalidValue;
+    prof_mark("resegment", s);
+    hipLaunchKernelGGL(resegment_kernel, dim3(d.units), dim3(64), 0, s, a);
+    prof_mark("segment_mass", s);
+    hipLaunchKernelGGL(segment_mass_kernel, dim3(a.S, d.units), dim3(64), 0, s, a, m_used, seg_mass);
+    return hipGetLastError();
+  }
   if (seg_mass) {
     prof_mark("segment_finalize", s);
     hipLaunchKernelGGL(segment_finalize_kernel, dim3(d.units), dim3(64), 0, s, a, seg_mass);

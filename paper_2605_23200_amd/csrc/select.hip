@@ -1,8 +1,9 @@
 // Segment quotas, in-segment top-k and the kept set (Sec. 3.3 "Segment-wise Quota Allocation",
 // "In-Segment Selection" and the must-keep rules; Alg. 1 steps 4-5).
 //
-// quota_kernel   one wave per unit; the arithmetic is a handful of double operations per segment
-//                and is done in index order so that it is reproducible bit for bit.
+// quota_kernel   one wave per unit (up to 64 segments; a workgroup of 256 threads above that); the
+//                arithmetic is a handful of double operations per segment and is done in index
+//                order so that it is reproducible bit for bit.
 // select_kernel  one workgroup per (segment, unit): radix select (4 x 8 bits, most significant
 //                digit first) of the quota-th largest score on an order-preserving integer image
 //                of the floats, then an ordered compaction that keeps everything above the
@@ -86,38 +87,35 @@ __device__ __forceinline__ int quota_wave(int S, int bud, int q_min, const int32
   return quo;
 }
 
-// cpre_all / mpart_all (optional): prefix of the mass at the cuts and chunk totals as the prefix-sum
-// kernel left them; when given, the segment masses are formed here (and stored) instead of being read.
-__global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_lens, int S, int budget,
-                                                   int q_min, const int32_t* bounds_all,
-                                                   float* seg_mass_all, int32_t* quota_all,
-                                                   int32_t* idx_all, int32_t* n_kept_all,
-                                                   const double* cpre_all, const double* mpart_all,
-                                                   int n_chunks, int n_sink, int n_last,
-                                                   uint32_t* flags_all, int n_words) {
-  __shared__ int32_t len[kMaxSeg], room[kMaxSeg], quo[kMaxSeg];
-  __shared__ double raw[kMaxSeg];
-  __shared__ uint8_t active[kMaxSeg];
-  const int unit = blockIdx.x;
+// What both quota kernels do before the quotas: segment masses from the raw output of the prefix-sum
+// kernel (cpre_all / mpart_all, optional: when given, the masses are formed and stored here instead of
+// being read), the -1 tail of idx, the kept count, the cleared bitmap of the must-keep path.
+// Returns the budget the segments share.
+__device__ __forceinline__ int quota_prologue(const Dims& d, const int32_t* seq_lens, int S, int budget,
+                                              float* seg_mass_all, int32_t* idx_all, int32_t* n_kept_all,
+                                              const double* cpre_all, const double* mpart_all, int n_chunks,
+                                              int n_sink, int n_last, uint32_t* flags_all, int n_words) {
+  const int unit = blockIdx.x, nthr = blockDim.x;
   int l, b, h;
   unit_coords(d, unit, l, b, h);
   const int T = seq_lens[b];
-  const int32_t* bounds = bounds_all + (int64_t)unit * (S + 1);
   float* mass = seg_mass_all + (int64_t)unit * S;
   if (cpre_all) {
     const int nch = (T + kChunk - 1) / kChunk;
-    double total = 0.0;  // chunk totals in index order
-    for (int base = 0; base < nch; base += 64) {
-      const int k = min(64, nch - base);
-      double v = 0.0;
-      if ((int)threadIdx.x < k) v = mpart_all[(int64_t)unit * n_chunks + base + threadIdx.x];
-      for (int j = 0; j < k; ++j) total += __shfl(v, j);
-    }
-    const double* cpre = cpre_all + (int64_t)unit * (S + 1);
-    for (int i = threadIdx.x; i < S; i += 64) {
-      const double lo = cpre[i] < 0.0 ? total : cpre[i];
-      const double hi = (i + 1 == S || cpre[i + 1] < 0.0) ? total : cpre[i + 1];
-      mass[i] = (float)(hi - lo);
+    double total = 0.0;  // chunk totals in index order, by the first wave; the others wait at the barrier
+    if (threadIdx.x < 64) {
+      for (int base = 0; base < nch; base += 64) {
+        const int k = min(64, nch - base);
+        double v = 0.0;
+        if ((int)threadIdx.x < k) v = mpart_all[(int64_t)unit * n_chunks + base + threadIdx.x];
+        for (int j = 0; j < k; ++j) total += __shfl(v, j);
+      }
+      const double* cpre = cpre_all + (int64_t)unit * (S + 1);
+      for (int i = threadIdx.x; i < S; i += 64) {
+        const double lo = cpre[i] < 0.0 ? total : cpre[i];
+        const double hi = (i + 1 == S || cpre[i + 1] < 0.0) ? total : cpre[i + 1];
+        mass[i] = (float)(hi - lo);
+      }
     }
     __syncthreads();
   }
@@ -126,95 +124,149 @@ __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_le
   const int kept = min(budget, T);
   const int sinks = min(n_sink, kept);
   const int bud = kept - sinks - min(n_last, kept - sinks);
-  int32_t* quota = quota_all + (int64_t)unit * S;
   int32_t* idx = idx_all + (int64_t)unit * budget;
   // entries of idx beyond the kept count are -1
-  for (int j = kept + threadIdx.x; j < budget; j += 64) idx[j] = -1;
+  for (int j = kept + threadIdx.x; j < budget; j += nthr) idx[j] = -1;
   if (threadIdx.x == 0) n_kept_all[unit] = kept;
   if (flags_all)
-    for (int j = threadIdx.x; j < n_words; j += 64) flags_all[(int64_t)unit * n_words + j] = 0u;
-  if (S <= 64) {
-    const int q = quota_wave(S, bud, q_min, bounds, mass);
-    if (threadIdx.x < S) quota[threadIdx.x] = q;
-    return;
+    for (int j = threadIdx.x; j < n_words; j += nthr) flags_all[(int64_t)unit * n_words + j] = 0u;
+  return bud;
+}
+
+// Up to 64 segments: one wave per unit.
+__global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_lens, int S, int budget,
+                                                   int q_min, const int32_t* bounds_all,
+                                                   float* seg_mass_all, int32_t* quota_all,
+                                                   int32_t* idx_all, int32_t* n_kept_all,
+                                                   const double* cpre_all, const double* mpart_all,
+                                                   int n_chunks, int n_sink, int n_last,
+                                                   uint32_t* flags_all, int n_words) {
+  const int unit = blockIdx.x;
+  const int bud = quota_prologue(d, seq_lens, S, budget, seg_mass_all, idx_all, n_kept_all, cpre_all, mpart_all,
+                                 n_chunks, n_sink, n_last, flags_all, n_words);
+  const int q = quota_wave(S, bud, q_min, bounds_all + (int64_t)unit * (S + 1), seg_mass_all + (int64_t)unit * S);
+  if (threadIdx.x < S) quota_all[(int64_t)unit * S + threadIdx.x] = q;
+}
+
+// More than 64 segments (up to 1024): one workgroup of 256 threads per unit, the segments in LDS.
+// Integer sums are order-free; the sum of the masses of the open segments is taken by one thread
+// in index order, the same order as plain C, so that every share is the same double.
+constexpr int kQuotaBlock = 256;
+
+__device__ __forceinline__ int block_sum_int(int v, int* sm) {
+  v = wave_sum(v);
+  __syncthreads();  // sm may still be read from a previous call
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (sm[0] + sm[1]) + (sm[2] + sm[3]);
+}
+
+__global__ __launch_bounds__(kQuotaBlock) void quota_block_kernel(Dims d, const int32_t* seq_lens, int S,
+                                                                  int budget, int q_min,
+                                                                  const int32_t* bounds_all, float* seg_mass_all,
+                                                                  int32_t* quota_all, int32_t* idx_all,
+                                                                  int32_t* n_kept_all, const double* cpre_all,
+                                                                  const double* mpart_all, int n_chunks,
+                                                                  int n_sink, int n_last, uint32_t* flags_all,
+                                                                  int n_words) {
+  __shared__ int32_t len[kMaxSeg], room[kMaxSeg], quo[kMaxSeg];
+  __shared__ double mass_d[kMaxSeg], raw[kMaxSeg];
+  __shared__ uint8_t active[kMaxSeg], can[kMaxSeg];
+  __shared__ int red[4];
+  __shared__ double msum_sm;
+  const int unit = blockIdx.x;
+  const int bud = quota_prologue(d, seq_lens, S, budget, seg_mass_all, idx_all, n_kept_all, cpre_all, mpart_all,
+                                 n_chunks, n_sink, n_last, flags_all, n_words);
+  const int32_t* bounds = bounds_all + (int64_t)unit * (S + 1);
+  const float* mass = seg_mass_all + (int64_t)unit * S;
+  int c_nonempty = 0, c_need = 0;
+  for (int i = threadIdx.x; i < S; i += kQuotaBlock) {
+    len[i] = bounds[i + 1] - bounds[i];
+    mass_d[i] = (double)mass[i];
+    c_nonempty += len[i] > 0;
+    c_need += min(q_min, len[i]);
   }
-  // more than 64 segments: the same arithmetic, serially
-  if (threadIdx.x == 0) {
-    int nonempty = 0;
-    for (int i = 0; i < S; ++i) {
-      len[i] = bounds[i + 1] - bounds[i];
-      nonempty += len[i] > 0;
-    }
-    int floor_q = q_min;
-    long long need = 0;
-    for (int i = 0; i < S; ++i) need += min(floor_q, len[i]);
-    if (need > bud) floor_q = nonempty > 0 ? bud / nonempty : 0;
-    int rem = bud;
-    for (int i = 0; i < S; ++i) {
-      const int lo = min(floor_q, len[i]);
-      room[i] = len[i] - lo;
-      active[i] = room[i] > 0;
-      quo[i] = lo;
-      rem -= lo;
-      raw[i] = 0.0;
-    }
-    for (;;) {
-      int n_active = 0;
+  const int nonempty = block_sum_int(c_nonempty, red);
+  const int need = block_sum_int(c_need, red);
+  int floor_q = q_min;
+  if (need > bud) floor_q = nonempty > 0 ? bud / nonempty : 0;
+  int c_lo = 0;
+  for (int i = threadIdx.x; i < S; i += kQuotaBlock) {
+    const int lo = min(floor_q, len[i]);
+    room[i] = len[i] - lo;
+    active[i] = room[i] > 0;
+    quo[i] = lo;
+    raw[i] = 0.0;
+    c_lo += lo;
+  }
+  int rem = bud - block_sum_int(c_lo, red);
+  // proportional shares; a segment whose share reaches its room is filled and leaves the pool
+  for (;;) {
+    int c_act = 0;
+    for (int i = threadIdx.x; i < S; i += kQuotaBlock) c_act += active[i];
+    const int n_active = block_sum_int(c_act, red);
+    if (n_active == 0 || rem <= 0) break;
+    if (threadIdx.x == 0) {
       double msum = 0.0;
       for (int i = 0; i < S; ++i)
-        if (active[i]) {
-          ++n_active;
-          msum += (double)mass[i];
-        }
-      if (n_active == 0 || rem <= 0) break;
-      for (int i = 0; i < S; ++i)
-        if (active[i])
-          raw[i] = msum > 0.0 ? (double)rem * (double)mass[i] / msum : (double)rem / (double)n_active;
-      bool filled = false;
-      int taken = 0;
-      for (int i = 0; i < S; ++i)
-        if (active[i] && raw[i] >= (double)room[i]) {
-          quo[i] = len[i];
-          taken += room[i];
-          active[i] = 0;
-          filled = true;
-        }
-      rem -= taken;
-      if (!filled) break;
+        if (active[i]) msum += mass_d[i];
+      msum_sm = msum;
     }
-    if (rem > 0) {
-      int given = 0;
-      for (int i = 0; i < S; ++i)
-        if (active[i]) {
-          const double fl = floor(raw[i]);
-          raw[i] -= fl;  // now the fractional part
-          quo[i] += (int)fl;
-          given += (int)fl;
+    __syncthreads();
+    const double msum = msum_sm;
+    int c_sat = 0, c_taken = 0;
+    for (int i = threadIdx.x; i < S; i += kQuotaBlock)
+      if (active[i]) {
+        raw[i] = msum > 0.0 ? (double)rem * mass_d[i] / msum : (double)rem / (double)n_active;
+        if (raw[i] >= (double)room[i]) {
+          quo[i] = len[i];
+          active[i] = 0;
+          ++c_sat;
+          c_taken += room[i];
         }
-      int left = rem - given;
-      // a served segment is marked with a negative part until the round is over
-      while (left > 0) {
-        int best = -1;
-        for (int i = 0; i < S; ++i)
-          if (active[i] && raw[i] >= 0.0 && quo[i] < len[i] && (best < 0 || raw[i] > raw[best])) best = i;
-        if (best < 0) {
-          bool any = false;
-          for (int i = 0; i < S; ++i)
-            if (active[i] && raw[i] < 0.0) {
-              raw[i] = -raw[i] - 1.0;
-              any = any || quo[i] < len[i];
-            }
-          if (!any) break;
-          continue;
-        }
-        ++quo[best];
-        raw[best] = -raw[best] - 1.0;
-        --left;
       }
+    const int n_sat = block_sum_int(c_sat, red);
+    rem -= block_sum_int(c_taken, red);
+    if (n_sat == 0) break;
+  }
+  if (rem > 0) {
+    int c_given = 0;
+    for (int i = threadIdx.x; i < S; i += kQuotaBlock)
+      if (active[i]) {
+        const double fl = floor(raw[i]);
+        raw[i] -= fl;  // now the fractional part
+        quo[i] += (int)fl;
+        c_given += (int)fl;
+      }
+    int left = rem - block_sum_int(c_given, red);
+    // one extra each, largest fractional part first, equal parts by lower segment index
+    while (left > 0) {
+      int c_can = 0;
+      for (int i = threadIdx.x; i < S; i += kQuotaBlock) {
+        can[i] = active[i] && quo[i] < len[i];
+        c_can += can[i];
+      }
+      const int n_can = block_sum_int(c_can, red);
+      if (n_can == 0) break;
+      int c_take = 0;
+      for (int i = threadIdx.x; i < S; i += kQuotaBlock)
+        if (can[i]) {
+          int rank = 0;
+          if (n_can > left) {  // otherwise everybody is served
+            const double fi = raw[i];
+            for (int j = 0; j < S; ++j)
+              if (can[j] && (raw[j] > fi || (raw[j] == fi && j < i))) ++rank;
+          }
+          if (rank < left) {
+            ++quo[i];
+            ++c_take;
+          }
+        }
+      left -= block_sum_int(c_take, red);
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < S; i += 64) quota[i] = quo[i];
+  for (int i = threadIdx.x; i < S; i += kQuotaBlock) quota_all[(int64_t)unit * S + i] = quo[i];
 }
 
 // Order-preserving image of a score: larger float <-> larger unsigned; -0 and +0 coincide and
@@ -744,9 +796,14 @@ hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_
   const bool must = p->n_sink > 0 || p->n_last > 0;
   if (must && !flags) return hipErrorInvalidValue;
   prof_mark("quota", s);
-  hipLaunchKernelGGL(quota_kernel, dim3(d.units), dim3(64), 0, s, d, seq_lens, S, p->budget, p->q_min,
-                     bounds, seg_mass, quota, idx, n_kept, cpre, mpart, n_chunks, p->n_sink, p->n_last,
-                     must ? flags : nullptr, n_words);
+  if (S <= 64)
+    hipLaunchKernelGGL(quota_kernel, dim3(d.units), dim3(64), 0, s, d, seq_lens, S, p->budget, p->q_min,
+                       bounds, seg_mass, quota, idx, n_kept, cpre, mpart, n_chunks, p->n_sink, p->n_last,
+                       must ? flags : nullptr, n_words);
+  else
+    hipLaunchKernelGGL(quota_block_kernel, dim3(d.units), dim3(kQuotaBlock), 0, s, d, seq_lens, S, p->budget,
+                       p->q_min, bounds, seg_mass, quota, idx, n_kept, cpre, mpart, n_chunks, p->n_sink,
+                       p->n_last, must ? flags : nullptr, n_words);
   prof_mark("select", s);
   if (!must) {
     hipLaunchKernelGGL(select_kernel<false>, dim3(S, d.units), dim3(kSelBlock), 0, s, d, S, p->budget, g,

@@ -32,7 +32,8 @@ class Job:
                                t_max=self.t_max, t_stride=self.t_stride, budget=w.budget,
                                n_segments=w.S, q_min=w.q_min, ema_lambda=w.lam, ema_beta=w.beta,
                                mass_eps=w.eps, scorer=scorer, n_sink=w.n_sink, n_last=w.n_last,
-                               causal=w.causal)
+                               causal=w.causal, seg_delta=w.seg_delta, l_min=w.l_min, l_max=w.l_max,
+                               pool_kernel=w.pool_kernel)
         self.units = w.units
         self.keep = min(w.budget, self.t_max)
         self.lens = _dev(lens, device)

@@ -53,6 +53,10 @@ class Workload:
     n_sink: int = 0       # must-keep sizes (0, 0: none)
     n_last: int = 0
     causal: bool = False  # causal window with padded observations
+    seg_delta: float = 0.0  # > 0: target segment mass as printed, S is then the capacity of the segment arrays
+    l_min: int = 0
+    l_max: int = 0
+    pool_kernel: int = 0  # odd k > 1: k-point average pooling of the usage before Eq. (1)
 
     @property
     def N(self) -> int:

@@ -26,7 +26,8 @@ def params_for(w: inputs.Workload, scorer=B.SCORER_MEAN_WINDOW, t_stride=None, *
     kw = dict(n_layers=w.L, batch=w.B, n_kv_heads=w.H, group=w.G, window=w.W, head_dim=w.D,
               kv_dtype=B.F32 if w.dtype == "f32" else B.BF16, t_max=w.T, t_stride=t_stride or w.T,
               budget=w.budget, n_segments=w.S, q_min=w.q_min, ema_lambda=w.lam, ema_beta=w.beta,
-              mass_eps=w.eps, scorer=scorer, n_sink=w.n_sink, n_last=w.n_last, causal=w.causal)
+              mass_eps=w.eps, scorer=scorer, n_sink=w.n_sink, n_last=w.n_last, causal=w.causal,
+              seg_delta=w.seg_delta, l_min=w.l_min, l_max=w.l_max, pool_kernel=w.pool_kernel)
     kw.update(over)
     return B.make_params(**kw)
 

@@ -163,6 +163,82 @@ def test_segment_exact_cases(oracle):
     np.testing.assert_array_equal(bounds[0], np.arange(9) * 512)
 
 
+@pytest.mark.parametrize("T", [1, 500, 4096, 10000, 70001])
+@pytest.mark.parametrize("delta,l_min,l_max", [(0.1, 16, 256), (0.1, 0, 0), (0.01, 0, 200), (0.3, 100, 0),
+                                               (0.125, 32, 128), (0.5, 3000, 0)])
+def test_segment_as_printed_parity(oracle, T, delta, l_min, l_max):
+    """Thresholds k*Delta, split above L_max, merge below L_min (Sec. 3.3; Alg. 1 step 3)."""
+    rng = np.random.default_rng(T + int(1000 * delta))
+    units = 5
+    cap = int(np.ceil(1 / delta)) + 1 + (T // l_max if l_max else 0)
+    m = np.stack([oracle.mass((rng.random(T) ** e).astype(np.float32)) for e in (1, 3, 8, 20, 40)])
+    m[1] = 1.0 / T                                                       # uniform: thresholds hit exactly or by rounding
+    p = _vec_params(units, T, S=cap)
+    p.seg_delta, p.l_min, p.l_max = delta, l_min, l_max
+    bounds = torch.full((units, cap + 1), -3, dtype=torch.int32, device=DEV)
+    seg_mass = torch.full((units, cap), -3.0, device=DEV)
+    B.ams_mass_segment(p, to_dev(np.array([T], np.int32)), to_dev(m), bounds, seg_mass, workspace(p))
+    torch.cuda.synchronize()
+    bounds, seg_mass = to_host(bounds), to_host(seg_mass)
+    for i in range(units):
+        bo, so, n = oracle.segment_adaptive(m[i], delta, l_min, l_max, cap)
+        np.testing.assert_array_equal(bounds[i], bo, err_msg=f"unit {i}")
+        assert_close_rel(seg_mass[i], so, what=f"seg_mass unit {i}")
+
+
+def test_segment_as_printed_rejects_small_capacity():
+    p = _vec_params(1, 4096, S=20)
+    p.seg_delta, p.l_max = 0.1, 128                                      # needs 10 + 32 entries
+    z = torch.zeros(4096, device=DEV)
+    zi = torch.zeros(64, dtype=torch.int32, device=DEV)
+    with pytest.raises(B.AmsError):
+        B.ams_mass_segment(p, zi, z, zi, z, z)
+
+
+@pytest.mark.parametrize("T", [1, 7, 4096, 10000])
+@pytest.mark.parametrize("kernel", [3, 5, 9])
+def test_ema_with_pooled_usage_parity(oracle, T, kernel):
+    rng = np.random.default_rng(T + kernel)
+    units = 3
+    u = (rng.standard_normal((units, T)) ** 3).astype(np.float32) / T
+    credit = (rng.random((units, T)) / T).astype(np.float32)
+    p = _vec_params(units, T, lam=0.9, beta=0.9, t_stride=T + 3)
+    p.pool_kernel = kernel
+    pad = lambda a: np.pad(a, ((0, 0), (0, 3)), constant_values=9.0)
+    u_d, c_d = to_dev(pad(u)), to_dev(pad(credit))
+    m_d = torch.full((units, T + 3), 9.0, device=DEV)
+    B.ams_ema_update(p, to_dev(np.array([T], np.int32)), u_d, c_d, m_d, workspace(p))
+    torch.cuda.synchronize()
+    m_g, c_g = to_host(m_d), to_host(c_d)
+    for i in range(units):
+        m_o, c_o = oracle.ema(oracle.mass(oracle.pool(u[i], kernel), 1e-6), credit[i], 0.9, 0.9)
+        assert_close_rel(m_g[i, :T], m_o, what=f"m_used unit {i}")
+        assert_close_rel(c_g[i, :T], c_o, what=f"credit unit {i}")
+        assert (m_g[i, T:] == 9.0).all()
+
+
+def test_quota_many_segments(oracle):
+    # more than 64 segments: the workgroup-wide quota kernel; ties, empty segments, binding caps
+    rng = np.random.default_rng(21)
+    for S in (65, 200, 1000):
+        for budget in (5, S // 2, 3 * S, 40 * S):
+            lens = rng.integers(0, 60, size=S)
+            lens[rng.integers(0, S)] += 7
+            bounds = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)[None]
+            mass = (rng.integers(0, 9, size=S) / 16).astype(np.float32)
+            mass[lens == 0] = 0
+            mass = mass[None]
+            Ti = int(bounds[0, -1])
+            p = _vec_params(1, Ti, S=S, budget=budget)
+            quota = torch.zeros((1, S), dtype=torch.int32, device=DEV)
+            idx = torch.zeros((1, budget), dtype=torch.int32, device=DEV)
+            n_kept = torch.zeros(1, dtype=torch.int32, device=DEV)
+            B.ams_select(p, to_dev(np.array([Ti], np.int32)), torch.zeros((1, Ti), device=DEV), to_dev(bounds),
+                         to_dev(mass), quota, idx, n_kept)
+            np.testing.assert_array_equal(to_host(quota)[0], oracle.quota(bounds[0], mass[0], budget, 1),
+                                          err_msg=f"S {S} budget {budget}")
+
+
 def _select(g, bounds, seg_mass, budget, T, q_min=1):
     units, S = seg_mass.shape
     p = _vec_params(units, T, S=S, budget=budget)

@@ -56,10 +56,14 @@ def check_units(oracle, job, host, credit_before, units, scorer=B.SCORER_MEAN_WI
                 assert_close_rel(g_g[j, :T], go, what=f"g unit {i}")
             else:
                 assert_close_norm(g_g[j, :T], go, what=f"g unit {i}")
-        m_o, c_o = oracle.ema(oracle.mass(u_g[j, :T], w.eps), credit_before[i, :T], w.lam, w.beta)
+        u_mass = oracle.pool(u_g[j, :T], w.pool_kernel) if w.pool_kernel > 1 else u_g[j, :T]
+        m_o, c_o = oracle.ema(oracle.mass(u_mass, w.eps), credit_before[i, :T], w.lam, w.beta)
         assert_close_rel(m_g[j, :T], m_o, what=f"m_used unit {i}")
         assert_close_rel(cred_g[j, :T], c_o, what=f"credit unit {i}")
-        b_o, sm_o = oracle.segment(m_g[j, :T], w.S)
+        if w.seg_delta > 0:
+            b_o, sm_o, _ = oracle.segment_adaptive(m_g[j, :T], w.seg_delta, w.l_min, w.l_max, w.S)
+        else:
+            b_o, sm_o = oracle.segment(m_g[j, :T], w.S)
         np.testing.assert_array_equal(b_g[j], b_o, err_msg=f"bounds unit {i}")
         assert_close_rel(sm_g[j], sm_o, what=f"seg_mass unit {i}")
         sinks, last, seg_budget = oracle.must_keep(T, w.budget, w.n_sink, w.n_last)
@@ -319,6 +323,27 @@ def test_causal_must_keep_step(oracle, scorer):
     job.step()
     check_properties_all_units(job)
     check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), list(range(w.units)), scorer=sc)
+
+
+@pytest.mark.parametrize("delta,l_min,l_max,pool", [(0.1, 16, 256, 5), (0.05, 0, 128, 0), (0.1, 64, 0, 3),
+                                                     (0.02, 16, 256, 7)])
+def test_segmentation_as_printed_step(oracle, delta, l_min, l_max, pool):
+    """Target segment mass with split / merge and pooled usage (Sec. 3.3; App. A), together with the
+    must-keep set and the causal window: the configuration the paper's hyper-parameter table describes."""
+    T = 6000
+    cap = int(np.ceil(1 / delta)) + 1 + (T // l_max if l_max else 0)
+    w = inputs.CONFIGS[1].scaled(L=2, H=3, T=T, budget=512, S=cap, n_spans=6, span_len=(32, 300),
+                                 n_sink=4, n_last=32, causal=True, seg_delta=delta, l_min=l_min, l_max=l_max,
+                                 pool_kernel=pool)
+    host = inputs.dense_cache(w, n_threads=4)
+    job = Job(w, host)
+    job.step()
+    check_properties_all_units(job)
+    check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), list(range(w.units)))
+    # a second event on the same cache: the credit is now non-zero
+    credit_before = to_host(job.credit).copy()
+    job.step()
+    check_units(oracle, job, host, credit_before[:, :w.T], [0, w.units - 1])
 
 
 def test_causal_paged_ragged(oracle):
