@@ -58,6 +58,11 @@ def main():
     ap.add_argument("--n-sink", type=int, default=0, help="must-keep sinks (not part of the headline workload)")
     ap.add_argument("--n-last", type=int, default=0, help="must-keep recent suffix (not part of the headline workload)")
     ap.add_argument("--causal", action="store_true", help="causal query window (not part of the headline workload)")
+    ap.add_argument("--seg-delta", type=float, default=0.0, help="target segment mass as printed, with --l-min/--l-max "
+                    "(not part of the headline workload; the segment arrays get the capacity they need)")
+    ap.add_argument("--l-min", type=int, default=0)
+    ap.add_argument("--l-max", type=int, default=0)
+    ap.add_argument("--pool", type=int, default=0, help="average-pooling kernel of the usage (odd)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that a counter run of this "
                          "command can be scaled: see profiles/")
@@ -75,7 +80,12 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     B.lib()                                   # fails loudly if the HIP library is not built
-    w = inputs.CONFIGS[args.config].scaled(n_sink=args.n_sink, n_last=args.n_last, causal=args.causal)
+    w = inputs.CONFIGS[args.config].scaled(n_sink=args.n_sink, n_last=args.n_last, causal=args.causal,
+                                           pool_kernel=args.pool)
+    if args.seg_delta > 0:
+        import math
+        cap = math.ceil(1 / args.seg_delta) + 1 + (w.T // args.l_max if args.l_max else 0)
+        w = w.scaled(seg_delta=args.seg_delta, l_min=args.l_min, l_max=args.l_max, S=cap)
     if w.paged or w.T_min is not None:
         sys.exit("bench.py: only dense single-length workloads are benchmark lines")
     t0 = time.time()
@@ -144,7 +154,9 @@ def main():
                                f"T {w.T}, window {w.W}, budget {w.budget}, S {w.S}, lambda {w.lam}, "
                                f"{w.n_spans} planted spans, seed {w.seed}; steady-state events at full T"
                                + (f"; must-keep {w.n_sink}+{w.n_last}" if w.n_sink or w.n_last else "")
-                               + ("; causal window" if w.causal else ""),
+                               + ("; causal window" if w.causal else "")
+                               + (f"; Delta {w.seg_delta} L {w.l_min}/{w.l_max}" if w.seg_delta else "")
+                               + (f"; pool {w.pool_kernel}" if w.pool_kernel > 1 else ""),
                    "units": w.units, "scorer": "mean_window"},
         "effective_GBps": round(eff_gbps, 1), "algorithmic_bytes_per_step": step_bytes,
         "hbm_peak_frac": round(eff_gbps / HBM_PEAK_GBPS, 4),
@@ -169,7 +181,8 @@ def main():
         _, _, used = O.compress_many(np.ascontiguousarray(Qf), np.ascontiguousarray(Kf), credit, G=w.G, W=w.W,
                                      budget=w.budget, S=w.S, lam=w.lam, beta=w.beta, eps=w.eps, q_min=w.q_min,
                                      n_threads=n_threads, K_rows=Kr, V_rows=Vr, n_sink=w.n_sink, n_last=w.n_last,
-                                     causal=w.causal)
+                                     causal=w.causal, delta=w.seg_delta, l_min=w.l_min, l_max=w.l_max,
+                                     pool_kernel=w.pool_kernel)
         cpu_s = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(n_units / cpu_s / w.units, 5), "unit": "steps/s", "cores": used,
                                "kind": "oracle",

@@ -163,23 +163,40 @@ __device__ __forceinline__ void init_cuts(const MsArgs& a, int unit, int T) {
 }
 
 // Usage as Eq. (1) sees it: with pooling (App. A; Alg. 1 step 1 "optionally smooth") the mean of u
-// over the positions t-r .. t+r that exist, rounded to fp32 like a stored intermediate.
-__device__ __forceinline__ void pool_run(const float* u, int j0, int T, int r, float (&x)[kPer]) {
-#pragma unroll
-  for (int i = 0; i < kPer; ++i) {
-    const int t = j0 + i;
+// over the positions t-r .. t+r that exist, rounded to fp32 like a stored intermediate.  The chunk's
+// scores and r more on either side are staged in LDS once; every thread then reads its windows there.
+constexpr int kMaxPoolR = 31;
+__device__ __forceinline__ void pool_run(const float* u, int chunk0, int j0, int T, int r, float* tile,
+                                         float* pooled, float (&x)[kPer]) {
+  const int first = chunk0 - r;  // position of tile[0]
+  for (int e = threadIdx.x; e < kChunk + 2 * r; e += kBlock) {
+    const int t = first + e;
+    tile[e] = (t >= 0 && t < T) ? u[t] : 0.f;
+  }
+  __syncthreads();
+  // consecutive threads take consecutive positions here (no bank conflicts); the runs of kPer
+  // positions each thread owns afterwards are read back from the pooled copy
+  const double inv_full = 1.0 / (double)(2 * r + 1);
+  for (int e = threadIdx.x; e < kChunk; e += kBlock) {
+    const int t = chunk0 + e;
     if (t < T) {
       const int lo = max(0, t - r), hi = min(T - 1, t + r);
       double sum = 0.0;
-      for (int j = lo; j <= hi; ++j) sum += (double)u[j];
-      x[i] = (float)(sum / (double)(hi - lo + 1));
+      for (int j = lo; j <= hi; ++j) sum += (double)tile[j - first];
+      const int n = hi - lo + 1;
+      pooled[e] = (float)(n == 2 * r + 1 ? sum * inv_full : sum / (double)n);
     }
   }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kPer; ++i)
+    if (j0 + i < T) x[i] = pooled[j0 - chunk0 + i];
 }
 
 __global__ __launch_bounds__(kBlock) void vc_sums_kernel(MsArgs a, const float* u_all, const float* credit_all,
                                                           float eps_f) {
   __shared__ double sm[kWaves];
+  __shared__ float tile[kChunk + 2 * kMaxPoolR], pooled[kChunk];
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
@@ -192,7 +209,7 @@ __global__ __launch_bounds__(kBlock) void vc_sums_kernel(MsArgs a, const float* 
   float ux[kPer], cx[kPer];
   load_run(u, j0, T, a.vec, ux, 0.f);
   load_run(credit, j0, T, a.vec, cx, 0.f);
-  if (a.pool_r > 0) pool_run(u, j0, T, a.pool_r, ux);
+  if (a.pool_r > 0) pool_run(u, chunk * kChunk, j0, T, a.pool_r, tile, pooled, ux);
 #pragma unroll
   for (int i = 0; i < kPer; ++i)
     if (j0 + i < T) {
@@ -209,6 +226,7 @@ __global__ __launch_bounds__(kBlock) void mass_ema_kernel(MsArgs a, const float*
                                                            float eps_f) {
   __shared__ double wave_tot[kWaves];
   __shared__ double bcast;
+  __shared__ float tile[kChunk + 2 * kMaxPoolR], pooled[kChunk];
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
@@ -223,7 +241,7 @@ __global__ __launch_bounds__(kBlock) void mass_ema_kernel(MsArgs a, const float*
   float mu[kPer], ux[kPer], cx[kPer];
   load_run(u, j0, T, a.vec, ux, 0.f);  // in flight while the normalisers are summed
   load_run(credit, j0, T, a.vec, cx, 0.f);
-  if (a.pool_r > 0) pool_run(u, j0, T, a.pool_r, ux);
+  if (a.pool_r > 0) pool_run(u, chunk * kChunk, j0, T, a.pool_r, tile, pooled, ux);
   const int nvc = (T + a.vc_tokens - 1) / a.vc_tokens;
   const double2 zc = ordered_sum2(a.vc_part + (int64_t)unit * a.vc_stride, nvc, &sums);
   const double Z = zc.x, c_old = zc.y;

@@ -291,12 +291,13 @@ struct Emit {
   }
 };
 
-constexpr int kSelBlock = 256;
-constexpr int kSelWaves = kSelBlock / 64;
-constexpr int kSelCap = 4096;  // segment lengths up to this are selected from a copy of the keys in LDS
+// The selection kernel comes in two shapes: 256 threads with room for 4096 keys in LDS (segments of
+// thousands of positions) and one wave with room for 1024 keys (many short segments: more workgroups
+// per compute unit and no barriers between waves).  BLOCK = threads, CAP = segment lengths up to
+// which the keys are selected from a copy in LDS.
 
 // Segment longer than the LDS staging area: the scores are re-read from memory for every pass.
-template <bool FLAGS>
+template <bool FLAGS, int BLOCK>
 __device__ void select_from_memory(const float* g, int a, int b, int q, const Emit<FLAGS>& emit, int* hist,
                                    uint32_t* sel_prefix, int* sel_rem, int2* wave_cnt) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -304,9 +305,9 @@ __device__ void select_from_memory(const float* g, int a, int b, int q, const Em
   uint32_t prefix = 0, mask = 0;
   int rem = q;
   for (int shift = 24; shift >= 0; shift -= 8) {
-    for (int i = threadIdx.x; i < 256; i += kSelBlock) hist[i] = 0;
+    for (int i = threadIdx.x; i < 256; i += BLOCK) hist[i] = 0;
     __syncthreads();
-    for (int t = a + threadIdx.x; t < b; t += kSelBlock) {
+    for (int t = a + threadIdx.x; t < b; t += BLOCK) {
       const uint32_t k = score_key(g[t]);
       if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
     }
@@ -341,7 +342,7 @@ __device__ void select_from_memory(const float* g, int a, int b, int q, const Em
   // prefix = key of the q-th largest score; rem = how many of the keys equal to it are kept
   const uint32_t thr = prefix;
   int base_gt = 0, base_eq = 0;  // counts over the positions before the current tile
-  for (int t0 = a; t0 < b; t0 += kSelBlock) {
+  for (int t0 = a; t0 < b; t0 += BLOCK) {
     const int t = t0 + threadIdx.x;
     uint32_t k = 0;
     const bool in = t < b;
@@ -354,7 +355,7 @@ __device__ void select_from_memory(const float* g, int a, int b, int q, const Em
     int n_gt = base_gt + __popcll(bgt & below), n_eq = base_eq + __popcll(beq & below);
     int tot_gt = 0, tot_eq = 0;
 #pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) {
+    for (int w = 0; w < (BLOCK / 64); ++w) {
       const int2 c = wave_cnt[w];
       if (w < wave) {
         n_gt += c.x;
@@ -370,41 +371,50 @@ __device__ void select_from_memory(const float* g, int a, int b, int q, const Em
   }
 }
 
-template <bool FLAGS>
-__global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int budget, const float* g_all,
+template <bool FLAGS, int BLOCK, int CAP>
+__global__ __launch_bounds__(BLOCK) void select_kernel(Dims d, int S, int budget, const float* g_all,
                                                            const int32_t* bounds_all,
                                                            const int32_t* quota_all, int32_t* idx_all,
                                                            uint32_t* flags_all, int n_words) {
-  __shared__ uint32_t keys[kSelCap];
-  __shared__ int hist[kSelWaves][256];
+  __shared__ uint32_t keys[CAP];
+  __shared__ int hist[(BLOCK / 64)][256];
   __shared__ uint32_t sel_prefix;
   __shared__ int sel_rem;
-  __shared__ int2 wave_cnt[kSelWaves];
-  __shared__ uint32_t red_and[kSelWaves], red_or[kSelWaves];
+  __shared__ int2 wave_cnt[(BLOCK / 64)];
+  __shared__ uint32_t red_and[(BLOCK / 64)], red_or[(BLOCK / 64)];
   const int unit = blockIdx.y, seg = blockIdx.x;
   const int32_t* bounds = bounds_all + (int64_t)unit * (S + 1);
   const int32_t* quota = quota_all + (int64_t)unit * S;
   const int a = bounds[seg], b = bounds[seg + 1], q = quota[seg];
   if (q <= 0) return;
-  int out0 = 0;
-  for (int i = 0; i < seg; ++i) out0 += quota[i];
+  int out0 = 0;  // place of this segment's picks in the index list: the quotas before it
+  if (!FLAGS) {
+    for (int i = threadIdx.x; i < seg; i += BLOCK) out0 += quota[i];
+    out0 = wave_sum(out0);
+    if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6].x = out0;
+    __syncthreads();
+    out0 = 0;
+#pragma unroll
+    for (int w = 0; w < BLOCK / 64; ++w) out0 += wave_cnt[w].x;
+    __syncthreads();
+  }
   const float* g = g_all + (int64_t)unit * d.t_stride;
   const Emit<FLAGS> emit{idx_all + (int64_t)unit * budget + out0,
                          FLAGS ? flags_all + (int64_t)unit * n_words : nullptr};
   const int L = b - a;
   if (q >= L) {  // whole segment kept
-    for (int j = threadIdx.x; j < L; j += kSelBlock) emit(j, a + j);
+    for (int j = threadIdx.x; j < L; j += BLOCK) emit(j, a + j);
     return;
   }
-  if (L > kSelCap) {
-    select_from_memory<FLAGS>(g, a, b, q, emit, &hist[0][0], &sel_prefix, &sel_rem, wave_cnt);
+  if (L > CAP) {
+    select_from_memory<FLAGS, BLOCK>(g, a, b, q, emit, &hist[0][0], &sel_prefix, &sel_rem, wave_cnt);
     return;
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
   // keys of the segment -> LDS; bits that are the same in every key need no radix pass
   uint32_t k_and = 0xFFFFFFFFu, k_or = 0;
-  for (int e = threadIdx.x; e < L; e += kSelBlock) {
+  for (int e = threadIdx.x; e < L; e += BLOCK) {
     const uint32_t k = score_key(g[a + e]);
     keys[e] = k;
     k_and &= k;
@@ -420,8 +430,13 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int bu
     red_or[wave] = k_or;
   }
   __syncthreads();
-  k_and = red_and[0] & red_and[1] & red_and[2] & red_and[3];
-  k_or = red_or[0] | red_or[1] | red_or[2] | red_or[3];
+  k_and = red_and[0];
+  k_or = red_or[0];
+#pragma unroll
+  for (int w = 1; w < BLOCK / 64; ++w) {
+    k_and &= red_and[w];
+    k_or |= red_or[w];
+  }
   const uint32_t diff = k_and ^ k_or;
   uint32_t thr = k_and;  // all keys equal: the threshold is that key
   int rem = q;
@@ -431,9 +446,9 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int bu
     uint32_t prefix = k_and & mask;
     int shift = max(hb - 7, 0);
     for (;;) {
-      for (int i = threadIdx.x; i < kSelWaves * 256; i += kSelBlock) (&hist[0][0])[i] = 0;
+      for (int i = threadIdx.x; i < (BLOCK / 64) * 256; i += BLOCK) (&hist[0][0])[i] = 0;
       __syncthreads();
-      for (int e = threadIdx.x; e < L; e += kSelBlock) {
+      for (int e = threadIdx.x; e < L; e += BLOCK) {
         const uint32_t k = keys[e];
         if ((k & mask) == prefix) atomicAdd(&hist[wave][(k >> shift) & 255], 1);
       }
@@ -444,7 +459,7 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int bu
         for (int i = 0; i < 4; ++i) {
           hbin[i] = 0;
 #pragma unroll
-          for (int w = 0; w < kSelWaves; ++w) hbin[i] += hist[w][lane * 4 + i];
+          for (int w = 0; w < (BLOCK / 64); ++w) hbin[i] += hist[w][lane * 4 + i];
         }
         const int s = hbin[0] + hbin[1] + hbin[2] + hbin[3];
         int incl = s;  // sum over lanes >= this one
@@ -477,7 +492,7 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(Dims d, int S, int bu
   // thr = key of the q-th largest score; rem = how many of the keys equal to it are kept (the first
   // rem in position order).  Every thread takes a contiguous run of positions, so one workgroup scan
   // of the per-thread counts gives every kept position its place in the ascending output.
-  const int per = (L + kSelBlock - 1) / kSelBlock;
+  const int per = (L + BLOCK - 1) / BLOCK;
   const int e0 = min(L, (int)threadIdx.x * per), e1 = min(L, e0 + per);
   int c_gt = 0, c_eq = 0;
   for (int e = e0; e < e1; ++e) {
@@ -805,13 +820,27 @@ hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_
                        p->q_min, bounds, seg_mass, quota, idx, n_kept, cpre, mpart, n_chunks, p->n_sink,
                        p->n_last, must ? flags : nullptr, n_words);
   prof_mark("select", s);
+  // expected segment length decides the shape of the selection workgroups
+  const double expect = p->seg_delta > 0.f
+                            ? (p->l_max > 0 ? (double)p->l_max : (double)p->t_max * (double)p->seg_delta)
+                            : (double)p->t_max / (double)S;
+  const bool small = expect <= 512.0;
+  const dim3 grid(S, d.units);
   if (!must) {
-    hipLaunchKernelGGL(select_kernel<false>, dim3(S, d.units), dim3(kSelBlock), 0, s, d, S, p->budget, g,
-                       bounds, quota, idx, nullptr, 0);
+    if (small)
+      hipLaunchKernelGGL((select_kernel<false, 64, 1024>), grid, dim3(64), 0, s, d, S, p->budget, g, bounds, quota,
+                         idx, nullptr, 0);
+    else
+      hipLaunchKernelGGL((select_kernel<false, 256, 4096>), grid, dim3(256), 0, s, d, S, p->budget, g, bounds,
+                         quota, idx, nullptr, 0);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(select_kernel<true>, dim3(S, d.units), dim3(kSelBlock), 0, s, d, S, p->budget, g, bounds,
-                     quota, idx, flags, n_words);
+  if (small)
+    hipLaunchKernelGGL((select_kernel<true, 64, 1024>), grid, dim3(64), 0, s, d, S, p->budget, g, bounds, quota,
+                       idx, flags, n_words);
+  else
+    hipLaunchKernelGGL((select_kernel<true, 256, 4096>), grid, dim3(256), 0, s, d, S, p->budget, g, bounds, quota,
+                       idx, flags, n_words);
   prof_mark("finalize", s);
   hipLaunchKernelGGL(finalize_kernel, dim3(d.units), dim3(kFinBlock), 0, s, d, seq_lens, p->budget, p->n_sink,
                      p->n_last, g, flags, n_words, idx);
