@@ -197,6 +197,22 @@ def test_config1_full_size(oracle, cfg1_job):
     check_units(oracle, job, host, credit1, sample, check_scores=False)
 
 
+def test_config1_full_size_paper_options(oracle, cfg1_job):
+    """Config 1 at full size with everything the paper's default configuration switches on: target mass
+    0.1 with L_min 16 / L_max 256, pooled usage, 4 sinks + 32 recent tokens, causal window."""
+    w0, host, _ = cfg1_job
+    cap = 10 + 1 + w0.T // 256
+    w = w0.scaled(S=cap, seg_delta=0.1, l_min=16, l_max=256, pool_kernel=5, n_sink=4, n_last=32, causal=True)
+    job = Job(w, host)
+    job.step()
+    torch.cuda.synchronize()
+    check_properties_all_units(job)
+    check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), [3, 200])
+    n_seg = (job.intermediates().bounds[:, 1:] > job.intermediates().bounds[:, :-1]).sum(1)
+    print("segments per unit: min", int(n_seg.min()), "max", int(n_seg.max()))
+    assert int(n_seg.min()) >= 10 and int(n_seg.max()) <= cap
+
+
 def test_config1_deterministic(cfg1_job):
     w, host, job = cfg1_job
     job.credit.zero_()
