@@ -137,6 +137,24 @@ int amso_score(const float* Q, const float* K, int G, int W, int T, int D,
   return 0;
 }
 
+// Value-weighted expected attention (Sec. 3.3 plug-in scorer, "expected-attention-based scorer"
+// with its epsilon): the log-moment scores e are turned into a distribution over the cache,
+// p = softmax_t(e), and every token is weighted by the length of its value vector:
+// g_t = (p_t + eps) * ||v_t||_2.
+int amso_value_weight(const float* e, const float* V, int T, int D, float eps, float* g) {
+  if (!e || !V || !g || T < 1 || D < 1 || !(eps >= 0.0f)) return -1;
+  double emax = -INFINITY;
+  for (int t = 0; t < T; ++t) emax = std::max(emax, (double)e[t]);
+  double z = 0.0;
+  for (int t = 0; t < T; ++t) z += std::exp((double)e[t] - emax);
+  for (int t = 0; t < T; ++t) {
+    double n2 = 0.0;
+    for (int d = 0; d < D; ++d) n2 += (double)V[(size_t)t * D + d] * (double)V[(size_t)t * D + d];
+    g[t] = (float)((std::exp((double)e[t] - emax) / z + (double)eps) * std::sqrt(n2));
+  }
+  return 0;
+}
+
 // Eq. (1).
 int amso_mass(const float* u, int T, float eps, float* m_cur) {
   if (!u || !m_cur || T < 1 || !(eps > 0.0f)) return -1;
@@ -479,7 +497,7 @@ int amso_compact_paged(const void* K_pool, const void* V_pool, const int32_t* sr
   return 0;
 }
 
-int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K,
+int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K, const float* V,
                        const void* K_rows, const void* V_rows, int64_t row_bytes,
                        float* credit,
                        float* u, float* g, float* m_used, int32_t* bounds, float* seg_mass,
@@ -490,7 +508,15 @@ int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K
   std::vector<float> u_((size_t)T), g_((size_t)T), mc((size_t)T), mu((size_t)T), sm((size_t)S);
   std::vector<int32_t> bd((size_t)S + 1), qt((size_t)S);
   int rc;
-  if ((rc = amso_score(Q, K, p->G, p->W, T, p->D, p->scorer, p->causal, u_.data(), g_.data()))) return rc;
+  const bool vnorm = p->scorer == AMSO_SCORER_EXPECTED_VNORM;
+  if (vnorm && !V) return -1;
+  if ((rc = amso_score(Q, K, p->G, p->W, T, p->D, vnorm ? AMSO_SCORER_EXPECTED : p->scorer, p->causal, u_.data(),
+                       g_.data())))
+    return rc;
+  if (vnorm) {
+    std::vector<float> e(g_);
+    if ((rc = amso_value_weight(e.data(), V, T, p->D, p->vnorm_eps, g_.data()))) return rc;
+  }
   std::vector<float> up;  // smoothed usage feeds the mass only; the base score keeps the raw one
   if (p->pool_kernel > 1) {
     up.resize((size_t)T);
@@ -527,7 +553,7 @@ int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K
 
 int amso_compress_many(const amso_unit_params* p, int n_units, int n_threads,
                        const float* Q, int64_t q_stride,
-                       const float* K, int64_t k_stride,
+                       const float* K, int64_t k_stride, const float* V,
                        float* credit, int64_t c_stride,
                        float* u, float* g, int32_t* idx, int32_t* n_kept,
                        const void* K_rows, const void* V_rows, int64_t row_bytes,
@@ -547,7 +573,7 @@ int amso_compress_many(const amso_unit_params* p, int n_units, int n_threads,
       const size_t src_off = (size_t)i * p->T * (size_t)row_bytes;
       const size_t dst_off = (size_t)i * p->budget * (size_t)row_bytes;
       const int rc = amso_compress_unit(
-          p, Q + (size_t)i * q_stride, K + (size_t)i * k_stride,
+          p, Q + (size_t)i * q_stride, K + (size_t)i * k_stride, V ? V + (size_t)i * k_stride : nullptr,
           gather ? (const char*)K_rows + src_off : nullptr, gather ? (const char*)V_rows + src_off : nullptr,
           gather ? row_bytes : 1, credit + (size_t)i * c_stride,
           u ? u + (size_t)i * p->T : nullptr, g ? g + (size_t)i * p->T : nullptr,

@@ -23,7 +23,8 @@
  * over the pairs that see the key); the order in which equal scores are
  * trimmed or backfilled; the split / merge rules of amso_segment_adaptive
  * (the paper says "roughly equal" and "a neighboring segment") and the edge
- * handling of amso_pool.
+ * handling of amso_pool; the form of the value weighting in amso_value_weight
+ * (the paper names the scorer and its epsilon only).
  */
 #ifndef AMS_ORACLE_H
 #define AMS_ORACLE_H
@@ -38,7 +39,8 @@ enum {
   AMSO_SCORER_LAST_QUERY = 0,  /* attention of the newest query of each head   */
   AMSO_SCORER_MEAN_WINDOW = 1, /* the usage u itself                            */
   AMSO_SCORER_KEYDIFF = 2,     /* negative cosine to the mean key               */
-  AMSO_SCORER_EXPECTED = 3     /* log Gaussian moment of the query window       */
+  AMSO_SCORER_EXPECTED = 3,    /* log Gaussian moment of the query window       */
+  AMSO_SCORER_EXPECTED_VNORM = 5 /* amso_value_weight of the above (whole event only) */
 };
 
 /* Step 1 of Alg. 1 (usage) + the plug-in base score g (Sec. 3.3 "In-Segment
@@ -50,6 +52,10 @@ enum {
  * probability the key received from the pairs that see it. */
 int amso_score(const float* Q, const float* K, int G, int W, int T, int D,
                int scorer, int causal, float* u, float* g);
+
+/* Value-weighted expected attention: p = softmax over the cache of the log-moment
+ * scores e [T]; g_t = (p_t + eps) * ||v_t||_2 with V [T][D] widened to float. */
+int amso_value_weight(const float* e, const float* V, int T, int D, float eps, float* g);
 
 /* Eq. (1): m_t = (max(u_t,0)+eps) / sum_v (max(u_v,0)+eps). */
 int amso_mass(const float* u, int T, float eps, float* m_cur);
@@ -130,9 +136,11 @@ typedef struct {
   float delta;        /* > 0: amso_segment_adaptive with S as the capacity; 0: amso_segment(S) */
   int l_min, l_max;   /* with delta > 0 */
   int pool_kernel;    /* > 1: amso_pool before Eq. (1) */
+  float vnorm_eps;    /* eps of amso_value_weight (scorer AMSO_SCORER_EXPECTED_VNORM) */
 } amso_unit_params;
 
 int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K,
+                       const float* V /* [T][D] widened; only read by AMSO_SCORER_EXPECTED_VNORM, else may be NULL */,
                        const void* K_rows, const void* V_rows, int64_t row_bytes,
                        float* credit,
                        float* u, float* g, float* m_used, int32_t* bounds, float* seg_mass,
@@ -150,6 +158,7 @@ int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K
 int amso_compress_many(const amso_unit_params* p, int n_units, int n_threads,
                        const float* Q, int64_t q_stride,
                        const float* K, int64_t k_stride,
+                       const float* V /* [n_units][T][D] or NULL, see amso_compress_unit */,
                        float* credit, int64_t c_stride,
                        float* u, float* g, int32_t* idx, int32_t* n_kept,
                        const void* K_rows, const void* V_rows, int64_t row_bytes,

@@ -12,6 +12,7 @@ import numpy as np
 from . import build as _build
 
 SCORER_LAST_QUERY, SCORER_MEAN_WINDOW, SCORER_KEYDIFF, SCORER_EXPECTED = 0, 1, 2, 3
+SCORER_EXPECTED_VNORM = 5
 
 _lib = None
 
@@ -21,7 +22,8 @@ class _UnitParams(C.Structure):
                 ("scorer", C.c_int), ("budget", C.c_int), ("S", C.c_int), ("q_min", C.c_int),
                 ("lam", C.c_float), ("beta", C.c_float), ("eps", C.c_float),
                 ("n_sink", C.c_int), ("n_last", C.c_int), ("causal", C.c_int),
-                ("delta", C.c_float), ("l_min", C.c_int), ("l_max", C.c_int), ("pool_kernel", C.c_int)]
+                ("delta", C.c_float), ("l_min", C.c_int), ("l_max", C.c_int), ("pool_kernel", C.c_int),
+                ("vnorm_eps", C.c_float)]
 
 
 def lib():
@@ -65,6 +67,15 @@ def score(Q, K, G, W, scorer=SCORER_MEAN_WINDOW, causal=False):
     g = np.empty(T, np.float32)
     _chk(lib().amso_score(_f(Q), _f(K), G, W, T, D, int(scorer), int(bool(causal)), _f(u), _f(g)), "score")
     return u, g
+
+
+def value_weight(e, V, eps=1e-2):
+    """(softmax(e) + eps) * row norms of V."""
+    e = np.ascontiguousarray(e, np.float32)
+    V = np.ascontiguousarray(widen(V))
+    g = np.empty_like(e)
+    _chk(lib().amso_value_weight(_f(e), _f(V), V.shape[0], V.shape[1], C.c_float(eps), _f(g)), "value_weight")
+    return g
 
 
 def mass(u, eps=1e-6):
@@ -182,7 +193,7 @@ def compact_paged(K_pool, V_pool, src_table, K_pool_out, V_pool_out, dst_table, 
 
 def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_min=1,
                   scorer=SCORER_MEAN_WINDOW, n_sink=0, n_last=0, causal=False, delta=0.0, l_min=0, l_max=0,
-                  pool_kernel=0):
+                  pool_kernel=0, vnorm_eps=1e-2):
     """One whole event for one unit.  K, V [T, D] in storage dtype (float32 or
     uint16 = bf16 bits).  Returns a dict with every intermediate."""
     Kf = np.ascontiguousarray(widen(K))
@@ -192,7 +203,9 @@ def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, 
     T, D = Kf.shape
     kept = min(budget, T)
     p = _UnitParams(G, W, T, D, int(scorer), int(budget), int(S), int(q_min), lam, beta, eps,
-                    int(n_sink), int(n_last), int(bool(causal)), delta, int(l_min), int(l_max), int(pool_kernel))
+                    int(n_sink), int(n_last), int(bool(causal)), delta, int(l_min), int(l_max), int(pool_kernel),
+                    vnorm_eps)
+    Vf = np.ascontiguousarray(widen(V)) if int(scorer) == SCORER_EXPECTED_VNORM else None
     c = np.array(credit, dtype=np.float32, copy=True)
     out = dict(u=np.empty(T, np.float32), g=np.empty(T, np.float32), m_used=np.empty(T, np.float32),
                bounds=np.empty(S + 1, np.int32), seg_mass=np.empty(S, np.float32),
@@ -201,7 +214,8 @@ def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, 
                credit_out=np.zeros(kept, np.float32))
     n = C.c_int32(0)
     _chk(lib().amso_compress_unit(
-        C.byref(p), _f(Qf), _f(Kf), K.ctypes.data_as(C.c_void_p), V.ctypes.data_as(C.c_void_p),
+        C.byref(p), _f(Qf), _f(Kf), _f(Vf) if Vf is not None else None,
+        K.ctypes.data_as(C.c_void_p), V.ctypes.data_as(C.c_void_p),
         C.c_int64(K[0].nbytes), _f(c), _f(out["u"]), _f(out["g"]), _f(out["m_used"]),
         _i(out["bounds"]), _f(out["seg_mass"]), _i(out["quota"]), _i(out["idx"]), C.byref(n),
         out["K_out"].ctypes.data_as(C.c_void_p), out["V_out"].ctypes.data_as(C.c_void_p),
@@ -213,7 +227,8 @@ def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, 
 
 def compress_many(Q, K, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_min=1,
                   scorer=SCORER_MEAN_WINDOW, n_threads=0, want_scores=False, K_rows=None, V_rows=None,
-                  n_sink=0, n_last=0, causal=False, delta=0.0, l_min=0, l_max=0, pool_kernel=0):
+                  n_sink=0, n_last=0, causal=False, delta=0.0, l_min=0, l_max=0, pool_kernel=0, vnorm_eps=1e-2,
+                  V=None):
     """Q [U, G*W, D], K [U, T, D] float32 (already widened), credit [U, T] (updated in
     place).  K_rows, V_rows [U, T, D] in the storage dtype: when given, the kept rows are
     gathered as well (whole event).  Returns (idx [U, budget], n_kept [U], threads_used[, u, g])."""
@@ -222,7 +237,10 @@ def compress_many(Q, K, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_m
     for a in (Q, K, credit):
         assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"]
     p = _UnitParams(G, W, T, D, int(scorer), int(budget), int(S), int(q_min), lam, beta, eps,
-                    int(n_sink), int(n_last), int(bool(causal)), delta, int(l_min), int(l_max), int(pool_kernel))
+                    int(n_sink), int(n_last), int(bool(causal)), delta, int(l_min), int(l_max), int(pool_kernel),
+                    vnorm_eps)
+    if int(scorer) == SCORER_EXPECTED_VNORM:
+        assert V is not None and V.shape == K.shape and V.dtype == np.float32 and V.flags["C_CONTIGUOUS"]
     idx = np.empty((U, budget), np.int32)
     n_kept = np.empty(U, np.int32)
     u = np.empty((U, T), np.float32) if want_scores else None
@@ -235,7 +253,7 @@ def compress_many(Q, K, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_m
         c_out = np.zeros((U, budget), np.float32)
     vp = lambda a: a.ctypes.data_as(C.c_void_p)
     rc = lib().amso_compress_many(C.byref(p), U, int(n_threads), _f(Q), C.c_int64(G * W * D), _f(K),
-                                  C.c_int64(T * D), _f(credit), C.c_int64(T),
+                                  C.c_int64(T * D), _f(V) if V is not None else None, _f(credit), C.c_int64(T),
                                   _f(u) if want_scores else None, _f(g) if want_scores else None,
                                   _i(idx), _i(n_kept),
                                   vp(K_rows) if gather else None, vp(V_rows) if gather else None,

@@ -124,3 +124,53 @@ def test_bf16_inputs_are_widened_exactly(oracle):
     # round-to-nearest-even: 1 + 2^-8 is a tie between 1.0 and 1 + 2^-7 -> even mantissa (1.0)
     assert inputs.bf16_bits_to_f32(inputs.to_bf16_bits(np.array([1 + 2.0 ** -8], np.float32)))[0] == 1.0
     assert inputs.bf16_bits_to_f32(inputs.to_bf16_bits(np.array([1 + 3 * 2.0 ** -8], np.float32)))[0] == 1 + 2.0 ** -6
+
+
+# --- value-weighted expected attention (Sec. 3.3 plug-in scorer; the paper gives the scorer's epsilon 1e-2) ---
+
+def test_value_weight_closed_forms(oracle):
+    # equal scores: p = 1/T; rows (3,4,0..) and (0,..,0,12,5) have lengths 5 and 13
+    T, D = 4, 8
+    V = np.zeros((T, D), np.float32)
+    V[0, :2] = (3, 4)
+    V[1, -2:] = (12, 5)
+    V[2, 0] = 1
+    g = oracle.value_weight(np.full(T, 7.0, np.float32), V, eps=0.25)
+    np.testing.assert_allclose(g, [0.5 * 5, 0.5 * 13, 0.5 * 1, 0.0], rtol=1e-7)
+    # eps = 0 and unit values: the softmax of the scores itself, here ln 1, ln 2, ln 5 -> 1/8, 2/8, 5/8
+    V = np.zeros((3, 4), np.float32)
+    V[:, 1] = 1
+    g = oracle.value_weight(np.log(np.array([1, 2, 5], np.float32)), V, eps=0.0)
+    np.testing.assert_allclose(g, [0.125, 0.25, 0.625], rtol=1e-6)
+
+
+def test_value_weight_against_library_routines(oracle):
+    from scipy.special import softmax
+    rng = np.random.default_rng(8)
+    T, D = 500, 128
+    e = (rng.standard_normal(T) * 4).astype(np.float32)
+    e[17] = 60.0                                   # a dominant token: no overflow, p close to 1
+    V = rng.standard_normal((T, D)).astype(np.float32)
+    g = oracle.value_weight(e, V, eps=1e-2)
+    want = (softmax(e.astype(np.float64)) + 1e-2) * np.linalg.norm(V.astype(np.float64), axis=1)
+    np.testing.assert_allclose(g, want, rtol=1e-6)
+    assert np.argmax(g) == 17
+    # bf16 values are widened exactly
+    from paper_2605_23200_amd import inputs
+    Vb = inputs.to_bf16_bits(V)
+    g2 = oracle.value_weight(e, Vb, eps=1e-2)
+    want2 = (softmax(e.astype(np.float64)) + 1e-2) * np.linalg.norm(inputs.bf16_bits_to_f32(Vb).astype(np.float64), axis=1)
+    np.testing.assert_allclose(g2, want2, rtol=1e-6)
+
+
+def test_whole_event_with_value_weighted_scorer(oracle):
+    from paper_2605_23200_amd import inputs
+    w = inputs.CONFIGS[0].scaled(T=600, budget=96, S=8, n_spans=3, span_len=(16, 48), H=1)
+    q = inputs.unit_q(w, 0, 0, 0)
+    k, v = inputs.unit_kv(w, 0, 0, 0, w.T, q)
+    r = oracle.compress_unit(q, k, v, np.zeros(w.T, np.float32), G=w.G, W=w.W, budget=w.budget, S=w.S, lam=w.lam,
+                             scorer=oracle.SCORER_EXPECTED_VNORM)
+    u, e = oracle.score(q, k, w.G, w.W, oracle.SCORER_EXPECTED)
+    np.testing.assert_array_equal(r["u"], u)
+    np.testing.assert_array_equal(r["g"], oracle.value_weight(e, v, 1e-2))
+    np.testing.assert_array_equal(r["idx"], oracle.select(r["g"], r["bounds"], r["quota"]))
