@@ -52,7 +52,10 @@ typedef enum {
   AMS_SCORER_MEAN_WINDOW = 1, /* g = u, the mean attention over the query window           */
   AMS_SCORER_KEYDIFF = 2,     /* negative cosine between a key and the mean key            */
   AMS_SCORER_EXPECTED = 3,    /* log Gaussian moment of the window's query distribution    */
-  AMS_SCORER_EXTERNAL = 4     /* caller supplies g (stage calls only)                      */
+  AMS_SCORER_EXTERNAL = 4,    /* caller supplies g (stage calls only)                      */
+  AMS_SCORER_EXPECTED_VNORM = 5 /* value-weighted expected attention: p = softmax over the
+                                   cache of the AMS_SCORER_EXPECTED scores,
+                                   g = (p + vnorm_eps) * ||v||_2; reads V                  */
 } ams_scorer;
 
 typedef enum {
@@ -87,6 +90,7 @@ typedef struct {
   int32_t l_min;      /* seg_delta > 0: segments shorter than this are merged (0 = off)    */
   int32_t l_max;      /* seg_delta > 0: segments longer than this are split (0 = off)      */
   int32_t pool_kernel;/* odd k > 1: Eq. (1) sees the k-point centred mean of u (App. A); 0/1 = off */
+  float vnorm_eps;    /* epsilon of AMS_SCORER_EXPECTED_VNORM, >= 0 (1e-2 in the paper's runs) */
 } ams_params;
 
 /* A KV cache as the library sees it.  Plain data, [host]; k, v, block_table [dev]. */

@@ -69,7 +69,8 @@ static int check_params(const ams_params* p) {
   if (!(p->ema_lambda >= 0.f && p->ema_lambda < 1.f) || !(p->ema_beta >= 0.f && p->ema_beta <= 1.f) ||
       !(p->mass_eps > 0.f) || isinf(p->mass_eps))
     return AMS_ERR_INVALID_ARG;
-  if (p->scorer < AMS_SCORER_LAST_QUERY || p->scorer > AMS_SCORER_EXTERNAL) return AMS_ERR_INVALID_ARG;
+  if (p->scorer < AMS_SCORER_LAST_QUERY || p->scorer > AMS_SCORER_EXPECTED_VNORM) return AMS_ERR_INVALID_ARG;
+  if (p->scorer == AMS_SCORER_EXPECTED_VNORM && !(p->vnorm_eps >= 0.f)) return AMS_ERR_INVALID_ARG;
   if (p->head_dim != 128) return AMS_ERR_UNSUPPORTED;
   if (p->n_segments > 1024) return AMS_ERR_UNSUPPORTED;
   const int64_t units = (int64_t)p->n_layers * p->batch * p->n_kv_heads;
@@ -216,15 +217,17 @@ int ams_score(const ams_params* p, const ams_kv_view* src, const int32_t* seq_le
               float* u, float* g, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_params(p);
   if (rc) return rc;
-  if ((rc = check_view(p, src, p->t_max, false))) return rc;
+  const bool need_v = p->scorer == AMS_SCORER_EXPECTED_VNORM;
+  if ((rc = check_view(p, src, p->t_max, need_v))) return rc;
   if (!seq_lens || !q || !u || !ws) return AMS_ERR_INVALID_ARG;
   if (p->scorer != AMS_SCORER_EXTERNAL && !g) return AMS_ERR_INVALID_ARG;
   if (p->scorer != AMS_SCORER_MEAN_WINDOW && p->scorer != AMS_SCORER_EXTERNAL && g == u)
     return AMS_ERR_INVALID_ARG;
   const WsLayout wl = ws_layout(p);
   if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
-  return hip_status(launch_score(p, make_dims(p), make_kv(p, src, src->k), seq_lens, q, u, g, nullptr, nullptr,
-                                 (char*)ws, wl, (hipStream_t)stream), (hipStream_t)stream);
+  const KvDev vdev = make_kv(p, src, src->v);
+  return hip_status(launch_score(p, make_dims(p), make_kv(p, src, src->k), need_v ? &vdev : nullptr, seq_lens, q, u, g,
+                                 nullptr, nullptr, (char*)ws, wl, (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u, float* credit,
@@ -310,7 +313,8 @@ int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t
   int32_t* quota = (int32_t*)(w + wl.quota);
   hipError_t e;
   VcInfo vc{false, 0, 0};
-  if ((e = launch_score(p, d, make_kv(p, src, src->k), seq_lens, q, u, g, credit, &vc, w, wl, s)) != hipSuccess)
+  const KvDev vdev = make_kv(p, src, src->v);
+  if ((e = launch_score(p, d, make_kv(p, src, src->k), &vdev, seq_lens, q, u, g, credit, &vc, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;
   if ((e = launch_ema(p, d, seq_lens, u, credit, m_used, bounds, vc, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;

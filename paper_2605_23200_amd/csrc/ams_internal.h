@@ -83,7 +83,9 @@ void prof_mark(const char* label, hipStream_t s);
 // ---- launchers (each returns hipGetLastError() of its launches) ----
 // credit and vc are optional: when vc is given, the scorer also leaves the per-chunk sums that
 // launch_ema needs in the workspace and describes them in *vc.
-hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
+// v: the values of the cache, read by AMS_SCORER_EXPECTED_VNORM only (else may be null)
+hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, const KvDev* v,
+                        const int32_t* seq_lens,
                         const void* q, float* u, float* g, const float* credit, VcInfo* vc, char* ws,
                         const WsLayout& wl, hipStream_t s);
 size_t fused_score_ws_bytes(int64_t units, int t_max, int n_pad, int batch);

@@ -433,6 +433,96 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Value-weighted expected attention (Sec. 3.3 plug-in scorer): the log-moment scores e left in g by
+// the second sweep become p = softmax over the cache, and g[t] = (p[t] + eps) * ||v_t||.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void esoftmax_part_kernel(ScoreArgs a, double2* part) {
+  __shared__ double2 sm[4];
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  const int c0 = chunk * kScoreChunk;
+  if (c0 >= T) return;
+  const float* e = a.g + (int64_t)unit * a.d.t_stride;
+  const int end = min(T, c0 + kScoreChunk);
+  double m = -INFINITY, z = 0.0;
+  for (int t = c0 + threadIdx.x; t < end; t += kThreads) {
+    const double x = (double)e[t];
+    const double mx = fmax(m, x);
+    z = z * exp(m - mx) + exp(x - mx);
+    m = mx;
+  }
+  // lanes, then waves, each in a fixed order; an empty partial is (-inf, 0)
+  auto merge = [](double& m1, double& z1, double m2, double z2) __attribute__((always_inline)) {
+    const double mx = fmax(m1, m2);
+    if (mx == -INFINITY) return;
+    z1 = z1 * exp(m1 - mx) + z2 * exp(m2 - mx);
+    m1 = mx;
+  };
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const double m2 = __shfl_xor(m, o), z2 = __shfl_xor(z, o);
+    // both partners must arrive at the same value: combine in lane order
+    double ml = (threadIdx.x & o) ? m2 : m, zl = (threadIdx.x & o) ? z2 : z;
+    const double mh = (threadIdx.x & o) ? m : m2, zh = (threadIdx.x & o) ? z : z2;
+    merge(ml, zl, mh, zh);
+    m = ml;
+    z = zl;
+  }
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = make_double2(m, z);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double M = sm[0].x, Z = sm[0].y;
+    for (int w = 1; w < 4; ++w) merge(M, Z, sm[w].x, sm[w].y);
+    part[(int64_t)unit * a.n_chunks + chunk] = make_double2(M, Z);
+  }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void vweight_kernel(ScoreArgs a, KvDev v, const double2* part, float eps_f) {
+  constexpr int CPR = Tr<BF16>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
+  __shared__ double2 stat;
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = a.seq_lens[b];
+  const int c0 = chunk * kScoreChunk;
+  if (c0 >= T) return;
+  if (threadIdx.x == 0) {  // chunk statistics merged in index order
+    const int nch = (T + kScoreChunk - 1) / kScoreChunk;
+    double M = -INFINITY;
+    for (int c = 0; c < nch; ++c) M = fmax(M, part[(int64_t)unit * a.n_chunks + c].x);
+    double Z = 0.0;
+    for (int c = 0; c < nch; ++c) {
+      const double2 s = part[(int64_t)unit * a.n_chunks + c];
+      Z += s.y * exp(s.x - M);
+    }
+    stat = make_double2(M, Z);
+  }
+  __syncthreads();
+  const double M = stat.x, inv_z = 1.0 / stat.y, eps = (double)eps_f;
+  const int col = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
+  float* g_row = a.g + (int64_t)unit * a.d.t_stride;
+  for (int tb = c0; tb < min(T, c0 + kScoreChunk); tb += RPI) {
+    const int t = tb + r0;
+    double n2 = 0.0;
+    if (t < T) {
+      const uint4 x4 = *(const uint4*)(kv_row(v, l, b, h, t) + col * 16);
+      float x[8];
+      int n;
+      widen8<BF16>(x4, x, n);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) n2 += (double)x[e] * (double)x[e];
+    }
+    // the CPR lanes of a row are consecutive lanes of one wave
+#pragma unroll
+    for (int o = CPR / 2; o >= 1; o >>= 1) n2 += __shfl_xor(n2, o);
+    if (col == 0 && t < T) g_row[t] = (float)((exp((double)g_row[t] - M) * inv_z + eps) * sqrt(n2));
+  }
+}
+
 template <typename K>
 hipError_t set_lds(K kernel, int bytes) {
   return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
@@ -496,7 +586,8 @@ hipError_t run_by_nb(const ScoreArgs& a, int nb, int mode, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
+hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, const KvDev* v,
+                        const int32_t* seq_lens,
                         const void* q, float* u, float* g, const float* credit, VcInfo* vc, char* ws,
                         const WsLayout& wl, hipStream_t s) {
   if (vc) vc->have = false;
@@ -524,7 +615,9 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
   a.g = nullptr;
   if (p->scorer == AMS_SCORER_MEAN_WINDOW) a.g = (g != u) ? g : nullptr;
   if (p->scorer == AMS_SCORER_LAST_QUERY) { mode = MODE_LAST; a.g = g; }
-  if (p->scorer == AMS_SCORER_EXPECTED) { mode = MODE_EXPECTED; a.g = g; }
+  const bool vnorm = p->scorer == AMS_SCORER_EXPECTED_VNORM;
+  if (vnorm && !v) return hipErrorInvalidValue;
+  if (p->scorer == AMS_SCORER_EXPECTED || vnorm) { mode = MODE_EXPECTED; a.g = g; }
   const int nb = wl.n_pad / 32;
   bool oneread = false;
   int vc_stride = 0, vc_tokens = 0;
@@ -543,6 +636,18 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
     vc->have = true;
     vc->stride = vc_stride;
     vc->tokens = vc_tokens;
+  }
+  if (vnorm) {
+    double2* part = (double2*)(ws + wl.kbar);
+    const dim3 grid(a.n_chunks, d.units), blk(kThreads);
+    prof_mark("esoftmax_part", s);
+    hipLaunchKernelGGL(esoftmax_part_kernel, grid, blk, 0, s, a, part);
+    prof_mark("vweight", s);
+    if (bf16)
+      hipLaunchKernelGGL(vweight_kernel<true>, grid, blk, 0, s, a, *v, (const double2*)part, p->vnorm_eps);
+    else
+      hipLaunchKernelGGL(vweight_kernel<false>, grid, blk, 0, s, a, *v, (const double2*)part, p->vnorm_eps);
+    e = hipGetLastError();
   }
   if (p->scorer == AMS_SCORER_KEYDIFF) {
     a.g = g;

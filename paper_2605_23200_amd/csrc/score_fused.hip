@@ -407,7 +407,8 @@ hipError_t launch_score_oneread(const ams_params* p, const Dims& d, const KvDev&
   float* g_out = nullptr;
   if (p->scorer == AMS_SCORER_MEAN_WINDOW) g_out = (g != u) ? g : nullptr;
   if (p->scorer == AMS_SCORER_LAST_QUERY) { mode = MODE_LAST; g_out = g; }
-  if (p->scorer == AMS_SCORER_EXPECTED) return hipSuccess;  // the moment-based score keeps all logits of a token live
+  // the moment-based scores keep all logits of a token live
+  if (p->scorer == AMS_SCORER_EXPECTED || p->scorer == AMS_SCORER_EXPECTED_VNORM) return hipSuccess;
   FusedArgs a;
   a.s.k = k;
   a.s.d = d;

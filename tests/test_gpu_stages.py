@@ -80,6 +80,32 @@ def test_score_causal_parity(oracle, dtype, G, W, T, scorer):
             assert_close_norm(g_h[i], go, what=f"g unit {i}")
 
 
+@pytest.mark.parametrize("dtype,G,W,T", [("f32", 1, 8, 4096), ("bf16", 4, 32, 5000), ("bf16", 7, 32, 2085),
+                                          ("bf16", 3, 5, 1), ("f32", 4, 32, 777)])
+def test_score_value_weighted_parity(oracle, dtype, G, W, T):
+    """g = (softmax over the cache of the log-moment scores + eps) * ||v|| (Sec. 3.3 plug-in scorer)."""
+    w = _workload(dtype, G, W, T)
+    host = inputs.dense_cache(w, n_threads=4)
+    host["V"][0, 0, 0, T // 2] = 0                                   # a zero value row
+    p = params_for(w, scorer=B.SCORER_EXPECTED_VNORM)
+    ws = workspace(p)
+    K, V, Q = to_dev(host["K"]), to_dev(host["V"]), to_dev(host["Q"])
+    lens = to_dev(host["seq_lens"])
+    u = torch.full((p.units, w.T), -7.0, device=DEV)
+    g = torch.full((p.units, w.T), -7.0, device=DEV)
+    with pytest.raises(B.AmsError):                                  # the values are needed
+        B.ams_score(p, B.dense_view(K, None), lens, Q, u, g, ws)
+    B.ams_score(p, B.dense_view(K, V), lens, Q, u, g, ws)
+    torch.cuda.synchronize()
+    u_h, g_h = to_host(u), to_host(g)
+    for i, (l, b, h) in enumerate(unit_list(w)):
+        uo, eo = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), host["K"][l, b, h, :T],
+                              w.G, w.W, B.SCORER_EXPECTED)
+        assert_close_rel(u_h[i], uo, what=f"u unit {i}")
+        assert_close_rel(g_h[i], oracle.value_weight(eo, host["V"][l, b, h, :T], 1e-2), what=f"g unit {i}")
+    assert g_h[0, T // 2] == 0
+
+
 def test_score_ragged_batch_paged(oracle):
     # ragged batch in a paged layout: lengths that are not multiples of 16 or 32, permuted blocks
     w = inputs.CONFIGS[2].scaled(L=2, B=3, H=2, T=1500, T_min=300, n_spans=3, span_len=(16, 64), budget=128)

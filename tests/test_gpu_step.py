@@ -49,10 +49,13 @@ def check_units(oracle, job, host, credit_before, units, scorer=B.SCORER_MEAN_WI
         T = int(lens[b])
         Kh, Vh = host["K"][l, b, h, :T], host["V"][l, b, h, :T]
         if check_scores:
-            uo, go = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), Kh, w.G, w.W, scorer,
-                                  causal=w.causal)
+            vnorm = scorer == B.SCORER_EXPECTED_VNORM
+            uo, go = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), Kh, w.G, w.W,
+                                  B.SCORER_EXPECTED if vnorm else scorer, causal=w.causal)
+            if vnorm:
+                go = oracle.value_weight(go, Vh, 1e-2)
             assert_close_rel(u_g[j, :T], uo, what=f"u unit {i}")
-            if scorer in (B.SCORER_MEAN_WINDOW, B.SCORER_LAST_QUERY):
+            if scorer in (B.SCORER_MEAN_WINDOW, B.SCORER_LAST_QUERY, B.SCORER_EXPECTED_VNORM):
                 assert_close_rel(g_g[j, :T], go, what=f"g unit {i}")
             else:
                 assert_close_norm(g_g[j, :T], go, what=f"g unit {i}")
@@ -259,11 +262,11 @@ def test_config3_long_context(oracle):
     check_units(oracle, job, host, zeros, [0, 1])
 
 
-@pytest.mark.parametrize("scorer", ["last", "mean", "keydiff", "expected"])
+@pytest.mark.parametrize("scorer", ["last", "mean", "keydiff", "expected", "expected_vnorm"])
 def test_config4_scorer_sweep(oracle, scorer):
     """Config 4: scorer x S in {1,4,16,64} x budget in T/{8,16,32}; S = 1 must equal a global top-k."""
     sc = {"last": B.SCORER_LAST_QUERY, "mean": B.SCORER_MEAN_WINDOW, "keydiff": B.SCORER_KEYDIFF,
-          "expected": B.SCORER_EXPECTED}[scorer]
+          "expected": B.SCORER_EXPECTED, "expected_vnorm": B.SCORER_EXPECTED_VNORM}[scorer]
     base = inputs.CONFIGS[4].scaled(L=1, H=2, T=8192, n_spans=10)
     host = inputs.dense_cache(base, n_threads=8)
     zeros = np.zeros((base.units, base.T), np.float32)
