@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--l-min", type=int, default=0)
     ap.add_argument("--l-max", type=int, default=0)
     ap.add_argument("--pool", type=int, default=0, help="average-pooling kernel of the usage (odd)")
+    ap.add_argument("--scorer", default="mean_window",
+                    choices=["mean_window", "last_query", "keydiff", "expected", "expected_vnorm"],
+                    help="base scorer (the headline workload uses mean_window)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that a counter run of this "
                          "command can be scaled: see profiles/")
@@ -90,7 +93,10 @@ def main():
         sys.exit("bench.py: only dense single-length workloads are benchmark lines")
     t0 = time.time()
     host = inputs.dense_cache(w, n_threads=16)
-    job = Job(w, host)
+    scorer_id = {"mean_window": B.SCORER_MEAN_WINDOW, "last_query": B.SCORER_LAST_QUERY,
+                 "keydiff": B.SCORER_KEYDIFF, "expected": B.SCORER_EXPECTED,
+                 "expected_vnorm": B.SCORER_EXPECTED_VNORM}[args.scorer]
+    job = Job(w, host, scorer=scorer_id)
     n_q = 4
     q_windows = [job.Q] + [torch.empty_like(job.Q) for _ in range(n_q - 1)]
     for e in range(1, n_q):
@@ -157,7 +163,7 @@ def main():
                                + ("; causal window" if w.causal else "")
                                + (f"; Delta {w.seg_delta} L {w.l_min}/{w.l_max}" if w.seg_delta else "")
                                + (f"; pool {w.pool_kernel}" if w.pool_kernel > 1 else ""),
-                   "units": w.units, "scorer": "mean_window"},
+                   "units": w.units, "scorer": args.scorer},
         "effective_GBps": round(eff_gbps, 1), "algorithmic_bytes_per_step": step_bytes,
         "hbm_peak_frac": round(eff_gbps / HBM_PEAK_GBPS, 4),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
@@ -180,7 +186,9 @@ def main():
         t0 = time.perf_counter()
         _, _, used = O.compress_many(np.ascontiguousarray(Qf), np.ascontiguousarray(Kf), credit, G=w.G, W=w.W,
                                      budget=w.budget, S=w.S, lam=w.lam, beta=w.beta, eps=w.eps, q_min=w.q_min,
-                                     n_threads=n_threads, K_rows=Kr, V_rows=Vr, n_sink=w.n_sink, n_last=w.n_last,
+                                     n_threads=n_threads, K_rows=Kr, V_rows=Vr, scorer=scorer_id,
+                                     V=np.ascontiguousarray(np.stack([inputs.as_f32(host["V"][l, b, h]) for l, b, h in ids]))
+                                     if scorer_id == B.SCORER_EXPECTED_VNORM else None, n_sink=w.n_sink, n_last=w.n_last,
                                      causal=w.causal, delta=w.seg_delta, l_min=w.l_min, l_max=w.l_max,
                                      pool_kernel=w.pool_kernel)
         cpu_s = time.perf_counter() - t0

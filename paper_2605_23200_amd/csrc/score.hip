@@ -43,8 +43,14 @@ __device__ __forceinline__ int causal_t_end(const ScoreArgs& a, int T) {
   return a.causal ? max(0, (T - a.d.W + 1) / 32 * 32) : T;
 }
 
-template <bool BF16, int NB, bool TAIL>
-__global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES : 2) void score_stats_kernel(ScoreArgs a) {
+//
+// MOMENTS (expected-attention score, Sec. 3.3 plug-in scorer): the log of the Gaussian moment of the
+// window's queries is mean_n s + var_n s / 2 over the N logits of a token.  It needs no softmax
+// statistics, so it is formed here, where few registers are live, from sums of (s - r) and (s - r)^2
+// with r the token's logit against the unit's first query (a reference close to the mean keeps the
+// subtraction of the squares harmless).  Raw logits are used: the causal mask does not apply.
+template <bool BF16, int NB, bool TAIL, bool MOMENTS>
+__global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE_MIN_WAVES : 2) void score_stats_kernel(ScoreArgs a) {
   constexpr int NG = kGroup<NB>, QS = Tr<BF16>::kQStride, NBLK = kScoreChunk / 128;
   extern __shared__ __align__(16) char qlds[];
   __shared__ float2 xch[4][NB * 32];
@@ -68,16 +74,39 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
     z[nb] = 0.f;
   }
   const float c2 = a.c2;
+  float* g_row = MOMENTS ? a.g + (int64_t)unit * a.d.t_stride : nullptr;
   auto block = [&](const uint4 (&av)[Tr<BF16>::kAVecs], int t0) __attribute__((always_inline)) {
     const bool ragged = t0 + 32 > T;
     // the query fragments are re-read from LDS for every block: keeping them in registers across
     // blocks would cost more registers than the reads cost time, so their address is made opaque
     int qoff = 0;
     asm volatile("" : "+s"(qoff));
+    float ref[16], s1[16], s2[16];
 #pragma unroll
     for (int g0 = 0; g0 < NB; g0 += NG) {
       floatx16 acc[NG];
       tile_mma<BF16, NG>(av, qlds + qoff + g0 * 32 * QS, lane, acc);
+      if (MOMENTS) {
+        if (g0 == 0) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            // the half wave's first lane holds the logit against query 0 of the rows this lane owns
+            const float r0 = __builtin_amdgcn_readlane(acc[0][i], 0), r1 = __builtin_amdgcn_readlane(acc[0][i], 32);
+            ref[i] = hf ? r1 : r0;
+            s1[i] = s2[i] = 0.f;
+          }
+        }
+#pragma unroll
+        for (int k = 0; k < NG; ++k) {
+          const bool real = (g0 + k) * 32 + (lane & 31) < a.d.N;  // padded query columns do not count
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float dlt = real ? acc[k][i] - ref[i] : 0.f;
+            s1[i] += dlt;
+            s2[i] = __builtin_fmaf(dlt, dlt, s2[i]);
+          }
+        }
+      }
 #pragma unroll
       for (int k = 0; k < NG; ++k) {
         const int nb = g0 + k;
@@ -100,6 +129,19 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
         z[nb] = __builtin_fmaf(z[nb], __builtin_amdgcn_exp2f(m[nb] - mx), sum);
         m[nb] = mx;
       }
+    }
+    if (MOMENTS) {
+      const int c = lane & 31;
+      float rr[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) rr[i] = c == 0 ? ref[i] : 0.f;
+      const float inv_n = 1.f / (float)a.d.N;
+      const float r_tok = reduce16_over32(rr, c);            // the reference of token c >> 1
+      const float d_mean = reduce16_over32(s1, c) * inv_n;   // mean of s - r
+      const float d_sq = reduce16_over32(s2, c) * inv_n;     // mean of (s - r)^2
+      const int t = t0 + acc_row(c >> 1, hf);
+      if ((c & 1) == 0 && t < T_all)
+        g_row[t] = (r_tok + d_mean) * a.inv_sqrt_d + 0.5f * (d_sq - d_mean * d_mean) * (a.inv_sqrt_d * a.inv_sqrt_d);
     }
   };
 #pragma unroll 1
@@ -183,14 +225,13 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Sweep 2: u[t] = sum_n exp2(x[n][t] - M_n) / (N Z_n), and g for the softmax- or moment-based scorers.
+// Sweep 2: u[t] = sum_n exp2(x[n][t] - M_n) / (N Z_n), and g for the softmax-based scorers.
 // ---------------------------------------------------------------------------------------------
 // TAIL (causal window, blocks from t_end on): a (query, key) pair the mask hides adds nothing, and
 // every observation a key is missing counts as the largest share it got.
 template <bool BF16, int NB, int MODE, bool TAIL>
 __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES : 2) void score_usage_kernel(ScoreArgs a) {
-  // the moment-based scorer needs all N logits of a token twice: keep every column block live
-  constexpr int NG = (MODE == MODE_EXPECTED) ? NB : kGroup<NB>;
+  constexpr int NG = kGroup<NB>;
   constexpr int QS = Tr<BF16>::kQStride, NBLK = kScoreChunk / 128;
   extern __shared__ __align__(16) char qlds[];
   const int unit = blockIdx.y, chunk = blockIdx.x;
@@ -211,7 +252,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   for (int nb = 0; nb < NB; ++nb) f[nb] = a.fin[(int64_t)unit * a.n_pad + nb * 32 + c];
   float* u_row = a.u + (int64_t)unit * a.d.t_stride;
   float* g_row = a.g ? a.g + (int64_t)unit * a.d.t_stride : nullptr;
-  const float inv_n = 1.f / (float)a.d.N, c2 = a.c2;
+  const float c2 = a.c2;
   const float* c_row = a.credit ? a.credit + (int64_t)unit * a.d.t_stride : nullptr;
   float v_part = 0.f;  // this lane's share of sum(max(u,0)+eps): at most 8 terms
   auto block = [&](const uint4 (&av)[Tr<BF16>::kAVecs], int t0) __attribute__((always_inline)) {
@@ -226,27 +267,6 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
     for (int g0 = 0; g0 < NB; g0 += NG) {
       floatx16 acc[NG];
       tile_mma<BF16, NG>(av, qlds + qoff + g0 * 32 * QS, lane, acc);
-      if (MODE == MODE_EXPECTED) {
-        // mean and centred second moment of the N logits of each token (padded queries add exact zeros)
-#pragma unroll
-        for (int k = 0; k < NG; ++k)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) pg[i] += acc[k][i] * a.inv_sqrt_d;
-        const float mean_mine = reduce16_over32(pg, c) * inv_n;
-        float pv[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float mean_i = __shfl(mean_mine, 2 * i + 32 * hf);
-          float s2 = 0.f;
-#pragma unroll
-          for (int k = 0; k < NG; ++k) {
-            const float dlt = acc[k][i] * a.inv_sqrt_d - mean_i;
-            s2 += f[g0 + k].w * dlt * dlt;
-          }
-          pv[i] = s2;
-        }
-        rg = mean_mine + 0.5f * reduce16_over32(pv, c) * inv_n;
-      }
 #pragma unroll
       for (int k = 0; k < NG; ++k) {
         const int nb = g0 + k;
@@ -385,6 +405,7 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   constexpr int CPR = Tr<BF16>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
   __shared__ double kbar[128];
   __shared__ double kbar_norm;
+  __shared__ float2 row_sums[kScoreChunk];  // per token: k . kbar and k . k
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
@@ -406,9 +427,13 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   __syncthreads();
   const int col = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
   float* g_row = a.g + (int64_t)unit * a.d.t_stride;
+  float kb[EPC];  // this lane's channels of the mean key
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) kb[e] = (float)kbar[col * EPC + e];
   for (int tb = c0; tb < min(T, c0 + kScoreChunk); tb += RPI) {
     const int t = tb + r0;
-    double dot = 0.0, nk = 0.0;
+    // a row's 128 products are summed in fp32 (8 per lane, then 16 or 32 lanes); the ratio is formed in double
+    float dot = 0.f, nk = 0.f;
     if (t < T) {
       const uint4 v = *(const uint4*)(kv_row(a.k, l, b, h, t) + col * 16);
       float x[8];
@@ -416,8 +441,8 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
       widen8<BF16>(v, x, n);
 #pragma unroll
       for (int e = 0; e < EPC; ++e) {
-        dot += (double)x[e] * kbar[col * EPC + e];
-        nk += (double)x[e] * (double)x[e];
+        dot = __builtin_fmaf(x[e], kb[e], dot);
+        nk = __builtin_fmaf(x[e], x[e], nk);
       }
     }
     // the CPR lanes of a row are consecutive lanes of one wave
@@ -426,10 +451,14 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
       dot += __shfl_xor(dot, o);
       nk += __shfl_xor(nk, o);
     }
-    if (col == 0 && t < T) {
-      const double den = sqrt(nk) * kbar_norm;
-      g_row[t] = den > 0.0 ? (float)(-dot / den) : 0.f;
-    }
+    if (col == 0 && t < T) row_sums[t - c0] = make_float2(dot, nk);
+  }
+  __syncthreads();
+  // one token per thread for the ratio, so that every lane works
+  for (int t = c0 + threadIdx.x; t < min(T, c0 + kScoreChunk); t += kThreads) {
+    const float2 r = row_sums[t - c0];
+    const double den = sqrt((double)r.y) * kbar_norm;
+    g_row[t] = den > 0.0 ? (float)(-(double)r.x / den) : 0.f;
   }
 }
 
@@ -484,6 +513,7 @@ template <bool BF16>
 __global__ __launch_bounds__(kThreads) void vweight_kernel(ScoreArgs a, KvDev v, const double2* part, float eps_f) {
   constexpr int CPR = Tr<BF16>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
   __shared__ double2 stat;
+  __shared__ float norm2[kScoreChunk];  // per token: v . v
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
@@ -507,25 +537,42 @@ __global__ __launch_bounds__(kThreads) void vweight_kernel(ScoreArgs a, KvDev v,
   float* g_row = a.g + (int64_t)unit * a.d.t_stride;
   for (int tb = c0; tb < min(T, c0 + kScoreChunk); tb += RPI) {
     const int t = tb + r0;
-    double n2 = 0.0;
+    float n2 = 0.f;  // 128 squares summed in fp32, the rest in double
     if (t < T) {
       const uint4 x4 = *(const uint4*)(kv_row(v, l, b, h, t) + col * 16);
       float x[8];
       int n;
       widen8<BF16>(x4, x, n);
 #pragma unroll
-      for (int e = 0; e < EPC; ++e) n2 += (double)x[e] * (double)x[e];
+      for (int e = 0; e < EPC; ++e) n2 = __builtin_fmaf(x[e], x[e], n2);
     }
     // the CPR lanes of a row are consecutive lanes of one wave
 #pragma unroll
     for (int o = CPR / 2; o >= 1; o >>= 1) n2 += __shfl_xor(n2, o);
-    if (col == 0 && t < T) g_row[t] = (float)((exp((double)g_row[t] - M) * inv_z + eps) * sqrt(n2));
+    if (col == 0 && t < T) norm2[t - c0] = n2;
   }
+  __syncthreads();
+  // one token per thread for the exponential, so that every lane works
+  for (int t = c0 + threadIdx.x; t < min(T, c0 + kScoreChunk); t += kThreads)
+    g_row[t] = (float)((exp((double)g_row[t] - M) * inv_z + eps) * sqrt((double)norm2[t - c0]));
 }
 
 template <typename K>
 hipError_t set_lds(K kernel, int bytes) {
   return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+template <bool BF16, int NB, bool TAIL>
+hipError_t launch_stats(const ScoreArgs& a, bool moments, dim3 grid, int lds, hipStream_t s) {
+  hipError_t e;
+  if (moments) {
+    if ((e = set_lds(score_stats_kernel<BF16, NB, TAIL, true>, lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL((score_stats_kernel<BF16, NB, TAIL, true>), grid, dim3(kThreads), lds, s, a);
+  } else {
+    if ((e = set_lds(score_stats_kernel<BF16, NB, TAIL, false>, lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL((score_stats_kernel<BF16, NB, TAIL, false>), grid, dim3(kThreads), lds, s, a);
+  }
+  return hipGetLastError();
 }
 
 template <bool BF16, int NB, bool TAIL>
@@ -537,10 +584,6 @@ hipError_t launch_usage(const ScoreArgs& a, int mode, dim3 grid, int lds, hipStr
       if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_LAST, TAIL>, lds)) != hipSuccess) return e;
       hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_LAST, TAIL>), grid, blk, lds, s, a);
       break;
-    case MODE_EXPECTED:
-      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_EXPECTED, TAIL>, lds)) != hipSuccess) return e;
-      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_EXPECTED, TAIL>), grid, blk, lds, s, a);
-      break;
     default:
       if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_MEAN, TAIL>, lds)) != hipSuccess) return e;
       hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_MEAN, TAIL>), grid, blk, lds, s, a);
@@ -551,23 +594,24 @@ hipError_t launch_usage(const ScoreArgs& a, int mode, dim3 grid, int lds, hipStr
 template <bool BF16, int NB>
 hipError_t run_softmax_sweeps(const ScoreArgs& a, int mode, hipStream_t s) {
   const int lds = NB * 32 * Tr<BF16>::kQStride;
-  const dim3 grid(a.n_chunks, a.d.units), blk(kThreads);
+  const dim3 grid(a.n_chunks, a.d.units);
   hipError_t e;
-  if ((e = set_lds(score_stats_kernel<BF16, NB, false>, lds)) != hipSuccess) return e;
   prof_mark("score_stats", s);
-  hipLaunchKernelGGL((score_stats_kernel<BF16, NB, false>), grid, blk, lds, s, a);
+  if ((e = launch_stats<BF16, NB, false>(a, mode == MODE_EXPECTED, grid, lds, s)) != hipSuccess) return e;
   if (a.causal) {
-    if ((e = set_lds(score_stats_kernel<BF16, NB, true>, lds)) != hipSuccess) return e;
     prof_mark("score_stats_tail", s);
-    hipLaunchKernelGGL((score_stats_kernel<BF16, NB, true>), dim3(1, a.d.units), blk, lds, s, a);
+    if ((e = launch_stats<BF16, NB, true>(a, mode == MODE_EXPECTED, dim3(1, a.d.units), lds, s)) != hipSuccess) return e;
   }
   prof_mark("score_reduce", s);
   hipLaunchKernelGGL(score_reduce_kernel, dim3(a.d.units), dim3(kReduceThreads), 0, s, a);
+  // the moment-based score has been written by the first sweep: the second one leaves g alone
+  ScoreArgs a2 = a;
+  if (mode == MODE_EXPECTED) a2.g = nullptr;
   prof_mark("score_usage", s);
-  if ((e = launch_usage<BF16, NB, false>(a, mode, grid, lds, s)) != hipSuccess) return e;
+  if ((e = launch_usage<BF16, NB, false>(a2, mode, grid, lds, s)) != hipSuccess) return e;
   if (a.causal) {
     prof_mark("score_usage_tail", s);
-    if ((e = launch_usage<BF16, NB, true>(a, mode, dim3(1, a.d.units), lds, s)) != hipSuccess) return e;
+    if ((e = launch_usage<BF16, NB, true>(a2, mode, dim3(1, a.d.units), lds, s)) != hipSuccess) return e;
   }
   return hipSuccess;
 }
