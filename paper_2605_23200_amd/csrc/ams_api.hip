@@ -46,6 +46,7 @@ WsLayout ws_layout(const ams_params* p) {
   w.cpre = o;       o += align256(units * (size_t)(p->n_segments + 1) * sizeof(double));
   w.n_words = div_up(p->t_max, 32);
   w.flags = o;      o += align256(units * (size_t)w.n_words * sizeof(uint32_t));
+  w.csum = o;       o += align256(units * sizeof(double));
   w.total = o;
   return w;
 }

@@ -62,7 +62,7 @@ inline int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 // Workspace carving (offsets in bytes, 256-byte aligned).
 struct WsLayout {
-  size_t part_stats, fin_stats, u, g, m_used, bounds, seg_mass, quota, kbar, fused, vc_part, mpart, cpre, flags, total;
+  size_t part_stats, fin_stats, u, g, m_used, bounds, seg_mass, quota, kbar, fused, vc_part, mpart, cpre, flags, csum, total;
   int n_chunks, n_pad;
   int n_chunks4k;  // chunks of kChunk positions per unit
   int n_words;     // 32-position words of the kept-set bitmap per unit

@@ -222,6 +222,32 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
     f.w = real ? 1.f : 0.f;
     a.fin[(int64_t)unit * a.n_pad + n] = f;
   }
+  if (a.csum) {  // sum of the credit before the update (for the EMA normaliser), strided partials in a fixed tree
+    __shared__ double cs[kReduceThreads / 64];
+    const float* c_row = a.credit + (int64_t)unit * a.d.t_stride;
+    double c = 0.0;
+    if ((a.d.t_stride & 3) == 0 && ((uintptr_t)a.credit & 15) == 0) {  // 16-byte loads, several in flight
+      const float4* c4 = (const float4*)c_row;
+      const int n4 = T >> 2;
+#pragma unroll 8
+      for (int q = threadIdx.x; q < n4; q += kReduceThreads) {
+        const float4 v = c4[q];
+        c += ((double)v.x + (double)v.y) + ((double)v.z + (double)v.w);
+      }
+      for (int t = (n4 << 2) + threadIdx.x; t < T; t += kReduceThreads) c += (double)c_row[t];
+    } else {
+      for (int t = threadIdx.x; t < T; t += kReduceThreads) c += (double)c_row[t];
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) c += __shfl_xor(c, o);
+    if ((threadIdx.x & 63) == 0) cs[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double t = 0.0;
+      for (int w = 0; w < kReduceThreads / 64; ++w) t += cs[w];
+      a.csum[unit] = t;
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -253,7 +279,6 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   float* u_row = a.u + (int64_t)unit * a.d.t_stride;
   float* g_row = a.g ? a.g + (int64_t)unit * a.d.t_stride : nullptr;
   const float c2 = a.c2;
-  const float* c_row = a.credit ? a.credit + (int64_t)unit * a.d.t_stride : nullptr;
   float v_part = 0.f;  // this lane's share of sum(max(u,0)+eps): at most 8 terms
   auto block = [&](const uint4 (&av)[Tr<BF16>::kAVecs], int t0) __attribute__((always_inline)) {
     float pu[16], pg[16], pm[16];
@@ -315,30 +340,17 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
     if (blk + 2 < NBLK && t0 + 256 < T) load_a<BF16>(a, l, b, h, t0 + 256, T, lane, av0);
     block(av1, t0 + 128);
   }
-  if (a.vc_part) {  // chunk sums in a fixed order: lanes, then waves
-    __shared__ double2 vc_sm[4];
-    double v_acc = (double)v_part, c_acc = 0.0;
-    if (c_row) {  // the chunk's credit, a few consecutive positions per thread
-      constexpr int PER = kScoreChunk / kThreads;
-      const int j0 = c0 + threadIdx.x * PER;
+  if (a.vc_part) {  // chunk sums of max(u,0)+eps in a fixed order: lanes, then waves
+    __shared__ double vc_sm[4];
+    double v_acc = (double)v_part;
 #pragma unroll
-      for (int i = 0; i < PER; ++i)
-        if (j0 + i < T) c_acc += (double)c_row[j0 + i];
-    }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-      v_acc += __shfl_xor(v_acc, o);
-      c_acc += __shfl_xor(c_acc, o);
-    }
-    if (lane == 0) vc_sm[wave] = make_double2(v_acc, c_acc);
+    for (int o = 32; o >= 1; o >>= 1) v_acc += __shfl_xor(v_acc, o);
+    if (lane == 0) vc_sm[wave] = v_acc;
     __syncthreads();
     if (threadIdx.x == 0) {
-      double2 t = vc_sm[0];
-      for (int w = 1; w < 4; ++w) {
-        t.x += vc_sm[w].x;
-        t.y += vc_sm[w].y;
-      }
-      a.vc_part[(int64_t)unit * a.n_chunks + chunk] = t;
+      // the unit's credit sum (formed between the sweeps) rides in the first chunk's entry
+      const double c = (chunk == 0 && a.csum) ? a.csum[unit] : 0.0;
+      a.vc_part[(int64_t)unit * a.n_chunks + chunk] = make_double2((vc_sm[0] + vc_sm[1]) + (vc_sm[2] + vc_sm[3]), c);
     }
   }
 }
@@ -642,6 +654,7 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
   if (causal) vc = nullptr;
   a.vc_part = vc ? (double2*)(ws + wl.vc_part) : nullptr;
   a.credit = credit;
+  a.csum = (vc && credit) ? (double*)(ws + wl.csum) : nullptr;
   a.eps = p->mass_eps;
   a.k = k;
   a.d = d;

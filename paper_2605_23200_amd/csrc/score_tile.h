@@ -29,10 +29,12 @@ struct ScoreArgs {
   int n_chunks, n_pad;
   float c2;          // log2(e) / sqrt(D)
   float inv_sqrt_d;  // 1 / sqrt(D)
-  // optional by-product of the second sweep for Eq. (1) and the EMA: per 1024-token chunk the sums
-  // of max(u,0)+eps and of the credit before the update (NULL: not wanted)
+  // optional by-products for Eq. (1) and the EMA (NULL: not wanted): per chunk the sum of
+  // max(u,0)+eps from the second sweep; the unit's sum of the credit before the update, formed by the
+  // kernel that merges the statistics and carried in the first chunk's entry
   double2* vc_part;     // [units][n_chunks]
   const float* credit;  // [units][t_stride]
+  double* csum;         // [units]
   float eps;
   bool causal;  // causal window (App. A): query w of the window sees keys 0 .. T-W+w
 };
