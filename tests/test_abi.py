@@ -51,7 +51,12 @@ def test_workspace_bytes_and_layout():
     ("ema_lambda", 1.0, B.ERR_INVALID_ARG), ("ema_lambda", -0.1, B.ERR_INVALID_ARG),
     ("ema_beta", 1.5, B.ERR_INVALID_ARG), ("mass_eps", 0.0, B.ERR_INVALID_ARG), ("kv_dtype", 7, B.ERR_INVALID_ARG),
     ("scorer", 9, B.ERR_INVALID_ARG), ("head_dim", 96, B.ERR_UNSUPPORTED), ("n_segments", 5000, B.ERR_UNSUPPORTED),
-    ("window", 100, B.ERR_UNSUPPORTED), ("n_layers", 10000, B.ERR_UNSUPPORTED)])
+    ("window", 100, B.ERR_UNSUPPORTED), ("n_layers", 10000, B.ERR_UNSUPPORTED),
+    ("n_sink", -1, B.ERR_INVALID_ARG), ("n_last", -3, B.ERR_INVALID_ARG), ("causal", 2, B.ERR_INVALID_ARG),
+    ("pool_kernel", 4, B.ERR_INVALID_ARG), ("pool_kernel", 65, B.ERR_INVALID_ARG), ("seg_delta", -0.1, B.ERR_INVALID_ARG),
+    ("seg_delta", 1e-4, B.ERR_INVALID_ARG),            # more than 1024 initial segments
+    ("seg_delta", 0.05, B.ERR_INVALID_ARG),            # 20 initial segments do not fit the 8 entries
+    ("l_max", 64, B.ERR_INVALID_ARG)])                 # length rules without a target mass
 def test_bad_params_are_rejected_on_the_host(field, value, status):
     p = _good()
     setattr(p, field, value)
@@ -60,6 +65,32 @@ def test_bad_params_are_rejected_on_the_host(field, value, status):
     assert B.lib().ams_workspace_layout(C.byref(p), C.byref(out)) == status
     # the launching entry points return the same status before touching any pointer
     assert B.lib().ams_ema_update(C.byref(p), None, None, None, None, None, 0, None) == status
+
+
+def test_segmentation_capacity_rule():
+    # target mass 0.1 -> 10 initial segments; with L_max = 256 up to 4096 / 256 = 16 more
+    p = _good()
+    p.seg_delta, p.l_min, p.l_max = 0.1, 16, 256
+    p.n_segments = 25
+    assert B.ams_workspace_bytes(p) == 0
+    p.n_segments = 26
+    assert B.ams_workspace_bytes(p) > 0
+    p.l_min = 300                                      # L_min above L_max
+    assert B.ams_workspace_bytes(p) == 0
+
+
+def test_optional_features_need_their_inputs():
+    L = B.lib()
+    p = _good()
+    p.n_sink = 4                                       # the must-keep path needs the workspace
+    assert L.ams_select(C.byref(p), 64, 64, 64, 64, 64, 64, 64, None, 0, None) == B.ERR_INVALID_ARG
+    assert L.ams_select(C.byref(p), 64, 64, 64, 64, 64, 64, 64, 64, 16, None) == B.ERR_WORKSPACE_TOO_SMALL
+    p = _good()
+    p.scorer = B.SCORER_EXPECTED_VNORM                 # the value-weighted scorer needs V
+    v = B.KvView(B.LAYOUT_DENSE, 64, None, 4096, None, 0, 0, 0)
+    assert L.ams_score(C.byref(p), C.byref(v), 64, 64, 64, 64, 64, 1 << 40, None) == B.ERR_INVALID_ARG
+    p.vnorm_eps = -1.0
+    assert B.ams_workspace_bytes(p) == 0
 
 
 def test_null_pointers_are_rejected_without_launch():
