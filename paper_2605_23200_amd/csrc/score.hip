@@ -260,7 +260,9 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   constexpr int NG = kGroup<NB>;
   constexpr int QS = Tr<BF16>::kQStride, NBLK = kScoreChunk / 128;
   extern __shared__ __align__(16) char qlds[];
-  const int unit = blockIdx.y, chunk = blockIdx.x;
+  // the second sweep walks the cache backwards: what the first sweep read last is still in the
+  // memory-side cache (about a tenth of the keys at the headline size)
+  const int unit = gridDim.y - 1 - blockIdx.y, chunk = TAIL ? 0 : gridDim.x - 1 - blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T_all = a.seq_lens[b], t_end = causal_t_end(a, T_all);

@@ -403,3 +403,31 @@ def test_one_read_scorer_path(oracle, monkeypatch):
     job.step()
     labels = [k for k, _ in B.ams_profile_end()]
     assert "score_stats" in labels and "score_usage" in labels               # default: the two sweeps
+
+
+def test_step_under_graph_capture(oracle):
+    """The fused call allocates nothing and never waits for the stream, so it can be recorded into a
+    HIP graph; every replay (with eager work between replays) gives the eager result bit for bit."""
+    w = inputs.CONFIGS[1].scaled(L=2, H=4, T=5000, budget=512, S=8, n_spans=6, span_len=(32, 300), n_sink=4,
+                                 n_last=32, causal=True)
+    host = inputs.dense_cache(w, n_threads=4)
+    job = Job(w, host)
+    job.step()                                             # eager: also sets the kernels' attributes once
+    torch.cuda.synchronize()
+    want = (job.idx.clone(), job.Kd.clone(), job.credit.clone(), job.credit_dst.clone())
+    credit0 = torch.zeros_like(job.credit)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    job.credit.copy_(credit0)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        job.step(torch.cuda.current_stream())
+    for _ in range(3):
+        job.credit.copy_(credit0)                          # eager work between the replays
+        job.idx.fill_(-7)
+        job.Kd.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(job.idx, want[0]) and torch.equal(job.Kd, want[1])
+        assert torch.equal(job.credit, want[2]) and torch.equal(job.credit_dst, want[3])
