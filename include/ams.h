@@ -20,6 +20,10 @@
  *  - Per-unit fp32 vectors (u, g, credit, m_used) are rows of a
  *    [units, t_stride] array; only the first seq_lens[b] entries of a row are
  *    read or written.
+ *  - A seq_lens[b] outside [0, t_max] is read as the nearest bound, and the
+ *    compaction skips an index outside [0, t_max): wrong lengths or indices give
+ *    wrong results for that unit, never an access outside the caller's buffers
+ *    (as long as those have the documented sizes).
  *  - Positions are 0-based positions in the CURRENT cache (the mass curve is
  *    defined "over current KV-cache positions", Fig. 3 caption).
  *  - KV head h owns query heads h*group .. h*group + group - 1.
@@ -224,11 +228,18 @@ int ams_compact(const ams_params* p, const ams_kv_view* src, const int32_t* idx,
                 float* credit_dst, void* stream);
 
 /*
- * ams_compress_step - one whole event: score -> Eq. (1) -> EMA -> prefix sum and
- * boundaries -> quotas -> segmented top-k -> gather-compact, in that order, all
- * enqueued on `stream`.  credit [units, t_stride] is updated in place at full
- * length; credit_dst [units, budget] receives the kept tokens' credit.
- * p->scorer must not be AMS_SCORER_EXTERNAL.
+ * ams_compress_step - one whole event (Alg. 1): score -> Eq. (1) -> EMA -> prefix
+ * sum and boundaries -> quotas -> segmented top-k (+ must-keep set) ->
+ * gather-compact, in that order, all enqueued on `stream`; every optional rule of
+ * ams_params (causal window, pooling, target mass with split / merge, must-keep
+ * set, scorer) applies as documented at the stage calls.  credit [units,
+ * t_stride] is updated in place at full length; credit_dst [units, budget]
+ * receives the kept tokens' credit.  src->v is read by the compaction and by
+ * AMS_SCORER_EXPECTED_VNORM.  The call allocates nothing and waits for nothing,
+ * so it may be recorded into a HIP graph.
+ * Errors: AMS_ERR_INVALID_ARG for a null pointer, for p->scorer ==
+ * AMS_SCORER_EXTERNAL and for dense src and dst that share a buffer;
+ * AMS_ERR_WORKSPACE_TOO_SMALL; AMS_ERR_HIP if a launch fails.
  */
 int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t* seq_lens,
                       const void* q, float* credit, const ams_kv_view* dst, float* credit_dst,

@@ -27,7 +27,8 @@ __device__ __forceinline__ char* kv_row(const KvDev& kv, int l, int b, int h, in
     const int64_t unit = ((int64_t)l * kv.B + b) * kv.H + h;
     return kv.base + (unit * kv.t_capacity + t) * (int64_t)kv.row_bytes;
   }
-  const int64_t slot = (int64_t)kv.block_table[(int64_t)b * kv.max_blocks + (t >> 4)] * 16 + (t & 15);
+  int64_t slot = (int64_t)kv.block_table[(int64_t)b * kv.max_blocks + (t >> 4)] * 16 + (t & 15);
+  slot = slot < 0 ? 0 : (slot >= kv.n_slots ? kv.n_slots - 1 : slot);  // a bad table entry stays inside the pool
   return kv.base + (((int64_t)l * kv.n_slots + slot) * kv.H + h) * (int64_t)kv.row_bytes;
 }
 
@@ -43,6 +44,12 @@ __device__ __forceinline__ void unit_coords(const Dims& d, int unit, int& l, int
   const int lb = unit / d.H;
   b = lb % d.B;
   l = lb / d.B;
+}
+
+// Length of sequence b as the kernels use it: a value outside [0, t_max] (a caller's mistake) is
+// clamped, so that no kernel leaves the arrays sized for t_max.
+__device__ __forceinline__ int seq_len(const Dims& d, const int32_t* seq_lens, int b) {
+  return max(0, min(seq_lens[b], d.t_max));
 }
 
 #ifndef AMS_SCORE_CHUNK

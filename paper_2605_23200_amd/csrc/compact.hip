@@ -17,7 +17,10 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(Dims d, KvDev ks, KvDev
   const int unit = blockIdx.y;
   int l, b, h;
   unit_coords(d, unit, l, b, h);
-  const int n = n_kept_all[unit];
+  // a count above the budget or an index outside the cache (a caller's mistake when the stage is
+  // used on its own) must not turn into an access outside the buffers: the count is clamped and
+  // such a row is skipped
+  const int n = min(n_kept_all[unit], min(budget, d.t_max));
   const int j0 = blockIdx.x * kRowsPerBlock;
   if (j0 >= n) return;
   const int32_t* idx = idx_all + (int64_t)unit * budget;
@@ -28,6 +31,7 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(Dims d, KvDev ks, KvDev
     const int j = j0 + jj;
     if (j >= n) break;
     const int t = idx[j];
+    if (t < 0 || t >= d.t_max) continue;
     const uint4 kx = *(const uint4*)(kv_row(ks, l, b, h, t) + sub * 16);
     const uint4 vx = *(const uint4*)(kv_row(vs, l, b, h, t) + sub * 16);
     *(uint4*)(kv_row(kd, l, b, h, j) + sub * 16) = kx;
@@ -35,7 +39,8 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(Dims d, KvDev ks, KvDev
   }
   if (credit_src && credit_dst && threadIdx.x < kRowsPerBlock) {
     const int j = j0 + threadIdx.x;
-    if (j < n) credit_dst[(int64_t)unit * budget + j] = credit_src[(int64_t)unit * d.t_stride + idx[j]];
+    if (j < n && idx[j] >= 0 && idx[j] < d.t_max)
+      credit_dst[(int64_t)unit * budget + j] = credit_src[(int64_t)unit * d.t_stride + idx[j]];
   }
 }
 

@@ -200,7 +200,7 @@ __global__ __launch_bounds__(kBlock) void vc_sums_kernel(MsArgs a, const float* 
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = seq_len(a.d, a.seq_lens, b);
   const int j0 = chunk * kChunk + threadIdx.x * kPer;
   if (chunk * kChunk >= T) return;
   const float* u = u_all + (int64_t)unit * a.d.t_stride;
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(kBlock) void mass_ema_kernel(MsArgs a, const float*
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = seq_len(a.d, a.seq_lens, b);
   if (chunk * kChunk >= T) return;
   if (chunk == 0) init_cuts(a, unit, T);
   __shared__ double2 sums;
@@ -274,7 +274,7 @@ __global__ __launch_bounds__(kBlock) void chunk_total_kernel(MsArgs a, const flo
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = seq_len(a.d, a.seq_lens, b);
   if (chunk * kChunk >= T) return;
   if (chunk == 0) init_cuts(a, unit, T);
   const float* m = m_all + (int64_t)unit * a.d.t_stride;
@@ -305,7 +305,7 @@ __global__ __launch_bounds__(kBlock) void segment_scan_kernel(MsArgs a, const fl
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = seq_len(a.d, a.seq_lens, b);
   if (chunk * kChunk >= T) return;
   const float* m = m_all + (int64_t)unit * a.d.t_stride;
   __shared__ double2 sums;
@@ -347,7 +347,7 @@ __global__ void segment_finalize_kernel(MsArgs a, float* seg_mass_all) {
   const int unit = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = seq_len(a.d, a.seq_lens, b);
   const int nch = (T + kChunk - 1) / kChunk;
   double total = 0.0;
   for (int c = 0; c < nch; ++c) total += a.mpart[(int64_t)unit * a.n_chunks + c];
@@ -371,7 +371,7 @@ __global__ __launch_bounds__(64) void resegment_kernel(MsArgs a) {
   const int unit = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = seq_len(a.d, a.seq_lens, b);
   int32_t* bounds = a.bounds + (int64_t)unit * (a.S + 1);
   if (threadIdx.x == 0) {
     int n = 0, start = 0;

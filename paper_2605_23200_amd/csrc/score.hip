@@ -4,19 +4,21 @@
 // the matrix cores (32x32 MFMA tiles, token rows x query columns).  The row
 // softmax needs every row's normaliser before a column can be finished, so the
 // work is two sweeps over K:
-//   sweep 1  per 1024-token chunk, per query: running (max, sum of exp) in the
+//   sweep 1  per chunk of tokens, per query: running (max, sum of exp) in the
 //            log2 domain, lane-local, merged per chunk          -> part_stats
+//            (with the expected-attention scorers also the moment score -> g)
 //   reduce   chunks merged in a fixed order                     -> (M_n, weights)
 //   sweep 2  tiles recomputed, exp2(s - M_n) weighted by 1/(N Z_n) and summed
 //            over the queries of each token                     -> u (and g)
-// The score matrix itself never reaches memory.
+// The score matrix itself never reaches memory.  The key-diversity and the
+// value-weighted scorers add streaming kernels of their own at the end of the file.
 #include "score_tile.h"
 
 namespace ams {
 namespace {
 
 // ---------------------------------------------------------------------------------------------
-// Both sweeps walk a 1024-token chunk in 32-token blocks per wave.  The keys of the next block are
+// Both sweeps walk a chunk of kScoreChunk tokens in 32-token blocks per wave.  The keys of the next block are
 // requested before the current block is multiplied (two register buffers, used alternately), and
 // the query columns are processed in groups of kGroup<NB> blocks of 32 so that only that many
 // accumulator tiles are live at a time: more bytes in flight per wave at the same occupancy.
@@ -57,7 +59,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T_all = a.seq_lens[b], t_end = causal_t_end(a, T_all);
+  const int T_all = seq_len(a.d, a.seq_lens, b), t_end = causal_t_end(a, T_all);
   const int T = TAIL ? T_all : t_end;
   const int c0 = TAIL ? t_end : chunk * kScoreChunk;
   if (c0 >= T) return;
@@ -187,7 +189,7 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
   const int unit = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = seq_len(a.d, a.seq_lens, b);
   const int nch = (causal_t_end(a, T) + kScoreChunk - 1) / kScoreChunk + (a.causal ? 1 : 0);
   const int parts = kReduceThreads / a.n_pad;
   const int n = threadIdx.x % a.n_pad, part = threadIdx.x / a.n_pad;
@@ -265,7 +267,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   const int unit = gridDim.y - 1 - blockIdx.y, chunk = TAIL ? 0 : gridDim.x - 1 - blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T_all = a.seq_lens[b], t_end = causal_t_end(a, T_all);
+  const int T_all = seq_len(a.d, a.seq_lens, b), t_end = causal_t_end(a, T_all);
   const int T = TAIL ? T_all : t_end;
   const int c0 = TAIL ? t_end : chunk * kScoreChunk;
   if (c0 >= T) return;
@@ -387,7 +389,7 @@ __global__ __launch_bounds__(kThreads) void keysum_kernel(ScoreArgs a, double* k
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = seq_len(a.d, a.seq_lens, b);
   const int c0 = chunk * kScoreChunk;
   if (c0 >= T) return;
   const int col = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
@@ -423,7 +425,7 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = seq_len(a.d, a.seq_lens, b);
   const int c0 = chunk * kScoreChunk;
   if (c0 >= T) return;
   const int nch = (T + kScoreChunk - 1) / kScoreChunk;
@@ -485,7 +487,7 @@ __global__ __launch_bounds__(kThreads) void esoftmax_part_kernel(ScoreArgs a, do
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = seq_len(a.d, a.seq_lens, b);
   const int c0 = chunk * kScoreChunk;
   if (c0 >= T) return;
   const float* e = a.g + (int64_t)unit * a.d.t_stride;
@@ -531,7 +533,7 @@ __global__ __launch_bounds__(kThreads) void vweight_kernel(ScoreArgs a, KvDev v,
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
-  const int T = a.seq_lens[b];
+  const int T = seq_len(a.d, a.seq_lens, b);
   const int c0 = chunk * kScoreChunk;
   if (c0 >= T) return;
   if (threadIdx.x == 0) {  // chunk statistics merged in index order

@@ -86,7 +86,7 @@ __device__ __forceinline__ TileId decode_tile(const FusedArgs& a, int tile, int 
   t.h = r2 / tiles_b;
   t.j = r2 - t.h * tiles_b;
   t.unit = (t.l * a.s.d.B + t.b) * a.s.d.H + t.h;
-  t.T = a.s.seq_lens[t.b];
+  t.T = seq_len(a.s.d, a.s.seq_lens, t.b);
   return t;
 }
 
@@ -101,7 +101,7 @@ __global__ void fused_init_kernel(FusedArgs a, int32_t* tiles_before_out) {
     int acc = 0;
     for (int b = 0; b < a.s.d.B; ++b) {
       tiles_before_out[b] = acc;
-      acc += (a.s.seq_lens[b] + kTileTok - 1) / kTileTok;
+      acc += (seq_len(a.s.d, a.s.seq_lens, b) + kTileTok - 1) / kTileTok;
     }
     tiles_before_out[a.s.d.B] = acc;
   }

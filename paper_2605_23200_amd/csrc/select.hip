@@ -98,7 +98,7 @@ __device__ __forceinline__ int quota_prologue(const Dims& d, const int32_t* seq_
   const int unit = blockIdx.x, nthr = blockDim.x;
   int l, b, h;
   unit_coords(d, unit, l, b, h);
-  const int T = seq_lens[b];
+  const int T = seq_len(d, seq_lens, b);
   float* mass = seg_mass_all + (int64_t)unit * S;
   if (cpre_all) {
     const int nch = (T + kChunk - 1) / kChunk;
@@ -554,7 +554,7 @@ __global__ __launch_bounds__(kFinBlock) void finalize_kernel(Dims d, const int32
   const int unit = blockIdx.x;
   int l, b, h;
   unit_coords(d, unit, l, b, h);
-  const int T = seq_lens[b];
+  const int T = seq_len(d, seq_lens, b);
   const int kept = min(budget, T);
   const int sinks = min(n_sink, kept);
   const int last = min(n_last, kept - sinks);

@@ -453,3 +453,33 @@ def test_compact_paged(oracle):
         j = np.arange(n_kept[i])
         slots = dst[b, j // 16].astype(np.int64) * 16 + j % 16
         np.testing.assert_array_equal(to_host(Kq_d, np.uint16)[l, slots, h], host["K"][l, b, h, idx[i, :n_kept[i]]])
+
+
+def test_lengths_and_indices_out_of_range_stay_inside_the_buffers(oracle):
+    """A length above t_max is read as t_max and the compaction skips indices outside [0, t_max):
+    the kernels clamp, so wrong arguments give wrong rows, never accesses outside the buffers."""
+    w = _workload("bf16", 2, 8, 1000)
+    host = inputs.dense_cache(w, n_threads=2)
+    p = params_for(w)
+    ws = workspace(p)
+    K, V, Q = to_dev(host["K"]), to_dev(host["V"]), to_dev(host["Q"])
+    u_ok = torch.zeros((p.units, w.T), device=DEV)
+    u_big = torch.zeros_like(u_ok)
+    B.ams_score(p, B.dense_view(K, None), to_dev(np.array([w.T], np.int32)), Q, u_ok, u_ok, ws)
+    B.ams_score(p, B.dense_view(K, None), to_dev(np.array([w.T + 12345], np.int32)), Q, u_big, u_big, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(u_ok, u_big)
+    budget = w.budget
+    idx = np.full((p.units, budget), -1, np.int32)
+    idx[:, :4] = [5, w.T + 7, -3, 9]
+    n_kept = np.full(p.units, budget + 50, np.int32)                   # above the budget: clamped
+    Kd = torch.full((w.L, w.B, w.H, budget, w.D), 77, dtype=K.dtype, device=DEV)
+    Vd = torch.full_like(Kd, 77)
+    B.ams_compact(p, B.dense_view(K, V), to_dev(idx), to_dev(n_kept), B.dense_view(Kd, Vd))
+    torch.cuda.synchronize()
+    Kd_h = to_host(Kd, np.uint16).reshape(p.units, budget, w.D)
+    Kh = host["K"].reshape(p.units, w.T, w.D)
+    for i in range(p.units):
+        np.testing.assert_array_equal(Kd_h[i, 0], Kh[i, 5])
+        np.testing.assert_array_equal(Kd_h[i, 3], Kh[i, 9])
+        assert (Kd_h[i, 1] == 77).all() and (Kd_h[i, 2] == 77).all() and (Kd_h[i, 4:] == 77).all()
