@@ -38,8 +38,8 @@ def kernel_bytes(label, w):
         "score_stats": T * D * e,                       # K stream
         "score_usage": T * D * e + 4 * T,               # K stream + u
         "score_reduce": 0,
-        "ema": 4 * T * 4,                               # u, credit in; credit, m_used out
-        "segment": 4 * T,                               # m_used in
+        "mass_ema": 4 * T * 4,                          # u, credit in; credit, m_used out
+        "segment_scan": 4 * T,                          # m_used in
         "quota": 0,
         "select": 4 * T + 4 * Bd,                       # g in, idx out
         "compact": 4 * Bd * D * e + 4 * Bd * 3,         # K,V rows in + out, idx, credit gather
@@ -130,9 +130,40 @@ def main():
     for label, ms in marks:
         per.setdefault(label, []).append(ms)
     kern = {k: sum(v) / len(v) for k, v in per.items()}
+    # one figure per step of that region: the sum of its kernels' intervals
+    n_prof = min(len(v) for v in per.values())
+    step_sums = sorted(sum(per[k][i] for k in per) for i in range(n_prof))
     dom = max(kern, key=kern.get)
     dom_bytes = kernel_bytes(dom, w)
     achieved = dom_bytes / (kern[dom] * 1e-3) / 1e9
+
+    # the ceiling a plain device copy reaches in the same run (1 GiB read + 1 GiB written)
+    src_c = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")
+    dst_c = torch.empty_like(src_c)
+    dst_c.copy_(src_c)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst_c.copy_(src_c)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * src_c.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src_c, dst_c
+
+    # the literal trajectory's later events are short (kept rows + appended tokens): launch-bound
+    small_ms = None
+    if w.n_append > 0:
+        ws_small = w.scaled(T=w.budget + w.n_append, n_spans=max(1, w.n_spans * (w.budget + w.n_append) // w.T))
+        job_s = Job(ws_small, inputs.dense_cache(ws_small, n_threads=16), scorer=scorer_id)
+        for _ in range(5):
+            job_s.step(stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(50):
+            job_s.step(stream)
+        torch.cuda.synchronize()
+        small_ms = (time.perf_counter() - t0) / 50 * 1e3
+        del job_s
 
     if args.calibrate_copy:
         src_c = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
@@ -170,6 +201,13 @@ def main():
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "kernel_ms": round(kern[dom], 4), "algorithmic_bytes_per_launch": dom_bytes},
         "kernel_ms": {k: round(v, 4) for k, v in kern.items()},
+        "stage_GBps": {k: round(kernel_bytes(k, w) / (v * 1e-3) / 1e9, 1) for k, v in kern.items()
+                       if kernel_bytes(k, w) > 0},
+        "step_ms_median": round(step_sums[len(step_sums) // 2], 4), "step_ms_min": round(step_sums[0], 4),
+        "copy_GBps": round(copy_gbps, 1),
+        "small_event": None if small_ms is None else
+        {"T": w.budget + w.n_append, "ms_per_step": round(small_ms, 4),
+         "note": "a later event of the literal trajectory: kept rows + appended tokens"},
         "setup_s": round(setup_s, 1),
     }
 
@@ -193,9 +231,20 @@ def main():
                                      pool_kernel=w.pool_kernel)
         cpu_s = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(n_units / cpu_s / w.units, 5), "unit": "steps/s", "cores": used,
-                               "kind": "oracle",
+                               "kind": "oracle", "host_cpus": os.cpu_count(),
                                "sample": f"first {n_units} of {w.units} units of the same workload, one event, "
                                          f"{cpu_s:.1f} s wall, scaled linearly to a whole step"}
+        # one core on the small fp32 configuration, for scale
+        w0 = inputs.CONFIGS[0]
+        h0 = inputs.dense_cache(w0, n_threads=4)
+        ids0 = inputs.unit_ids(w0)
+        Q0 = np.ascontiguousarray(np.stack([inputs.as_f32(h0["Q"][l, b, h * w0.G:(h + 1) * w0.G]).reshape(-1, w0.D)
+                                            for l, b, h in ids0]))
+        K0 = np.ascontiguousarray(np.stack([inputs.as_f32(h0["K"][l, b, h]) for l, b, h in ids0]))
+        t0 = time.perf_counter()
+        O.compress_many(Q0, K0, np.zeros((w0.units, w0.T), np.float32), G=w0.G, W=w0.W, budget=w0.budget, S=w0.S,
+                        lam=w0.lam, beta=w0.beta, eps=w0.eps, q_min=w0.q_min, n_threads=1)
+        out["cpu_baseline"]["config0_one_core_steps_per_s"] = round(1.0 / (time.perf_counter() - t0), 3)
     print(json.dumps(out))
 
 

@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/ams.h: argument checks, workspace carving and the
 // order of the launches.  Nothing here touches device memory or waits for the stream.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "ams_internal.h"
@@ -23,10 +24,27 @@ static int padded_queries(int n, bool bf16) {
   return 0;
 }
 
+// Tokens per workgroup of the scoring sweeps: as many as possible (the query window is loaded once per
+// workgroup), but few enough that the launch has a couple of thousand workgroups to fill 256 CUs.
+static int pick_score_chunk(size_t units, int t_max) {
+  static const int forced = [] {
+    const char* e = getenv("AMS_SCORE_CHUNK_TOKENS");  // tuning aid; a multiple of 256 up to kScoreChunk
+    const int v = e ? atoi(e) : 0;
+    return (v >= 256 && v <= kScoreChunk && v % 256 == 0) ? v : 0;
+  }();
+  if (forced) return forced;
+  // measured on 256 units: 2048 tokens are best from 16k positions on, 1024 below (2176 positions:
+  // 0.208 ms per step against 0.229); 512 and 256 lose to the per-workgroup load of the query window
+  int chunk = kScoreChunk;
+  if (chunk > 1024 && units * (size_t)div_up(t_max, chunk) < 2048) chunk = 1024;
+  return chunk;
+}
+
 WsLayout ws_layout(const ams_params* p) {
   WsLayout w;
   const size_t units = (size_t)p->n_layers * p->batch * p->n_kv_heads;
-  w.n_chunks = div_up(p->t_max, kScoreChunk);
+  w.score_chunk = pick_score_chunk(units, p->t_max);
+  w.n_chunks = div_up(p->t_max, w.score_chunk);
   w.n_pad = padded_queries(p->group * p->window, p->kv_dtype == AMS_BF16);
   const size_t vec = align256(units * (size_t)p->t_stride * sizeof(float));
   size_t o = 0;

@@ -55,7 +55,7 @@ __device__ __forceinline__ int seq_len(const Dims& d, const int32_t* seq_lens, i
 #ifndef AMS_SCORE_CHUNK
 #define AMS_SCORE_CHUNK 2048
 #endif
-constexpr int kScoreChunk = AMS_SCORE_CHUNK;  // tokens per workgroup of the scoring kernels
+constexpr int kScoreChunk = AMS_SCORE_CHUNK;  // most tokens per workgroup of the scoring kernels
 constexpr int kChunk = 4096;       // positions per workgroup of the mass / prefix kernels
 
 // Segments the thresholds k*delta (every k >= 1 with k*delta < 1) cut the unit interval into.
@@ -71,6 +71,7 @@ inline int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 struct WsLayout {
   size_t part_stats, fin_stats, u, g, m_used, bounds, seg_mass, quota, kbar, fused, vc_part, mpart, cpre, flags, csum, total;
   int n_chunks, n_pad;
+  int score_chunk;  // tokens per workgroup of the scoring kernels for these parameters
   int n_chunks4k;  // chunks of kChunk positions per unit
   int n_words;     // 32-position words of the kept-set bitmap per unit
 };

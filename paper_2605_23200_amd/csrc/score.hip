@@ -18,7 +18,8 @@ namespace ams {
 namespace {
 
 // ---------------------------------------------------------------------------------------------
-// Both sweeps walk a chunk of kScoreChunk tokens in 32-token blocks per wave.  The keys of the next block are
+// Both sweeps walk a chunk of tokens (256 .. kScoreChunk, chosen on the host so that short caches
+// still give the chip enough workgroups) in 32-token blocks per wave.  The keys of the next block are
 // requested before the current block is multiplied (two register buffers, used alternately), and
 // the query columns are processed in groups of kGroup<NB> blocks of 32 so that only that many
 // accumulator tiles are live at a time: more bytes in flight per wave at the same occupancy.
@@ -53,7 +54,7 @@ __device__ __forceinline__ int causal_t_end(const ScoreArgs& a, int T) {
 // subtraction of the squares harmless).  Raw logits are used: the causal mask does not apply.
 template <bool BF16, int NB, bool TAIL, bool MOMENTS>
 __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE_MIN_WAVES : 2) void score_stats_kernel(ScoreArgs a) {
-  constexpr int NG = kGroup<NB>, QS = Tr<BF16>::kQStride, NBLK = kScoreChunk / 128;
+  constexpr int NG = kGroup<NB>, QS = Tr<BF16>::kQStride;
   extern __shared__ __align__(16) char qlds[];
   __shared__ float2 xch[4][NB * 32];
   const int unit = blockIdx.y, chunk = blockIdx.x;
@@ -61,7 +62,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
   unit_coords(a.d, unit, l, b, h);
   const int T_all = seq_len(a.d, a.seq_lens, b), t_end = causal_t_end(a, T_all);
   const int T = TAIL ? T_all : t_end;
-  const int c0 = TAIL ? t_end : chunk * kScoreChunk;
+  const int c0 = TAIL ? t_end : chunk * a.chunk;
   if (c0 >= T) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
   const int t_vis0 = T_all - a.d.W;  // newest key visible to the oldest query of the window
@@ -146,14 +147,14 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
         g_row[t] = (r_tok + d_mean) * a.inv_sqrt_d + 0.5f * (d_sq - d_mean * d_mean) * (a.inv_sqrt_d * a.inv_sqrt_d);
     }
   };
+  // this wave's blocks: every fourth block of 32 tokens up to the end of the chunk (or of the cache)
+  const int t_lim = min(T, c0 + a.chunk);
 #pragma unroll 1
-  for (int blk = 0; blk < NBLK; blk += 2) {
-    const int t0 = c0 + (blk * 4 + wave) * 32;
-    if (t0 >= T) break;
-    if (t0 + 128 < T) load_a<BF16>(a, l, b, h, t0 + 128, T, lane, av1);
+  for (int t0 = c0 + wave * 32; t0 < t_lim; t0 += 256) {
+    if (t0 + 128 < t_lim) load_a<BF16>(a, l, b, h, t0 + 128, T, lane, av1);
     block(av0, t0);
-    if (t0 + 128 >= T) break;
-    if (blk + 2 < NBLK && t0 + 256 < T) load_a<BF16>(a, l, b, h, t0 + 256, T, lane, av0);
+    if (t0 + 128 >= t_lim) break;
+    if (t0 + 256 < t_lim) load_a<BF16>(a, l, b, h, t0 + 256, T, lane, av0);
     block(av1, t0 + 128);
   }
 #pragma unroll
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
 #pragma unroll
     for (int w = 0; w < 4; ++w) Z += xch[w][n].y * __builtin_amdgcn_exp2f(xch[w][n].x - M);
     // the tail's entry follows those of the chunks
-    const int slot = TAIL ? (t_end + kScoreChunk - 1) / kScoreChunk : chunk;
+    const int slot = TAIL ? (t_end + a.chunk - 1) / a.chunk : chunk;
     a.part[((int64_t)unit * (a.n_chunks + 1) + slot) * a.n_pad + n] = make_float2(M, Z);
   }
 }
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T = seq_len(a.d, a.seq_lens, b);
-  const int nch = (causal_t_end(a, T) + kScoreChunk - 1) / kScoreChunk + (a.causal ? 1 : 0);
+  const int nch = (causal_t_end(a, T) + a.chunk - 1) / a.chunk + (a.causal ? 1 : 0);
   const int parts = kReduceThreads / a.n_pad;
   const int n = threadIdx.x % a.n_pad, part = threadIdx.x / a.n_pad;
   if (part < parts) {
@@ -260,7 +261,7 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
 template <bool BF16, int NB, int MODE, bool TAIL>
 __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES : 2) void score_usage_kernel(ScoreArgs a) {
   constexpr int NG = kGroup<NB>;
-  constexpr int QS = Tr<BF16>::kQStride, NBLK = kScoreChunk / 128;
+  constexpr int QS = Tr<BF16>::kQStride;
   extern __shared__ __align__(16) char qlds[];
   // the second sweep walks the cache backwards: what the first sweep read last is still in the
   // memory-side cache (about a tenth of the keys at the headline size)
@@ -269,7 +270,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   unit_coords(a.d, unit, l, b, h);
   const int T_all = seq_len(a.d, a.seq_lens, b), t_end = causal_t_end(a, T_all);
   const int T = TAIL ? T_all : t_end;
-  const int c0 = TAIL ? t_end : chunk * kScoreChunk;
+  const int c0 = TAIL ? t_end : chunk * a.chunk;
   if (c0 >= T) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5, c = lane & 31;
   const int t_vis0 = T_all - a.d.W;  // newest key visible to the oldest query of the window
@@ -334,14 +335,14 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
       v_part += fmaxf(ru, 0.f) + a.eps;
     }
   };
+  // this wave's blocks: every fourth block of 32 tokens up to the end of the chunk (or of the cache)
+  const int t_lim = min(T, c0 + a.chunk);
 #pragma unroll 1
-  for (int blk = 0; blk < NBLK; blk += 2) {
-    const int t0 = c0 + (blk * 4 + wave) * 32;
-    if (t0 >= T) break;
-    if (t0 + 128 < T) load_a<BF16>(a, l, b, h, t0 + 128, T, lane, av1);
+  for (int t0 = c0 + wave * 32; t0 < t_lim; t0 += 256) {
+    if (t0 + 128 < t_lim) load_a<BF16>(a, l, b, h, t0 + 128, T, lane, av1);
     block(av0, t0);
-    if (t0 + 128 >= T) break;
-    if (blk + 2 < NBLK && t0 + 256 < T) load_a<BF16>(a, l, b, h, t0 + 256, T, lane, av0);
+    if (t0 + 128 >= t_lim) break;
+    if (t0 + 256 < t_lim) load_a<BF16>(a, l, b, h, t0 + 256, T, lane, av0);
     block(av1, t0 + 128);
   }
   if (a.vc_part) {  // chunk sums of max(u,0)+eps in a fixed order: lanes, then waves
@@ -390,13 +391,13 @@ __global__ __launch_bounds__(kThreads) void keysum_kernel(ScoreArgs a, double* k
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T = seq_len(a.d, a.seq_lens, b);
-  const int c0 = chunk * kScoreChunk;
+  const int c0 = chunk * a.chunk;
   if (c0 >= T) return;
   const int col = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
   double s[EPC];
 #pragma unroll
   for (int e = 0; e < EPC; ++e) s[e] = 0.0;
-  for (int t = c0 + r0; t < min(T, c0 + kScoreChunk); t += RPI) {
+  for (int t = c0 + r0; t < min(T, c0 + a.chunk); t += RPI) {
     const uint4 v = *(const uint4*)(kv_row(a.k, l, b, h, t) + col * 16);
     float x[8];
     int n;
@@ -426,9 +427,9 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T = seq_len(a.d, a.seq_lens, b);
-  const int c0 = chunk * kScoreChunk;
+  const int c0 = chunk * a.chunk;
   if (c0 >= T) return;
-  const int nch = (T + kScoreChunk - 1) / kScoreChunk;
+  const int nch = (T + a.chunk - 1) / a.chunk;
   if (threadIdx.x < a.d.D) {
     double t = 0.0;
     for (int c = 0; c < nch; ++c) t += ksum[((int64_t)unit * a.n_chunks + c) * a.d.D + threadIdx.x];
@@ -446,7 +447,7 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   float kb[EPC];  // this lane's channels of the mean key
 #pragma unroll
   for (int e = 0; e < EPC; ++e) kb[e] = (float)kbar[col * EPC + e];
-  for (int tb = c0; tb < min(T, c0 + kScoreChunk); tb += RPI) {
+  for (int tb = c0; tb < min(T, c0 + a.chunk); tb += RPI) {
     const int t = tb + r0;
     // a row's 128 products are summed in fp32 (8 per lane, then 16 or 32 lanes); the ratio is formed in double
     float dot = 0.f, nk = 0.f;
@@ -471,7 +472,7 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   }
   __syncthreads();
   // one token per thread for the ratio, so that every lane works
-  for (int t = c0 + threadIdx.x; t < min(T, c0 + kScoreChunk); t += kThreads) {
+  for (int t = c0 + threadIdx.x; t < min(T, c0 + a.chunk); t += kThreads) {
     const float2 r = row_sums[t - c0];
     const double den = sqrt((double)r.y) * kbar_norm;
     g_row[t] = den > 0.0 ? (float)(-(double)r.x / den) : 0.f;
@@ -488,10 +489,10 @@ __global__ __launch_bounds__(kThreads) void esoftmax_part_kernel(ScoreArgs a, do
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T = seq_len(a.d, a.seq_lens, b);
-  const int c0 = chunk * kScoreChunk;
+  const int c0 = chunk * a.chunk;
   if (c0 >= T) return;
   const float* e = a.g + (int64_t)unit * a.d.t_stride;
-  const int end = min(T, c0 + kScoreChunk);
+  const int end = min(T, c0 + a.chunk);
   double m = -INFINITY, z = 0.0;
   for (int t = c0 + threadIdx.x; t < end; t += kThreads) {
     const double x = (double)e[t];
@@ -534,10 +535,10 @@ __global__ __launch_bounds__(kThreads) void vweight_kernel(ScoreArgs a, KvDev v,
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T = seq_len(a.d, a.seq_lens, b);
-  const int c0 = chunk * kScoreChunk;
+  const int c0 = chunk * a.chunk;
   if (c0 >= T) return;
   if (threadIdx.x == 0) {  // chunk statistics merged in index order
-    const int nch = (T + kScoreChunk - 1) / kScoreChunk;
+    const int nch = (T + a.chunk - 1) / a.chunk;
     double M = -INFINITY;
     for (int c = 0; c < nch; ++c) M = fmax(M, part[(int64_t)unit * a.n_chunks + c].x);
     double Z = 0.0;
@@ -551,7 +552,7 @@ __global__ __launch_bounds__(kThreads) void vweight_kernel(ScoreArgs a, KvDev v,
   const double M = stat.x, inv_z = 1.0 / stat.y, eps = (double)eps_f;
   const int col = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
   float* g_row = a.g + (int64_t)unit * a.d.t_stride;
-  for (int tb = c0; tb < min(T, c0 + kScoreChunk); tb += RPI) {
+  for (int tb = c0; tb < min(T, c0 + a.chunk); tb += RPI) {
     const int t = tb + r0;
     float n2 = 0.f;  // 128 squares summed in fp32, the rest in double
     if (t < T) {
@@ -569,7 +570,7 @@ __global__ __launch_bounds__(kThreads) void vweight_kernel(ScoreArgs a, KvDev v,
   }
   __syncthreads();
   // one token per thread for the exponential, so that every lane works
-  for (int t = c0 + threadIdx.x; t < min(T, c0 + kScoreChunk); t += kThreads)
+  for (int t = c0 + threadIdx.x; t < min(T, c0 + a.chunk); t += kThreads)
     g_row[t] = (float)((exp((double)g_row[t] - M) * inv_z + eps) * sqrt((double)norm2[t - c0]));
 }
 
@@ -668,6 +669,7 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
   a.fin = (float4*)(ws + wl.fin_stats);
   a.u = u;
   a.n_chunks = wl.n_chunks;
+  a.chunk = wl.score_chunk;
   a.n_pad = wl.n_pad;
   a.inv_sqrt_d = (float)(1.0 / sqrt((double)d.D));
   a.c2 = (float)(1.4426950408889634 / sqrt((double)d.D));
@@ -690,7 +692,7 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
   if (!oneread) {
     e = bf16 ? run_by_nb<true>(a, nb, mode, s) : run_by_nb<false>(a, nb, mode, s);
     vc_stride = wl.n_chunks;
-    vc_tokens = kScoreChunk;
+    vc_tokens = wl.score_chunk;
   }
   if (e != hipSuccess) return e;
   if (vc) {

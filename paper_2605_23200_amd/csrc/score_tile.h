@@ -27,6 +27,7 @@ struct ScoreArgs {
   float* u;
   float* g;
   int n_chunks, n_pad;
+  int chunk;         // tokens per workgroup: a multiple of 256, at most kScoreChunk
   float c2;          // log2(e) / sqrt(D)
   float inv_sqrt_d;  // 1 / sqrt(D)
   // optional by-products for Eq. (1) and the EMA (NULL: not wanted): per chunk the sum of
