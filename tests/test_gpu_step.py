@@ -175,6 +175,37 @@ def test_config0_trajectory(oracle):
     assert agree[0] >= 7          # first event: same inputs, only fp32-vs-fp64 rounding can flip a choice
 
 
+def test_config1_literal_trajectory(oracle):
+    """Config 1's trajectory as stated (first event at T = 32768 -> 2048, later events at 2048 + 128 appended
+    tokens), on two layers: every event against the oracle, credit carried through the compaction."""
+    w = inputs.CONFIGS[1].scaled(L=2)
+    host = inputs.dense_cache(w, n_threads=16)
+    ids = unit_list(w)
+    credit = np.zeros((w.units, w.T), np.float32)
+    for e in range(3):
+        job = Job(w, host, credit=credit)
+        job.step()
+        torch.cuda.synchronize()
+        check_properties_all_units(job)
+        check_units(oracle, job, host, credit, [0, 5, w.units - 1] if e == 0 else list(range(w.units)))
+        Ko, Vo = _kv_out_host(job, host["K"].dtype)
+        cd = to_host(job.credit_dst)
+        T_new = w.budget + w.n_append
+        K2 = np.zeros((w.L, w.B, w.H, T_new, w.D), host["K"].dtype)
+        V2 = np.zeros_like(K2)
+        credit = np.zeros((w.units, T_new), np.float32)
+        Q2 = np.zeros_like(host["Q"])
+        for i, (l, b, h) in enumerate(ids):
+            fk, fv = inputs.unit_fresh_rows(w, l, b, h, e + 1, w.n_append)
+            K2[l, b, h] = np.concatenate([Ko[i], fk])
+            V2[l, b, h] = np.concatenate([Vo[i], fv])
+            credit[i, :w.budget] = cd[i]
+            Q2[l, b, h * w.G:(h + 1) * w.G] = inputs.unit_q(w, l, b, h, e + 1)
+        host = dict(Q=Q2, K=K2, V=V2, seq_lens=np.full(w.B, T_new, np.int32))
+        w = w.scaled(T=T_new)
+        assert credit.max() > 0                         # the carried credit is what the next event's EMA starts from
+
+
 @pytest.fixture(scope="module")
 def cfg1_job():
     w = inputs.CONFIGS[1]
