@@ -72,7 +72,7 @@ typedef enum {
 typedef struct {
   int32_t n_layers, batch, n_kv_heads;
   int32_t group;      /* G: query heads per KV head                                        */
-  int32_t head_dim;   /* D: 128                                                            */
+  int32_t head_dim;   /* D: 64 or 128                                                      */
   int32_t window;     /* W: recent decoding queries per query head (Sec. 3.2)             */
   int32_t kv_dtype;   /* ams_dtype of K, V and Q                                           */
   int32_t t_max;      /* upper bound of every seq_lens[b]; sizes the launches              */

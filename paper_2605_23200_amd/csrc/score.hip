@@ -52,9 +52,9 @@ __device__ __forceinline__ int causal_t_end(const ScoreArgs& a, int T) {
 // statistics, so it is formed here, where few registers are live, from sums of (s - r) and (s - r)^2
 // with r the token's logit against the unit's first query (a reference close to the mean keeps the
 // subtraction of the squares harmless).  Raw logits are used: the causal mask does not apply.
-template <bool BF16, int NB, bool TAIL, bool MOMENTS>
+template <bool BF16, int NB, bool TAIL, bool MOMENTS, int HD>
 __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE_MIN_WAVES : 2) void score_stats_kernel(ScoreArgs a) {
-  constexpr int NG = kGroup<NB>, QS = Tr<BF16>::kQStride;
+  constexpr int NG = kGroup<NB>, QS = Tr<BF16, HD>::kQStride;
   extern __shared__ __align__(16) char qlds[];
   __shared__ float2 xch[4][NB * 32];
   const int unit = blockIdx.y, chunk = blockIdx.x;
@@ -66,9 +66,9 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
   if (c0 >= T) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
   const int t_vis0 = T_all - a.d.W;  // newest key visible to the oldest query of the window
-  uint4 av0[Tr<BF16>::kAVecs], av1[Tr<BF16>::kAVecs];
-  if (c0 + wave * 32 < T) load_a<BF16>(a, l, b, h, c0 + wave * 32, T, lane, av0);
-  load_q<BF16, NB>(a, l, b, h, qlds);
+  uint4 av0[Tr<BF16, HD>::kAVecs], av1[Tr<BF16, HD>::kAVecs];
+  if (c0 + wave * 32 < T) load_a<BF16, HD>(a, l, b, h, c0 + wave * 32, T, lane, av0);
+  load_q<BF16, NB, HD>(a, l, b, h, qlds);
   __syncthreads();
   float m[NB], z[NB];
 #pragma unroll
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
   }
   const float c2 = a.c2;
   float* g_row = MOMENTS ? a.g + (int64_t)unit * a.d.t_stride : nullptr;
-  auto block = [&](const uint4 (&av)[Tr<BF16>::kAVecs], int t0) __attribute__((always_inline)) {
+  auto block = [&](const uint4 (&av)[Tr<BF16, HD>::kAVecs], int t0) __attribute__((always_inline)) {
     const bool ragged = t0 + 32 > T;
     // the query fragments are re-read from LDS for every block: keeping them in registers across
     // blocks would cost more registers than the reads cost time, so their address is made opaque
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
 #pragma unroll
     for (int g0 = 0; g0 < NB; g0 += NG) {
       floatx16 acc[NG];
-      tile_mma<BF16, NG>(av, qlds + qoff + g0 * 32 * QS, lane, acc);
+      tile_mma<BF16, NG, HD>(av, qlds + qoff + g0 * 32 * QS, lane, acc);
       if (MOMENTS) {
         if (g0 == 0) {
 #pragma unroll
@@ -151,10 +151,10 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
   const int t_lim = min(T, c0 + a.chunk);
 #pragma unroll 1
   for (int t0 = c0 + wave * 32; t0 < t_lim; t0 += 256) {
-    if (t0 + 128 < t_lim) load_a<BF16>(a, l, b, h, t0 + 128, T, lane, av1);
+    if (t0 + 128 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 128, T, lane, av1);
     block(av0, t0);
     if (t0 + 128 >= t_lim) break;
-    if (t0 + 256 < t_lim) load_a<BF16>(a, l, b, h, t0 + 256, T, lane, av0);
+    if (t0 + 256 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 256, T, lane, av0);
     block(av1, t0 + 128);
   }
 #pragma unroll
@@ -258,10 +258,10 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
 // ---------------------------------------------------------------------------------------------
 // TAIL (causal window, blocks from t_end on): a (query, key) pair the mask hides adds nothing, and
 // every observation a key is missing counts as the largest share it got.
-template <bool BF16, int NB, int MODE, bool TAIL>
+template <bool BF16, int NB, int MODE, bool TAIL, int HD>
 __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES : 2) void score_usage_kernel(ScoreArgs a) {
   constexpr int NG = kGroup<NB>;
-  constexpr int QS = Tr<BF16>::kQStride;
+  constexpr int QS = Tr<BF16, HD>::kQStride;
   extern __shared__ __align__(16) char qlds[];
   // the second sweep walks the cache backwards: what the first sweep read last is still in the
   // memory-side cache (about a tenth of the keys at the headline size)
@@ -274,9 +274,9 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   if (c0 >= T) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5, c = lane & 31;
   const int t_vis0 = T_all - a.d.W;  // newest key visible to the oldest query of the window
-  uint4 av0[Tr<BF16>::kAVecs], av1[Tr<BF16>::kAVecs];
-  if (c0 + wave * 32 < T) load_a<BF16>(a, l, b, h, c0 + wave * 32, T, lane, av0);
-  load_q<BF16, NB>(a, l, b, h, qlds);
+  uint4 av0[Tr<BF16, HD>::kAVecs], av1[Tr<BF16, HD>::kAVecs];
+  if (c0 + wave * 32 < T) load_a<BF16, HD>(a, l, b, h, c0 + wave * 32, T, lane, av0);
+  load_q<BF16, NB, HD>(a, l, b, h, qlds);
   __syncthreads();
   float4 f[NB];
 #pragma unroll
@@ -285,7 +285,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   float* g_row = a.g ? a.g + (int64_t)unit * a.d.t_stride : nullptr;
   const float c2 = a.c2;
   float v_part = 0.f;  // this lane's share of sum(max(u,0)+eps): at most 8 terms
-  auto block = [&](const uint4 (&av)[Tr<BF16>::kAVecs], int t0) __attribute__((always_inline)) {
+  auto block = [&](const uint4 (&av)[Tr<BF16, HD>::kAVecs], int t0) __attribute__((always_inline)) {
     float pu[16], pg[16], pm[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) pu[i] = pg[i] = pm[i] = 0.f;
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
 #pragma unroll
     for (int g0 = 0; g0 < NB; g0 += NG) {
       floatx16 acc[NG];
-      tile_mma<BF16, NG>(av, qlds + qoff + g0 * 32 * QS, lane, acc);
+      tile_mma<BF16, NG, HD>(av, qlds + qoff + g0 * 32 * QS, lane, acc);
 #pragma unroll
       for (int k = 0; k < NG; ++k) {
         const int nb = g0 + k;
@@ -339,10 +339,10 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   const int t_lim = min(T, c0 + a.chunk);
 #pragma unroll 1
   for (int t0 = c0 + wave * 32; t0 < t_lim; t0 += 256) {
-    if (t0 + 128 < t_lim) load_a<BF16>(a, l, b, h, t0 + 128, T, lane, av1);
+    if (t0 + 128 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 128, T, lane, av1);
     block(av0, t0);
     if (t0 + 128 >= t_lim) break;
-    if (t0 + 256 < t_lim) load_a<BF16>(a, l, b, h, t0 + 256, T, lane, av0);
+    if (t0 + 256 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 256, T, lane, av0);
     block(av1, t0 + 128);
   }
   if (a.vc_part) {  // chunk sums of max(u,0)+eps in a fixed order: lanes, then waves
@@ -383,9 +383,9 @@ __device__ __forceinline__ void widen8(const uint4& v, float (&x)[8], int& n) {
 }
 
 // partial key sums per chunk: ksum[unit][chunk][D] (double)
-template <bool BF16>
+template <bool BF16, int HD>
 __global__ __launch_bounds__(kThreads) void keysum_kernel(ScoreArgs a, double* ksum) {
-  constexpr int CPR = Tr<BF16>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
+  constexpr int CPR = Tr<BF16, HD>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
   __shared__ double sm[kThreads][EPC];
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
@@ -417,9 +417,9 @@ __global__ __launch_bounds__(kThreads) void keysum_kernel(ScoreArgs a, double* k
   }
 }
 
-template <bool BF16>
+template <bool BF16, int HD>
 __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const double* ksum) {
-  constexpr int CPR = Tr<BF16>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
+  constexpr int CPR = Tr<BF16, HD>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
   __shared__ double kbar[128];
   __shared__ double kbar_norm;
   __shared__ float2 row_sums[kScoreChunk];  // per token: k . kbar and k . k
@@ -526,9 +526,9 @@ __global__ __launch_bounds__(kThreads) void esoftmax_part_kernel(ScoreArgs a, do
   }
 }
 
-template <bool BF16>
+template <bool BF16, int HD>
 __global__ __launch_bounds__(kThreads) void vweight_kernel(ScoreArgs a, KvDev v, const double2* part, float eps_f) {
-  constexpr int CPR = Tr<BF16>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
+  constexpr int CPR = Tr<BF16, HD>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
   __shared__ double2 stat;
   __shared__ float norm2[kScoreChunk];  // per token: v . v
   const int unit = blockIdx.y, chunk = blockIdx.x;
@@ -579,45 +579,45 @@ hipError_t set_lds(K kernel, int bytes) {
   return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-template <bool BF16, int NB, bool TAIL>
+template <bool BF16, int NB, bool TAIL, int HD>
 hipError_t launch_stats(const ScoreArgs& a, bool moments, dim3 grid, int lds, hipStream_t s) {
   hipError_t e;
   if (moments) {
-    if ((e = set_lds(score_stats_kernel<BF16, NB, TAIL, true>, lds)) != hipSuccess) return e;
-    hipLaunchKernelGGL((score_stats_kernel<BF16, NB, TAIL, true>), grid, dim3(kThreads), lds, s, a);
+    if ((e = set_lds(score_stats_kernel<BF16, NB, TAIL, true, HD>, lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL((score_stats_kernel<BF16, NB, TAIL, true, HD>), grid, dim3(kThreads), lds, s, a);
   } else {
-    if ((e = set_lds(score_stats_kernel<BF16, NB, TAIL, false>, lds)) != hipSuccess) return e;
-    hipLaunchKernelGGL((score_stats_kernel<BF16, NB, TAIL, false>), grid, dim3(kThreads), lds, s, a);
+    if ((e = set_lds(score_stats_kernel<BF16, NB, TAIL, false, HD>, lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL((score_stats_kernel<BF16, NB, TAIL, false, HD>), grid, dim3(kThreads), lds, s, a);
   }
   return hipGetLastError();
 }
 
-template <bool BF16, int NB, bool TAIL>
+template <bool BF16, int NB, bool TAIL, int HD>
 hipError_t launch_usage(const ScoreArgs& a, int mode, dim3 grid, int lds, hipStream_t s) {
   const dim3 blk(kThreads);
   hipError_t e;
   switch (mode) {
     case MODE_LAST:
-      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_LAST, TAIL>, lds)) != hipSuccess) return e;
-      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_LAST, TAIL>), grid, blk, lds, s, a);
+      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_LAST, TAIL, HD>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_LAST, TAIL, HD>), grid, blk, lds, s, a);
       break;
     default:
-      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_MEAN, TAIL>, lds)) != hipSuccess) return e;
-      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_MEAN, TAIL>), grid, blk, lds, s, a);
+      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_MEAN, TAIL, HD>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_MEAN, TAIL, HD>), grid, blk, lds, s, a);
   }
   return hipGetLastError();
 }
 
-template <bool BF16, int NB>
+template <bool BF16, int NB, int HD>
 hipError_t run_softmax_sweeps(const ScoreArgs& a, int mode, hipStream_t s) {
-  const int lds = NB * 32 * Tr<BF16>::kQStride;
+  const int lds = NB * 32 * Tr<BF16, HD>::kQStride;
   const dim3 grid(a.n_chunks, a.d.units);
   hipError_t e;
   prof_mark("score_stats", s);
-  if ((e = launch_stats<BF16, NB, false>(a, mode == MODE_EXPECTED, grid, lds, s)) != hipSuccess) return e;
+  if ((e = launch_stats<BF16, NB, false, HD>(a, mode == MODE_EXPECTED, grid, lds, s)) != hipSuccess) return e;
   if (a.causal) {
     prof_mark("score_stats_tail", s);
-    if ((e = launch_stats<BF16, NB, true>(a, mode == MODE_EXPECTED, dim3(1, a.d.units), lds, s)) != hipSuccess) return e;
+    if ((e = launch_stats<BF16, NB, true, HD>(a, mode == MODE_EXPECTED, dim3(1, a.d.units), lds, s)) != hipSuccess) return e;
   }
   prof_mark("score_reduce", s);
   hipLaunchKernelGGL(score_reduce_kernel, dim3(a.d.units), dim3(kReduceThreads), 0, s, a);
@@ -625,24 +625,42 @@ hipError_t run_softmax_sweeps(const ScoreArgs& a, int mode, hipStream_t s) {
   ScoreArgs a2 = a;
   if (mode == MODE_EXPECTED) a2.g = nullptr;
   prof_mark("score_usage", s);
-  if ((e = launch_usage<BF16, NB, false>(a2, mode, grid, lds, s)) != hipSuccess) return e;
+  if ((e = launch_usage<BF16, NB, false, HD>(a2, mode, grid, lds, s)) != hipSuccess) return e;
   if (a.causal) {
     prof_mark("score_usage_tail", s);
-    if ((e = launch_usage<BF16, NB, true>(a2, mode, dim3(1, a.d.units), lds, s)) != hipSuccess) return e;
+    if ((e = launch_usage<BF16, NB, true, HD>(a2, mode, dim3(1, a.d.units), lds, s)) != hipSuccess) return e;
   }
   return hipSuccess;
 }
 
-template <bool BF16>
+template <bool BF16, int HD>
 hipError_t run_by_nb(const ScoreArgs& a, int nb, int mode, hipStream_t s) {
-  if (nb <= 1) return run_softmax_sweeps<BF16, 1>(a, mode, s);
-  if (nb <= 2) return run_softmax_sweeps<BF16, 2>(a, mode, s);
-  if (nb <= 4) return run_softmax_sweeps<BF16, 4>(a, mode, s);
+  if (nb <= 1) return run_softmax_sweeps<BF16, 1, HD>(a, mode, s);
+  if (nb <= 2) return run_softmax_sweeps<BF16, 2, HD>(a, mode, s);
+  if (nb <= 4) return run_softmax_sweeps<BF16, 4, HD>(a, mode, s);
   if constexpr (BF16) {
-    if (nb <= 7) return run_softmax_sweeps<BF16, 7>(a, mode, s);
-    if (nb <= 8) return run_softmax_sweeps<BF16, 8>(a, mode, s);
+    if (nb <= 7) return run_softmax_sweeps<BF16, 7, HD>(a, mode, s);
+    if (nb <= 8) return run_softmax_sweeps<BF16, 8, HD>(a, mode, s);
   }
   return hipErrorInvalidValue;
+}
+
+template <bool BF16, int HD>
+hipError_t launch_vweight(const ScoreArgs& a, const KvDev& v, char* ws, const WsLayout& wl, float eps, hipStream_t s) {
+  hipLaunchKernelGGL((vweight_kernel<BF16, HD>), dim3(a.n_chunks, a.d.units), dim3(kThreads), 0, s, a, v,
+                     (const double2*)(ws + wl.kbar), eps);
+  return hipGetLastError();
+}
+
+template <bool BF16, int HD>
+hipError_t launch_keydiff(const ScoreArgs& a, char* ws, const WsLayout& wl, hipStream_t s) {
+  double* ksum = (double*)(ws + wl.kbar);
+  const dim3 grid(a.n_chunks, a.d.units), blk(kThreads);
+  prof_mark("keysum", s);
+  hipLaunchKernelGGL((keysum_kernel<BF16, HD>), grid, blk, 0, s, a, ksum);
+  prof_mark("keydiff", s);
+  hipLaunchKernelGGL((keydiff_kernel<BF16, HD>), grid, blk, 0, s, a, (const double*)ksum);
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -690,7 +708,10 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
                              &oneread);
   if (e != hipSuccess) return e;
   if (!oneread) {
-    e = bf16 ? run_by_nb<true>(a, nb, mode, s) : run_by_nb<false>(a, nb, mode, s);
+    if (d.D == 64)
+      e = bf16 ? run_by_nb<true, 64>(a, nb, mode, s) : run_by_nb<false, 64>(a, nb, mode, s);
+    else
+      e = bf16 ? run_by_nb<true, 128>(a, nb, mode, s) : run_by_nb<false, 128>(a, nb, mode, s);
     vc_stride = wl.n_chunks;
     vc_tokens = wl.score_chunk;
   }
@@ -701,32 +722,21 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
     vc->tokens = vc_tokens;
   }
   if (vnorm) {
-    double2* part = (double2*)(ws + wl.kbar);
-    const dim3 grid(a.n_chunks, d.units), blk(kThreads);
     prof_mark("esoftmax_part", s);
-    hipLaunchKernelGGL(esoftmax_part_kernel, grid, blk, 0, s, a, part);
+    hipLaunchKernelGGL(esoftmax_part_kernel, dim3(a.n_chunks, d.units), dim3(kThreads), 0, s, a,
+                       (double2*)(ws + wl.kbar));
     prof_mark("vweight", s);
-    if (bf16)
-      hipLaunchKernelGGL(vweight_kernel<true>, grid, blk, 0, s, a, *v, (const double2*)part, p->vnorm_eps);
+    if (d.D == 64)
+      e = bf16 ? launch_vweight<true, 64>(a, *v, ws, wl, p->vnorm_eps, s) : launch_vweight<false, 64>(a, *v, ws, wl, p->vnorm_eps, s);
     else
-      hipLaunchKernelGGL(vweight_kernel<false>, grid, blk, 0, s, a, *v, (const double2*)part, p->vnorm_eps);
-    e = hipGetLastError();
+      e = bf16 ? launch_vweight<true, 128>(a, *v, ws, wl, p->vnorm_eps, s) : launch_vweight<false, 128>(a, *v, ws, wl, p->vnorm_eps, s);
   }
   if (p->scorer == AMS_SCORER_KEYDIFF) {
     a.g = g;
-    double* ksum = (double*)(ws + wl.kbar);
-    const dim3 grid(a.n_chunks, d.units), blk(kThreads);
-    prof_mark("keysum", s);
-    if (bf16) {
-      hipLaunchKernelGGL(keysum_kernel<true>, grid, blk, 0, s, a, ksum);
-      prof_mark("keydiff", s);
-      hipLaunchKernelGGL(keydiff_kernel<true>, grid, blk, 0, s, a, (const double*)ksum);
-    } else {
-      hipLaunchKernelGGL(keysum_kernel<false>, grid, blk, 0, s, a, ksum);
-      prof_mark("keydiff", s);
-      hipLaunchKernelGGL(keydiff_kernel<false>, grid, blk, 0, s, a, (const double*)ksum);
-    }
-    e = hipGetLastError();
+    if (d.D == 64)
+      e = bf16 ? launch_keydiff<true, 64>(a, ws, wl, s) : launch_keydiff<false, 64>(a, ws, wl, s);
+    else
+      e = bf16 ? launch_keydiff<true, 128>(a, ws, wl, s) : launch_keydiff<false, 128>(a, ws, wl, s);
   }
   return e;
 }

@@ -395,7 +395,7 @@ hipError_t launch_score_oneread(const ams_params* p, const Dims& d, const KvDev&
                                 int* vc_stride, int* vc_tokens, char* ws, const WsLayout& wl,
                                 hipStream_t s, bool* ran) {
   *ran = false;
-  if (p->kv_dtype != AMS_BF16 || wl.n_pad > 128) return hipSuccess;
+  if (p->kv_dtype != AMS_BF16 || wl.n_pad > 128 || d.D != 128) return hipSuccess;
   // Opt-in (AMS_SCORER=oneread).  Measured on MI355X at 32 layers x 8 heads x 32k tokens: 1.54 ms
   // against 0.92 ms for the two sweeps.  Each 32-token block costs a SIMD about 4000 cycles of
   // matrix + vector issue per product (they overlap little) against about 3400 cycles of HBM time,

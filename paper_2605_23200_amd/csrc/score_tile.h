@@ -40,21 +40,18 @@ struct ScoreArgs {
   bool causal;  // causal window (App. A): query w of the window sees keys 0 .. T-W+w
 };
 
-template <bool BF16>
-struct Tr;
-template <>
-struct Tr<true> {
-  static constexpr int kRowBytes = 256, kQStride = 272, kAVecs = 8;
-};
-template <>
-struct Tr<false> {
-  static constexpr int kRowBytes = 512, kQStride = 528, kAVecs = 16;
+// Row geometry of a cache of HD channels: bytes per row, stride of a query row in LDS (padded by
+// 16 bytes against bank conflicts), 16-byte vectors per half row (what one lane feeds the MFMA).
+template <bool BF16, int HD = 128>
+struct Tr {
+  static_assert(HD == 64 || HD == 128, "head dimensions the tiles are written for");
+  static constexpr int kRowBytes = HD * (BF16 ? 2 : 4), kQStride = kRowBytes + 16, kAVecs = kRowBytes / 32;
 };
 
 // Query window of the unit -> LDS, rows padded against bank conflicts, rows >= N zero.
-template <bool BF16, int NB>
+template <bool BF16, int NB, int HD = 128>
 __device__ __forceinline__ void load_q(const ScoreArgs& a, int l, int b, int h, char* qlds) {
-  constexpr int RB = Tr<BF16>::kRowBytes, QS = Tr<BF16>::kQStride, CPR = RB / 16;
+  constexpr int RB = Tr<BF16, HD>::kRowBytes, QS = Tr<BF16, HD>::kQStride, CPR = RB / 16;
   const char* src = a.q + ((((int64_t)l * a.d.B + b) * a.d.H + h) * a.d.G) * (int64_t)a.d.W * RB;
   for (int ch = threadIdx.x; ch < NB * 32 * CPR; ch += kThreads) {
     const int n = ch / CPR, col = ch % CPR;
@@ -64,33 +61,33 @@ __device__ __forceinline__ void load_q(const ScoreArgs& a, int l, int b, int h, 
   }
 }
 
-// Lane (r = lane % 32, hf = lane / 32) reads the hf-th half of row t0 + r: one contiguous
-// 128-byte (bf16) or 256-byte (fp32) piece.  The contraction index is permuted the same way on
+// Lane (r = lane % 32, hf = lane / 32) reads the hf-th half of row t0 + r: one contiguous piece
+// (128 bytes for bf16 rows of 128 channels).  The contraction index is permuted the same way on
 // the query side, which leaves the dot products unchanged.
-template <bool BF16>
+template <bool BF16, int HD = 128>
 __device__ __forceinline__ void load_a(const ScoreArgs& a, int l, int b, int h, int t0, int T,
-                                       int lane, uint4 (&av)[Tr<BF16>::kAVecs]) {
-  constexpr int NV = Tr<BF16>::kAVecs;
+                                       int lane, uint4 (&av)[Tr<BF16, HD>::kAVecs]) {
+  constexpr int NV = Tr<BF16, HD>::kAVecs;
   // rows past the end re-read the last row (no divergent branch); their logits are masked later
   const int t = min(t0 + (lane & 31), T - 1);
-  const uint4* p = (const uint4*)(kv_row(a.k, l, b, h, t) + (lane >> 5) * (Tr<BF16>::kRowBytes / 2));
+  const uint4* p = (const uint4*)(kv_row(a.k, l, b, h, t) + (lane >> 5) * (Tr<BF16, HD>::kRowBytes / 2));
 #pragma unroll
   for (int i = 0; i < NV; ++i) av[i] = p[i];
 }
 
 // acc[nb][i] = s_raw[token 8*(i/4) + 4*hf + i%4][query nb*32 + lane%32]
-template <bool BF16, int NB>
-__device__ __forceinline__ void tile_mma(const uint4 (&av)[Tr<BF16>::kAVecs], const char* qlds,
+template <bool BF16, int NB, int HD = 128>
+__device__ __forceinline__ void tile_mma(const uint4 (&av)[Tr<BF16, HD>::kAVecs], const char* qlds,
                                          int lane, floatx16 (&acc)[NB]) {
-  constexpr int QS = Tr<BF16>::kQStride;
-  const char* qb = qlds + (lane & 31) * QS + (lane >> 5) * (Tr<BF16>::kRowBytes / 2);
+  constexpr int QS = Tr<BF16, HD>::kQStride, NV = Tr<BF16, HD>::kAVecs;
+  const char* qb = qlds + (lane & 31) * QS + (lane >> 5) * (Tr<BF16, HD>::kRowBytes / 2);
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[nb][i] = 0.f;
   if constexpr (BF16) {
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < NV; ++ks) {
       const bf16x8 A = __builtin_bit_cast(bf16x8, av[ks]);
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
@@ -100,7 +97,7 @@ __device__ __forceinline__ void tile_mma(const uint4 (&av)[Tr<BF16>::kAVecs], co
     }
   } else {
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
+    for (int j = 0; j < NV; ++j) {
       const float4 A = __builtin_bit_cast(float4, av[j]);
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {

@@ -67,6 +67,13 @@ def test_bad_params_are_rejected_on_the_host(field, value, status):
     assert B.lib().ams_ema_update(C.byref(p), None, None, None, None, None, 0, None) == status
 
 
+def test_both_head_dimensions_are_accepted():
+    p = _good()
+    for d in (64, 128):
+        p.head_dim = d
+        assert B.ams_workspace_bytes(p) > 0
+
+
 def test_segmentation_capacity_rule():
     # target mass 0.1 -> 10 initial segments; with L_max = 256 up to 4096 / 256 = 16 more
     p = _good()

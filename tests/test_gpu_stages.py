@@ -106,6 +106,38 @@ def test_score_value_weighted_parity(oracle, dtype, G, W, T):
     assert g_h[0, T // 2] == 0
 
 
+@pytest.mark.parametrize("dtype,G,W,T,causal", [("bf16", 4, 32, 3000, False), ("f32", 2, 8, 1500, False),
+                                                 ("bf16", 7, 32, 2085, True), ("f32", 4, 32, 700, True)])
+@pytest.mark.parametrize("scorer", list(SCORERS) + ["expected_vnorm"])
+def test_score_parity_head_dim_64(oracle, dtype, G, W, T, causal, scorer):
+    """Caches with 64 channels per head: the same kernels with half-length rows."""
+    sc = SCORERS.get(scorer, B.SCORER_EXPECTED_VNORM)
+    w = _workload(dtype, G, W, T, D=64, causal=causal)
+    host = inputs.dense_cache(w, n_threads=4)
+    p = params_for(w, scorer=sc)
+    assert p.head_dim == 64
+    ws = workspace(p)
+    K, V, Q = to_dev(host["K"]), to_dev(host["V"]), to_dev(host["Q"])
+    lens = to_dev(host["seq_lens"])
+    u = torch.full((p.units, w.T), -7.0, device=DEV)
+    g = torch.full((p.units, w.T), -7.0, device=DEV)
+    B.ams_score(p, B.dense_view(K, V), lens, Q, u, g, ws)
+    torch.cuda.synchronize()
+    u_h, g_h = to_host(u), to_host(g)
+    for i, (l, b, h) in enumerate(unit_list(w)):
+        q_i, k_i = host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), host["K"][l, b, h, :T]
+        if scorer == "expected_vnorm":
+            uo, eo = oracle.score(q_i, k_i, w.G, w.W, B.SCORER_EXPECTED, causal=causal)
+            go = oracle.value_weight(eo, host["V"][l, b, h, :T], 1e-2)
+        else:
+            uo, go = oracle.score(q_i, k_i, w.G, w.W, sc, causal=causal)
+        assert_close_rel(u_h[i], uo, what=f"u unit {i}")
+        if scorer in ("mean", "last", "expected_vnorm"):
+            assert_close_rel(g_h[i], go, what=f"g unit {i}")
+        else:
+            assert_close_norm(g_h[i], go, what=f"g unit {i}")
+
+
 def test_score_ragged_batch_paged(oracle):
     # ragged batch in a paged layout: lengths that are not multiples of 16 or 32, permuted blocks
     w = inputs.CONFIGS[2].scaled(L=2, B=3, H=2, T=1500, T_min=300, n_spans=3, span_len=(16, 64), budget=128)

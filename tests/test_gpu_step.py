@@ -396,6 +396,21 @@ def test_segmentation_as_printed_step(oracle, delta, l_min, l_max, pool):
     check_units(oracle, job, host, credit_before[:, :w.T], [0, w.units - 1])
 
 
+@pytest.mark.parametrize("dtype,paged", [("bf16", False), ("f32", False), ("bf16", True)])
+def test_head_dim_64_step(oracle, dtype, paged):
+    """Whole step on caches with 64 channels per head (rows of 128 / 256 bytes), dense and paged."""
+    if paged:
+        w = inputs.CONFIGS[2].scaled(L=1, B=6, H=3, D=64, T=3000, T_min=700, n_spans=4, span_len=(16, 100), budget=256,
+                                     n_sink=4, n_last=16)
+    else:
+        w = inputs.CONFIGS[1].scaled(L=2, H=3, D=64, dtype=dtype, T=5000, budget=512, S=8, n_spans=6, span_len=(32, 300))
+    host = inputs.dense_cache(w, n_threads=4)
+    job = Job(w, host)
+    job.step()
+    check_properties_all_units(job)
+    check_units(oracle, job, host, np.zeros((w.units, job.t_max), np.float32), list(range(min(w.units, 8))))
+
+
 def test_causal_paged_ragged(oracle):
     w = inputs.CONFIGS[2].scaled(L=1, B=8, H=4, causal=True)
     host = inputs.dense_cache(w, n_threads=8)
