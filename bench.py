@@ -24,27 +24,36 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
 
 
-def algorithmic_bytes(w):
-    """Bytes one event must move per unit: K read once for scoring, kept K/V rows read and written,
+def _token_sums(w, lens):
+    """(sum of the sequence lengths, sum of the kept counts) over the batch."""
+    if lens is None:
+        return w.B * w.T, w.B * min(w.budget, w.T)
+    return int(sum(int(t) for t in lens)), int(sum(min(w.budget, int(t)) for t in lens))
+
+
+def algorithmic_bytes(w, lens=None):
+    """Bytes one event must move over all units: K read once for scoring, kept K/V rows read and written,
     three fp32 vector passes (u write + read, credit read), index and credit' writes."""
     e = w.elem_bytes
-    return w.T * w.D * e + 4 * w.budget * w.D * e + 4 * w.T * 3 + 4 * w.budget * 2
+    tok, kept = _token_sums(w, lens)
+    return (tok * w.D * e + 4 * kept * w.D * e + 4 * tok * 3 + 4 * kept * 2) * w.L * w.H
 
 
-def kernel_bytes(label, w):
+def kernel_bytes(label, w, lens=None):
     """Algorithmic bytes of one launch of a kernel over all units (what it must read + write)."""
-    e, U, T, Bd, D, S = w.elem_bytes, w.units, w.T, w.budget, w.D, w.S
-    per_unit = {
-        "score_stats": T * D * e,                       # K stream
-        "score_usage": T * D * e + 4 * T,               # K stream + u
+    e, D = w.elem_bytes, w.D
+    tok, kept = _token_sums(w, lens)
+    per_layer_head = {
+        "score_stats": tok * D * e,                       # K stream
+        "score_usage": tok * D * e + 4 * tok,             # K stream + u
         "score_reduce": 0,
-        "mass_ema": 4 * T * 4,                          # u, credit in; credit, m_used out
-        "segment_scan": 4 * T,                          # m_used in
+        "mass_ema": 4 * tok * 4,                          # u, credit in; credit, m_used out
+        "segment_scan": 4 * tok,                          # m_used in
         "quota": 0,
-        "select": 4 * T + 4 * Bd,                       # g in, idx out
-        "compact": 4 * Bd * D * e + 4 * Bd * 3,         # K,V rows in + out, idx, credit gather
+        "select": 4 * tok + 4 * kept,                     # g in, idx out
+        "compact": 4 * kept * D * e + 4 * kept * 3,       # K,V rows in + out, idx, credit gather
     }.get(label, 0)
-    return per_unit * U
+    return per_layer_head * w.L * w.H
 
 
 def main():
@@ -89,21 +98,32 @@ def main():
         import math
         cap = math.ceil(1 / args.seg_delta) + 1 + (w.T // args.l_max if args.l_max else 0)
         w = w.scaled(seg_delta=args.seg_delta, l_min=args.l_min, l_max=args.l_max, S=cap)
-    if w.paged or w.T_min is not None:
-        sys.exit("bench.py: only dense single-length workloads are benchmark lines")
     t0 = time.time()
-    host = inputs.dense_cache(w, n_threads=16)
     scorer_id = {"mean_window": B.SCORER_MEAN_WINDOW, "last_query": B.SCORER_LAST_QUERY,
                  "keydiff": B.SCORER_KEYDIFF, "expected": B.SCORER_EXPECTED,
                  "expected_vnorm": B.SCORER_EXPECTED_VNORM}[args.scorer]
-    job = Job(w, host, scorer=scorer_id)
     n_q = 4
-    q_windows = [job.Q] + [torch.empty_like(job.Q) for _ in range(n_q - 1)]
-    for e in range(1, n_q):
-        Q = np.zeros_like(host["Q"])
-        for (l, b, h) in inputs.unit_ids(w):
-            Q[l, b, h * w.G:(h + 1) * w.G] = inputs.unit_q(w, l, b, h, e)
-        q_windows[e].copy_(torch.from_numpy(Q.view(np.int16) if Q.dtype == np.uint16 else Q))
+    lens = None
+    if w.paged:
+        # the paged, ragged configuration is far too large to draw on the host: lengths and block tables are
+        # the seeded ones, the values are drawn on the device (no oracle leg, no planted spans)
+        from paper_2605_23200_amd.harness import DeviceFilledPagedJob
+        host = None
+        job = DeviceFilledPagedJob(w, scorer=scorer_id)
+        lens = job.lens_h
+        q_windows = [job.Q] + [torch.randn_like(job.Q, dtype=torch.float32).to(job.Q.dtype) for _ in range(n_q - 1)]
+        args.no_cpu_baseline = True
+    else:
+        if w.T_min is not None:
+            sys.exit("bench.py: ragged workloads are benchmarked in the paged layout only")
+        host = inputs.dense_cache(w, n_threads=16)
+        job = Job(w, host, scorer=scorer_id)
+        q_windows = [job.Q] + [torch.empty_like(job.Q) for _ in range(n_q - 1)]
+        for e in range(1, n_q):
+            Q = np.zeros_like(host["Q"])
+            for (l, b, h) in inputs.unit_ids(w):
+                Q[l, b, h * w.G:(h + 1) * w.G] = inputs.unit_q(w, l, b, h, e)
+            q_windows[e].copy_(torch.from_numpy(Q.view(np.int16) if Q.dtype == np.uint16 else Q))
     setup_s = time.time() - t0
     stream = torch.cuda.current_stream()
 
@@ -134,7 +154,7 @@ def main():
     n_prof = min(len(v) for v in per.values())
     step_sums = sorted(sum(per[k][i] for k in per) for i in range(n_prof))
     dom = max(kern, key=kern.get)
-    dom_bytes = kernel_bytes(dom, w)
+    dom_bytes = kernel_bytes(dom, w, lens)
     achieved = dom_bytes / (kern[dom] * 1e-3) / 1e9
 
     # the ceiling a plain device copy reaches in the same run (1 GiB read + 1 GiB written)
@@ -152,7 +172,7 @@ def main():
 
     # the literal trajectory's later events are short (kept rows + appended tokens): launch-bound
     small_ms = None
-    if w.n_append > 0:
+    if w.n_append > 0 and not w.paged:
         ws_small = w.scaled(T=w.budget + w.n_append, n_spans=max(1, w.n_spans * (w.budget + w.n_append) // w.T))
         job_s = Job(ws_small, inputs.dense_cache(ws_small, n_threads=16), scorer=scorer_id)
         for _ in range(5):
@@ -173,7 +193,7 @@ def main():
         torch.cuda.synchronize()
         del src_c, dst_c
 
-    step_bytes = algorithmic_bytes(w) * w.units
+    step_bytes = algorithmic_bytes(w, lens)
     eff_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     traffic = None
@@ -188,8 +208,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
         "data": "synthetic",
         "config": {"workload": f"config{args.config}: {w.L}L x {w.H} KV heads, group {w.G}, D {w.D}, {w.dtype}, "
-                               f"T {w.T}, window {w.W}, budget {w.budget}, S {w.S}, lambda {w.lam}, "
-                               f"{w.n_spans} planted spans, seed {w.seed}; steady-state events at full T"
+                               f"T {w.T}{'' if lens is None else f' (ragged from {w.T_min}, paged, device-drawn values)'}, window {w.W}, budget {w.budget}, S {w.S}, lambda {w.lam}, "
+                               f"{'no' if lens is not None else w.n_spans} planted spans, seed {w.seed}; steady-state events at full T"
                                + (f"; must-keep {w.n_sink}+{w.n_last}" if w.n_sink or w.n_last else "")
                                + ("; causal window" if w.causal else "")
                                + (f"; Delta {w.seg_delta} L {w.l_min}/{w.l_max}" if w.seg_delta else "")
@@ -201,8 +221,8 @@ def main():
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "kernel_ms": round(kern[dom], 4), "algorithmic_bytes_per_launch": dom_bytes},
         "kernel_ms": {k: round(v, 4) for k, v in kern.items()},
-        "stage_GBps": {k: round(kernel_bytes(k, w) / (v * 1e-3) / 1e9, 1) for k, v in kern.items()
-                       if kernel_bytes(k, w) > 0},
+        "stage_GBps": {k: round(kernel_bytes(k, w, lens) / (v * 1e-3) / 1e9, 1) for k, v in kern.items()
+                       if kernel_bytes(k, w, lens) > 0},
         "step_ms_median": round(step_sums[len(step_sums) // 2], 4), "step_ms_min": round(step_sums[0], 4),
         "copy_GBps": round(copy_gbps, 1),
         "small_event": None if small_ms is None else

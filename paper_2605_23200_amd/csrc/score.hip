@@ -42,6 +42,27 @@ constexpr int kGroup = (NB % AMS_SCORE_GROUP_DIV == 0 && NB >= 4) ? NB / AMS_SCO
 // are seen by every query and run through the plain kernels, which then stop at t_end; the few
 // blocks from t_end on go through the TAIL instantiation of the same kernels (one workgroup per
 // unit), where a (query, key) pair the mask hides is left out.
+// Which (unit, chunk) a workgroup of the sweeps takes.  Dense caches: grid x = chunk, grid y = unit.
+// Paged caches keep the rows of a position's KV heads next to each other in a slot, so there the
+// heads of one (layer, sequence, chunk) are given to consecutive workgroups: they run at the same
+// time and read the same slots (DRAM pages) together instead of eight separate times.
+__device__ __forceinline__ void sweep_tile(const ScoreArgs& a, bool tail, bool reversed, int& unit, int& chunk) {
+  int bx = blockIdx.x, by = blockIdx.y;
+  if (reversed) {
+    bx = gridDim.x - 1 - bx;
+    by = gridDim.y - 1 - by;
+  }
+  if (a.k.layout != AMS_LAYOUT_PAGED || tail) {
+    unit = by;
+    chunk = tail ? 0 : bx;
+    return;
+  }
+  const int lin = by * gridDim.x + bx;  // gridDim.x = chunks per unit, gridDim.y = units
+  const int h = lin % a.d.H, rest = lin / a.d.H;
+  chunk = rest % (int)gridDim.x;
+  unit = (rest / (int)gridDim.x) * a.d.H + h;
+}
+
 __device__ __forceinline__ int causal_t_end(const ScoreArgs& a, int T) {
   return a.causal ? max(0, (T - a.d.W + 1) / 32 * 32) : T;
 }
@@ -57,7 +78,8 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
   constexpr int NG = kGroup<NB>, QS = Tr<BF16, HD>::kQStride;
   extern __shared__ __align__(16) char qlds[];
   __shared__ float2 xch[4][NB * 32];
-  const int unit = blockIdx.y, chunk = blockIdx.x;
+  int unit, chunk;
+  sweep_tile(a, TAIL, false, unit, chunk);
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T_all = seq_len(a.d, a.seq_lens, b), t_end = causal_t_end(a, T_all);
@@ -265,7 +287,8 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   extern __shared__ __align__(16) char qlds[];
   // the second sweep walks the cache backwards: what the first sweep read last is still in the
   // memory-side cache (about a tenth of the keys at the headline size)
-  const int unit = gridDim.y - 1 - blockIdx.y, chunk = TAIL ? 0 : gridDim.x - 1 - blockIdx.x;
+  int unit, chunk;
+  sweep_tile(a, TAIL, true, unit, chunk);
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T_all = seq_len(a.d, a.seq_lens, b), t_end = causal_t_end(a, T_all);

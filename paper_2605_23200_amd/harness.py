@@ -71,3 +71,49 @@ class Job:
 
     def intermediates(self) -> B.StepIntermediates:
         return B.workspace_tensors(self.p, self.ws)
+
+
+class DeviceFilledPagedJob:
+    """A paged, ragged workload too large to draw on the host (config 2: about 90 GB of pools): lengths and
+    block tables come from the seeded generators of `inputs`, the K / V / Q VALUES are standard normal numbers
+    drawn on the device (seeded), without planted spans.  For throughput runs only: there is no host copy to
+    check against."""
+
+    def __init__(self, w: inputs.Workload, scorer: int = B.SCORER_MEAN_WINDOW, device: str = "cuda:0", seed: int = 0):
+        assert w.paged
+        self.w, self.device = w, device
+        lens = inputs.seq_lens(w)
+        self.lens_h = lens
+        self.t_max = int(lens.max())
+        self.t_stride = (self.t_max + 63) // 64 * 64
+        self.keep = min(w.budget, self.t_max)
+        self.units = w.units
+        src, dst, n_slots = inputs.block_tables(w, lens, self.keep)
+        dtype = torch.float32 if w.dtype == "f32" else torch.bfloat16
+        gen = torch.Generator(device=device)
+        gen.manual_seed(seed)
+        self.K = torch.empty((w.L, n_slots, w.H, w.D), dtype=dtype, device=device)
+        self.V = torch.empty_like(self.K)
+        for l in range(w.L):                       # layer by layer: no fp32 temporary of the whole pool
+            self.K[l].normal_(generator=gen)
+            self.V[l].normal_(generator=gen)
+        self.Q = torch.randn((w.L, w.B, w.H * w.G, w.W, w.D), device=device, generator=gen).to(dtype)
+        self.p = B.make_params(n_layers=w.L, batch=w.B, n_kv_heads=w.H, group=w.G, window=w.W, head_dim=w.D,
+                               kv_dtype=B.F32 if w.dtype == "f32" else B.BF16, t_max=self.t_max,
+                               t_stride=self.t_stride, budget=w.budget, n_segments=w.S, q_min=w.q_min,
+                               ema_lambda=w.lam, ema_beta=w.beta, mass_eps=w.eps, scorer=scorer, n_sink=w.n_sink,
+                               n_last=w.n_last, causal=w.causal, seg_delta=w.seg_delta, l_min=w.l_min,
+                               l_max=w.l_max, pool_kernel=w.pool_kernel)
+        self.lens = _dev(lens, device)
+        self.src_table, self.dst_table = _dev(src, device), _dev(dst, device)
+        self.src = B.paged_view(self.K, self.V, self.src_table)
+        self.dst = B.paged_view(self.K, self.V, self.dst_table)
+        self.credit = torch.zeros((self.units, self.t_stride), dtype=torch.float32, device=device)
+        self.credit_dst = torch.zeros((self.units, w.budget), dtype=torch.float32, device=device)
+        self.idx = torch.full((self.units, w.budget), -9, dtype=torch.int32, device=device)
+        self.n_kept = torch.zeros(self.units, dtype=torch.int32, device=device)
+        self.ws = torch.zeros(B.ams_workspace_bytes(self.p), dtype=torch.uint8, device=device)
+
+    def step(self, stream=None):
+        B.ams_compress_step(self.p, self.src, self.lens, self.Q, self.credit, self.dst, self.credit_dst,
+                            self.idx, self.n_kept, self.ws, stream)
