@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--scorer", default="mean_window",
                     choices=["mean_window", "last_query", "keydiff", "expected", "expected_vnorm"],
                     help="base scorer (the headline workload uses mean_window)")
+    ap.add_argument("--no-small-event", action="store_true",
+                    help="skip the short event of the literal trajectory (profiling runs: one workload per kernel name)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that a counter run of this "
                          "command can be scaled: see profiles/")
@@ -172,7 +174,7 @@ def main():
 
     # the literal trajectory's later events are short (kept rows + appended tokens): launch-bound
     small_ms = None
-    if w.n_append > 0 and not w.paged:
+    if w.n_append > 0 and not w.paged and not args.no_small_event:
         ws_small = w.scaled(T=w.budget + w.n_append, n_spans=max(1, w.n_spans * (w.budget + w.n_append) // w.T))
         job_s = Job(ws_small, inputs.dense_cache(ws_small, n_threads=16), scorer=scorer_id)
         for _ in range(5):
