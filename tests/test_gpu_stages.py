@@ -515,3 +515,35 @@ def test_lengths_and_indices_out_of_range_stay_inside_the_buffers(oracle):
         np.testing.assert_array_equal(Kd_h[i, 0], Kh[i, 5])
         np.testing.assert_array_equal(Kd_h[i, 3], Kh[i, 9])
         assert (Kd_h[i, 1] == 77).all() and (Kd_h[i, 2] == 77).all() and (Kd_h[i, 4:] == 77).all()
+
+
+@pytest.mark.parametrize("dtype,scale,rtol", [("bf16", 8.0, 1e-5), ("f32", 30.0, 3e-4), ("bf16", 0.0, 1e-5)])
+def test_score_extreme_logits(oracle, dtype, scale, rtol):
+    """Keys scaled so that the logits span hundreds of units (the softmax is all but one-hot), and
+    all-zero keys (uniform softmax): no overflow, no NaN, same numbers as the oracle.  A probability
+    inherits the ABSOLUTE error of its logit, and fp32 accumulation of 128 products of magnitude ~100
+    is good to a few 1e-5, so the relative bound is widened with the scale of the logits."""
+    w = _workload(dtype, 4, 16, 3000)
+    host = inputs.dense_cache(w, n_threads=4)
+    if dtype == "bf16":
+        Kf = inputs.bf16_bits_to_f32(host["K"]) * scale
+        host["K"] = inputs.to_bf16_bits(Kf.astype(np.float32))
+    else:
+        host["K"] = (host["K"] * scale).astype(np.float32)
+    for sc_name in ("mean", "last"):
+        p = params_for(w, scorer=SCORERS[sc_name])
+        ws = workspace(p)
+        K, Q = to_dev(host["K"]), to_dev(host["Q"])
+        u = torch.zeros((p.units, w.T), device=DEV)
+        g = torch.zeros((p.units, w.T), device=DEV)
+        B.ams_score(p, B.dense_view(K, None), to_dev(host["seq_lens"]), Q, u, g, ws)
+        torch.cuda.synchronize()
+        u_h, g_h = to_host(u), to_host(g)
+        assert np.isfinite(u_h).all() and np.isfinite(g_h).all()
+        for i, (l, b, h) in enumerate(unit_list(w)):
+            uo, go = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), host["K"][l, b, h],
+                                  w.G, w.W, SCORERS[sc_name])
+            assert_close_rel(u_h[i], uo, rtol=rtol, atol=1e-30, what=f"u unit {i}")
+            assert_close_rel(g_h[i], go, rtol=rtol, atol=1e-30, what=f"g unit {i}")
+            if scale == 0.0:
+                np.testing.assert_allclose(u_h[i], 1.0 / w.T, rtol=1e-6)
