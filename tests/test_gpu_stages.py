@@ -399,7 +399,8 @@ def test_select_single_segment_is_global_topk():
         np.testing.assert_array_equal(idx[i], np.sort(order[:k]))
 
 
-def test_quota_adversarial(oracle):
+@pytest.mark.parametrize("q_min", [0, 1, 3])
+def test_quota_adversarial(oracle, q_min):
     # masses with exact ties, empty segments, caps that bind, budgets below the number of segments
     rng = np.random.default_rng(3)
     S, units = 16, 64
@@ -416,13 +417,13 @@ def test_quota_adversarial(oracle):
         for i in range(units):
             Ti = int(bounds[i, -1])
             p = _vec_params(1, Ti, S=S, budget=budget)
+            p.q_min = q_min
             quota = torch.zeros((1, S), dtype=torch.int32, device=DEV)
-            idx = torch.zeros((1, budget), dtype=torch.int32, device=DEV) if budget < 1000 else \
-                torch.zeros((1, budget), dtype=torch.int32, device=DEV)
+            idx = torch.zeros((1, budget), dtype=torch.int32, device=DEV)
             n_kept = torch.zeros(1, dtype=torch.int32, device=DEV)
             B.ams_select(p, to_dev(np.array([Ti], np.int32)), torch.zeros((1, Ti), device=DEV),
                          to_dev(bounds[i:i + 1]), to_dev(mass[i:i + 1]), quota, idx, n_kept)
-            np.testing.assert_array_equal(to_host(quota)[0], oracle.quota(bounds[i], mass[i], budget, 1))
+            np.testing.assert_array_equal(to_host(quota)[0], oracle.quota(bounds[i], mass[i], budget, q_min))
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
