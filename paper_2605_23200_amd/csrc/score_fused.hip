@@ -37,7 +37,6 @@ struct FusedArgs {
   int32_t* counter;             // [units]
   int32_t* flag;                // [units]
   int32_t* status;              // [1] 0 = fine
-  long long* dbg;               // development aid (phase timing)
   int tiles_max;
 };
 
@@ -54,17 +53,6 @@ __device__ __forceinline__ float2 load_agent(const float2* p) {
                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 }
 __device__ __forceinline__ void wait_stores_complete() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0)
-
-#ifdef AMS_FUSED_TIMING
-#define TICK(k)                                                    \
-  do {                                                             \
-    const long long now_ = clock64();                              \
-    if (threadIdx.x == 0) tacc[k] += now_ - tprev;                 \
-    tprev = now_;                                                  \
-  } while (0)
-#else
-#define TICK(k) do {} while (0)
-#endif
 
 struct TileId {
   int unit, l, b, h, j, T;
@@ -125,10 +113,6 @@ __global__ __launch_bounds__(kThreads, 3) void score_oneread_kernel(FusedArgs a)
   const int total = a.s.d.L * per_layer;
   const int n_pad = a.s.n_pad;
   const float c2 = a.s.c2;
-#ifdef AMS_FUSED_TIMING
-  long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  long long tprev = clock64();
-#endif
 
 #pragma unroll 1
   for (int tile = blockIdx.x; tile < total; tile += gridDim.x) {
@@ -143,7 +127,6 @@ __global__ __launch_bounds__(kThreads, 3) void score_oneread_kernel(FusedArgs a)
     __syncthreads();  // the previous tile is done with the LDS areas
     load_q<true, NB>(a.s, cur.l, cur.b, cur.h, qlds);
     __syncthreads();
-    TICK(0);
 
     // ---- first product: per-query (max, sum exp2) over this wave's tokens, log2 domain ----
     float m[NB], z[NB];
@@ -192,7 +175,6 @@ __global__ __launch_bounds__(kThreads, 3) void score_oneread_kernel(FusedArgs a)
       if (hf == 0) xch[wave][nb * 32 + c] = make_float2(M, Z);
     }
     __syncthreads();
-    TICK(1);
     const int tiles_u = a.tiles_before[cur.b + 1] - a.tiles_before[cur.b];
     if (threadIdx.x < NB * 32) {
       const int n = threadIdx.x;
@@ -206,13 +188,11 @@ __global__ __launch_bounds__(kThreads, 3) void score_oneread_kernel(FusedArgs a)
     }
     wait_stores_complete();  // the statistics are in place before the tile is counted
     __syncthreads();
-    TICK(2);
     if (threadIdx.x == 0) {
       const int old = __hip_atomic_fetch_add(&a.counter[cur.unit], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       s_last = (old == tiles_u - 1);
     }
     __syncthreads();
-    TICK(3);
     if (s_last) {
       // last tile of the unit: merge all tiles' statistics.  The 256 threads split into
       // (query, contiguous range of tiles) pairs; loads go out in batches so that their latencies
@@ -257,7 +237,6 @@ __global__ __launch_bounds__(kThreads, 3) void score_oneread_kernel(FusedArgs a)
       __syncthreads();
       if (threadIdx.x == 0) __hip_atomic_store(&a.flag[cur.unit], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    TICK(4);
     if (threadIdx.x == 0) {
       int budget = kSpinLimit;
       while (__hip_atomic_load(&a.flag[cur.unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0 && --budget > 0)
@@ -273,7 +252,6 @@ __global__ __launch_bounds__(kThreads, 3) void score_oneread_kernel(FusedArgs a)
       fin_s[threadIdx.x] = make_float4(f01.x, f01.y, f23.x, f23.y);
     }
     __syncthreads();
-    TICK(5);
 
     // ---- second product from the same registers: u[t] = sum_n exp2(x - M_n) / (N Z_n) ----
     float4 f[NB];
@@ -339,12 +317,7 @@ __global__ __launch_bounds__(kThreads, 3) void score_oneread_kernel(FusedArgs a)
         a.s.vc_part[(int64_t)cur.unit * a.tiles_max + cur.j] = t;
       }
     }
-    TICK(6);
   }
-#ifdef AMS_FUSED_TIMING
-  if (threadIdx.x == 0)
-    for (int k = 0; k < 8; ++k) a.dbg[blockIdx.x * 8 + k] = tacc[k];
-#endif
 }
 static_assert(kTileTok == kThreads, "the credit sum reads one position per thread");
 
@@ -383,7 +356,6 @@ size_t fused_score_ws_bytes(int64_t units, int t_max, int n_pad, int batch) {
   o += align256((size_t)units * tiles_max * n_pad * sizeof(float2));
   o += align256(((size_t)units * 2 + 64) * sizeof(int32_t));
   o += align256(((size_t)batch + 1) * sizeof(int32_t));
-  o += align256((size_t)65536 * sizeof(long long));
   return o;
 }
 
@@ -435,7 +407,6 @@ hipError_t launch_score_oneread(const ams_params* p, const Dims& d, const KvDev&
   w += align256(((size_t)d.units * 2 + 64) * sizeof(int32_t));
   a.tiles_before = (int32_t*)w;
   w += align256(((size_t)d.B + 1) * sizeof(int32_t));
-  a.dbg = (long long*)w;
   const int nb = wl.n_pad / 32;
   const int lds = nb * 32 * Tr<true>::kQStride;
   const int64_t all_tiles = (int64_t)d.units * a.tiles_max;
