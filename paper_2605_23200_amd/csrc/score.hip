@@ -89,7 +89,13 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
   const int t_vis0 = T_all - a.d.W;  // newest key visible to the oldest query of the window
   uint4 av0[Tr<BF16, HD>::kAVecs], av1[Tr<BF16, HD>::kAVecs];
-  if (c0 + wave * 32 < T) load_a<BF16, HD>(a, l, b, h, c0 + wave * 32, T, lane, av0);
+  __shared__ int32_t blk_sm[kScoreChunk / 16];
+  const int32_t* blk = nullptr;  // paged caches: this chunk's block numbers, staged once
+  if (a.k.layout == AMS_LAYOUT_PAGED) {
+    stage_blocks(a, b, c0, min(T, c0 + a.chunk), blk_sm);
+    blk = blk_sm;
+  }
+  if (c0 + wave * 32 < T) load_a<BF16, HD>(a, l, b, h, c0 + wave * 32, T, lane, av0, blk, c0);
   load_q<BF16, NB, HD>(a, l, b, h, qlds);
   __syncthreads();
   float m[NB], z[NB];
@@ -173,10 +179,10 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
   const int t_lim = min(T, c0 + a.chunk);
 #pragma unroll 1
   for (int t0 = c0 + wave * 32; t0 < t_lim; t0 += 256) {
-    if (t0 + 128 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 128, T, lane, av1);
+    if (t0 + 128 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 128, T, lane, av1, blk, c0);
     block(av0, t0);
     if (t0 + 128 >= t_lim) break;
-    if (t0 + 256 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 256, T, lane, av0);
+    if (t0 + 256 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 256, T, lane, av0, blk, c0);
     block(av1, t0 + 128);
   }
 #pragma unroll
@@ -298,7 +304,13 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5, c = lane & 31;
   const int t_vis0 = T_all - a.d.W;  // newest key visible to the oldest query of the window
   uint4 av0[Tr<BF16, HD>::kAVecs], av1[Tr<BF16, HD>::kAVecs];
-  if (c0 + wave * 32 < T) load_a<BF16, HD>(a, l, b, h, c0 + wave * 32, T, lane, av0);
+  __shared__ int32_t blk_sm[kScoreChunk / 16];
+  const int32_t* blk = nullptr;  // paged caches: this chunk's block numbers, staged once
+  if (a.k.layout == AMS_LAYOUT_PAGED) {
+    stage_blocks(a, b, c0, min(T, c0 + a.chunk), blk_sm);
+    blk = blk_sm;
+  }
+  if (c0 + wave * 32 < T) load_a<BF16, HD>(a, l, b, h, c0 + wave * 32, T, lane, av0, blk, c0);
   load_q<BF16, NB, HD>(a, l, b, h, qlds);
   __syncthreads();
   float4 f[NB];
@@ -362,10 +374,10 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   const int t_lim = min(T, c0 + a.chunk);
 #pragma unroll 1
   for (int t0 = c0 + wave * 32; t0 < t_lim; t0 += 256) {
-    if (t0 + 128 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 128, T, lane, av1);
+    if (t0 + 128 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 128, T, lane, av1, blk, c0);
     block(av0, t0);
     if (t0 + 128 >= t_lim) break;
-    if (t0 + 256 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 256, T, lane, av0);
+    if (t0 + 256 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 256, T, lane, av0, blk, c0);
     block(av1, t0 + 128);
   }
   if (a.vc_part) {  // chunk sums of max(u,0)+eps in a fixed order: lanes, then waves

@@ -66,13 +66,32 @@ __device__ __forceinline__ void load_q(const ScoreArgs& a, int l, int b, int h, 
 // the query side, which leaves the dot products unchanged.
 template <bool BF16, int HD = 128>
 __device__ __forceinline__ void load_a(const ScoreArgs& a, int l, int b, int h, int t0, int T,
-                                       int lane, uint4 (&av)[Tr<BF16, HD>::kAVecs]) {
+                                       int lane, uint4 (&av)[Tr<BF16, HD>::kAVecs],
+                                       const int32_t* blk_lds = nullptr, int blk_t0 = 0) {
   constexpr int NV = Tr<BF16, HD>::kAVecs;
   // rows past the end re-read the last row (no divergent branch); their logits are masked later
   const int t = min(t0 + (lane & 31), T - 1);
-  const uint4* p = (const uint4*)(kv_row(a.k, l, b, h, t) + (lane >> 5) * (Tr<BF16, HD>::kRowBytes / 2));
+  const char* row;
+  if (blk_lds) {
+    // paged cache: the physical block numbers of the positions from blk_t0 (a multiple of 16) on
+    // were staged in LDS, so the row address does not wait for a table entry from memory
+    int64_t slot = (int64_t)blk_lds[(t - blk_t0) >> 4] * 16 + (t & 15);
+    slot = slot < 0 ? 0 : (slot >= a.k.n_slots ? a.k.n_slots - 1 : slot);
+    row = a.k.base + (((int64_t)l * a.k.n_slots + slot) * a.k.H + h) * (int64_t)a.k.row_bytes;
+  } else {
+    row = kv_row(a.k, l, b, h, t);
+  }
+  const uint4* p = (const uint4*)(row + (lane >> 5) * (Tr<BF16, HD>::kRowBytes / 2));
 #pragma unroll
   for (int i = 0; i < NV; ++i) av[i] = p[i];
+}
+
+// Paged cache: block numbers of the positions [c0, t_lim) of sequence b -> LDS (c0 a multiple of 16).
+__device__ __forceinline__ void stage_blocks(const ScoreArgs& a, int b, int c0, int t_lim, int32_t* blk_lds) {
+  const int n = (t_lim - c0 + 15) >> 4;
+  for (int i = threadIdx.x; i < n; i += kThreads)
+    blk_lds[i] = a.k.block_table[(int64_t)b * a.k.max_blocks + (c0 >> 4) + i];
+  __syncthreads();
 }
 
 // acc[nb][i] = s_raw[token 8*(i/4) + 4*hf + i%4][query nb*32 + lane%32]
