@@ -237,7 +237,7 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
     pz[threadIdx.x] = Z;
   }
   __syncthreads();
-  if (threadIdx.x < a.n_pad) {
+  if ((int)threadIdx.x < a.n_pad) {
     float M = kNegInit;
     for (int q = 0; q < parts; ++q) M = fmaxf(M, pm[q * a.n_pad + n]);
     double Z = 0.0;
@@ -465,7 +465,7 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   const int c0 = chunk * a.chunk;
   if (c0 >= T) return;
   const int nch = (T + a.chunk - 1) / a.chunk;
-  if (threadIdx.x < a.d.D) {
+  if ((int)threadIdx.x < a.d.D) {
     double t = 0.0;
     for (int c = 0; c < nch; ++c) t += ksum[((int64_t)unit * a.n_chunks + c) * a.d.D + threadIdx.x];
     kbar[threadIdx.x] = t / (double)T;

@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kThreads, 3) void score_oneread_kernel(FusedArgs a)
       merge_m[threadIdx.x] = M;
       merge_z[threadIdx.x] = Z;
       __syncthreads();
-      if (threadIdx.x < n_pad) {
+      if ((int)threadIdx.x < n_pad) {
         float Mf = kNegInit;
         for (int q = 0; q < parts; ++q) Mf = fmaxf(Mf, merge_m[q * n_pad + n]);
         double Zf = 0.0;

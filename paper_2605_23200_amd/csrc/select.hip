@@ -145,7 +145,7 @@ __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_le
   const int bud = quota_prologue(d, seq_lens, S, budget, seg_mass_all, idx_all, n_kept_all, cpre_all, mpart_all,
                                  n_chunks, n_sink, n_last, flags_all, n_words);
   const int q = quota_wave(S, bud, q_min, bounds_all + (int64_t)unit * (S + 1), seg_mass_all + (int64_t)unit * S);
-  if (threadIdx.x < S) quota_all[(int64_t)unit * S + threadIdx.x] = q;
+  if ((int)threadIdx.x < S) quota_all[(int64_t)unit * S + threadIdx.x] = q;
 }
 
 // More than 64 segments (up to 1024): one workgroup of 256 threads per unit, the segments in LDS.
