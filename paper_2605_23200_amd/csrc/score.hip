@@ -106,6 +106,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
   }
   const float c2 = a.c2;
   float* g_row = MOMENTS ? a.g + (int64_t)unit * a.d.t_stride : nullptr;
+  __shared__ float g_sm[MOMENTS ? kScoreChunk : 1];  // the chunk's moment scores, written once at the end
   auto block = [&](const uint4 (&av)[Tr<BF16, HD>::kAVecs], int t0) __attribute__((always_inline)) {
     const bool ragged = t0 + 32 > T;
     // the query fragments are re-read from LDS for every block: keeping them in registers across
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
       const float d_sq = reduce16_over32(s2, c) * inv_n;     // mean of (s - r)^2
       const int t = t0 + acc_row(c >> 1, hf);
       if ((c & 1) == 0 && t < T_all)
-        g_row[t] = (r_tok + d_mean) * a.inv_sqrt_d + 0.5f * (d_sq - d_mean * d_mean) * (a.inv_sqrt_d * a.inv_sqrt_d);
+        g_sm[t - c0] = (r_tok + d_mean) * a.inv_sqrt_d + 0.5f * (d_sq - d_mean * d_mean) * (a.inv_sqrt_d * a.inv_sqrt_d);
     }
   };
   // this wave's blocks: every fourth block of 32 tokens up to the end of the chunk (or of the cache)
@@ -195,6 +196,8 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
     if (hf == 0) xch[wave][nb * 32 + (lane & 31)] = make_float2(M, Z);
   }
   __syncthreads();
+  if (MOMENTS)
+    for (int t = c0 + threadIdx.x; t < t_lim; t += kThreads) g_row[t] = g_sm[t - c0];
   for (int n = threadIdx.x; n < NB * 32; n += kThreads) {
     float M = kNegInit;
 #pragma unroll
@@ -319,6 +322,11 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   float* u_row = a.u + (int64_t)unit * a.d.t_stride;
   float* g_row = a.g ? a.g + (int64_t)unit * a.d.t_stride : nullptr;
   const float c2 = a.c2;
+  // u (and the last-query g) of the chunk are collected in LDS and written once at the end: stores
+  // scattered through the sweep cost the key stream 7 % of its rate
+  constexpr bool kBufG = MODE == MODE_LAST && NB <= 7;  // (8 column blocks: LDS is needed for the query window)
+  __shared__ float u_sm[kScoreChunk];
+  __shared__ float g_sm[kBufG ? kScoreChunk : 1];
   float v_part = 0.f;  // this lane's share of sum(max(u,0)+eps): at most 8 terms
   auto block = [&](const uint4 (&av)[Tr<BF16, HD>::kAVecs], int t0) __attribute__((always_inline)) {
     float pu[16], pg[16], pm[16];
@@ -365,8 +373,11 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
     if (MODE == MODE_MEAN) rg = ru;
     if (MODE == MODE_LAST) rg = reduce16_over32(pg, c);
     if ((c & 1) == 0 && t < T) {
-      u_row[t] = ru;
-      if (g_row) g_row[t] = rg;
+      u_sm[t - c0] = ru;
+      if (kBufG)
+        g_sm[t - c0] = rg;
+      else if (g_row)
+        g_row[t] = rg;
       v_part += fmaxf(ru, 0.f) + a.eps;
     }
   };
@@ -379,6 +390,11 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
     if (t0 + 128 >= t_lim) break;
     if (t0 + 256 < t_lim) load_a<BF16, HD>(a, l, b, h, t0 + 256, T, lane, av0, blk, c0);
     block(av1, t0 + 128);
+  }
+  __syncthreads();
+  for (int t = c0 + threadIdx.x; t < t_lim; t += kThreads) {
+    u_row[t] = u_sm[t - c0];
+    if (kBufG) g_row[t] = g_sm[t - c0];
   }
   if (a.vc_part) {  // chunk sums of max(u,0)+eps in a fixed order: lanes, then waves
     __shared__ double vc_sm[4];
