@@ -33,10 +33,11 @@ static int pick_score_chunk(size_t units, int t_max) {
     return (v >= 256 && v <= kScoreChunk && v % 256 == 0) ? v : 0;
   }();
   if (forced) return forced;
-  // measured on 256 units: 2048 tokens are best from 16k positions on, 1024 below (2176 positions:
-  // 0.208 ms per step against 0.229); 512 and 256 lose to the per-workgroup load of the query window
+  // measured on 256 units: 4096 tokens at 32k positions (1.060 ms per step against 1.077 with 2048 and
+  // 1.13 with 1024), 1024 at 2176 positions (0.208 against 0.229 with 2048); 512 and 256 lose to the
+  // per-workgroup load of the query window
   int chunk = kScoreChunk;
-  if (chunk > 1024 && units * (size_t)div_up(t_max, chunk) < 2048) chunk = 1024;
+  while (chunk > 1024 && units * (size_t)div_up(t_max, chunk) < 2048) chunk /= 2;
   return chunk;
 }
 

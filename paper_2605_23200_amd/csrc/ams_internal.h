@@ -53,7 +53,7 @@ __device__ __forceinline__ int seq_len(const Dims& d, const int32_t* seq_lens, i
 }
 
 #ifndef AMS_SCORE_CHUNK
-#define AMS_SCORE_CHUNK 2048
+#define AMS_SCORE_CHUNK 4096
 #endif
 constexpr int kScoreChunk = AMS_SCORE_CHUNK;  // most tokens per workgroup of the scoring kernels
 constexpr int kChunk = 4096;       // positions per workgroup of the mass / prefix kernels
