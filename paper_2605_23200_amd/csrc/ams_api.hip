@@ -26,7 +26,7 @@ static int padded_queries(int n, bool bf16) {
 
 // Tokens per workgroup of the scoring sweeps: as many as possible (the query window is loaded once per
 // workgroup), but few enough that the launch has a couple of thousand workgroups to fill 256 CUs.
-static int pick_score_chunk(size_t units, int t_max) {
+static int pick_score_chunk(size_t units, int t_max, bool paged) {
   static const int forced = [] {
     const char* e = getenv("AMS_SCORE_CHUNK_TOKENS");  // tuning aid; a multiple of 256 up to kScoreChunk
     const int v = e ? atoi(e) : 0;
@@ -36,7 +36,10 @@ static int pick_score_chunk(size_t units, int t_max) {
   // measured on 256 units: 4096 tokens at 32k positions (1.060 ms per step against 1.077 with 2048 and
   // 1.13 with 1024), 1024 at 2176 positions (0.208 against 0.229 with 2048); 512 and 256 lose to the
   // per-workgroup load of the query window
-  int chunk = kScoreChunk;
+  // paged pools (16384 ragged units of up to 16384 positions): 26.4 ms per step with 1024 against 27.3 with
+  // 2048, 30.8 with 4096 and 28.0 with 512 -- the eight heads of a (layer, sequence, chunk) share each 2 KB
+  // stripe of the pool, and short chunks keep their workgroups close together in time
+  int chunk = paged ? 1024 : kScoreChunk;
   while (chunk > 1024 && units * (size_t)div_up(t_max, chunk) < 2048) chunk /= 2;
   return chunk;
 }
@@ -44,12 +47,15 @@ static int pick_score_chunk(size_t units, int t_max) {
 WsLayout ws_layout(const ams_params* p) {
   WsLayout w;
   const size_t units = (size_t)p->n_layers * p->batch * p->n_kv_heads;
-  w.score_chunk = pick_score_chunk(units, p->t_max);
+  w.score_chunk = pick_score_chunk(units, p->t_max, false);
+  w.score_chunk_paged = pick_score_chunk(units, p->t_max, true);
   w.n_chunks = div_up(p->t_max, w.score_chunk);
+  w.n_chunks_paged = div_up(p->t_max, w.score_chunk_paged);
+  const size_t nc_cap = (size_t)max(w.n_chunks, w.n_chunks_paged);  // the parameters do not say which layout comes
   w.n_pad = padded_queries(p->group * p->window, p->kv_dtype == AMS_BF16);
   const size_t vec = align256(units * (size_t)p->t_stride * sizeof(float));
   size_t o = 0;
-  w.part_stats = o; o += align256(units * (w.n_chunks + 1) * (size_t)w.n_pad * sizeof(float2));
+  w.part_stats = o; o += align256(units * (nc_cap + 1) * (size_t)w.n_pad * sizeof(float2));
   w.fin_stats = o;  o += align256(units * (size_t)w.n_pad * sizeof(float4));
   w.u = o;          o += vec;
   w.g = o;          o += vec;
@@ -57,7 +63,7 @@ WsLayout ws_layout(const ams_params* p) {
   w.bounds = o;     o += align256(units * (size_t)(p->n_segments + 1) * sizeof(int32_t));
   w.seg_mass = o;   o += align256(units * (size_t)p->n_segments * sizeof(float));
   w.quota = o;      o += align256(units * (size_t)p->n_segments * sizeof(int32_t));
-  w.kbar = o;       o += align256(units * w.n_chunks * (size_t)p->head_dim * sizeof(double));
+  w.kbar = o;       o += align256(units * nc_cap * (size_t)p->head_dim * sizeof(double));
   w.fused = o;      o += align256(fused_score_ws_bytes((int64_t)units, p->t_max, w.n_pad, p->batch));
   w.n_chunks4k = div_up(p->t_max, kChunk);
   w.vc_part = o;    o += align256(units * (size_t)div_up(p->t_max, 128) * 2 * sizeof(double));  // finest producer: 256 positions per entry

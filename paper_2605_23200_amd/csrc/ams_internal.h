@@ -71,7 +71,8 @@ inline int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 struct WsLayout {
   size_t part_stats, fin_stats, u, g, m_used, bounds, seg_mass, quota, kbar, fused, vc_part, mpart, cpre, flags, csum, total;
   int n_chunks, n_pad;
-  int score_chunk;  // tokens per workgroup of the scoring kernels for these parameters
+  int score_chunk;  // tokens per workgroup of the scoring kernels for these parameters, dense cache
+  int score_chunk_paged, n_chunks_paged;  // the same for a paged cache
   int n_chunks4k;  // chunks of kChunk positions per unit
   int n_words;     // 32-position words of the kept-set bitmap per unit
 };

@@ -448,13 +448,24 @@ __global__ __launch_bounds__(kThreads) void keysum_kernel(ScoreArgs a, double* k
   double s[EPC];
 #pragma unroll
   for (int e = 0; e < EPC; ++e) s[e] = 0.0;
-  for (int t = c0 + r0; t < min(T, c0 + a.chunk); t += RPI) {
-    const uint4 v = *(const uint4*)(kv_row(a.k, l, b, h, t) + col * 16);
-    float x[8];
-    int n;
-    widen8<BF16>(v, x, n);
+  // four rows per lane in flight (a row past the end re-reads the last one and is not added)
+  constexpr int kRows = 4;
+  const int t_end = min(T, c0 + a.chunk);
+  for (int tb = c0 + r0; tb < t_end; tb += kRows * RPI) {
+    uint4 v[kRows];
 #pragma unroll
-    for (int e = 0; e < EPC; ++e) s[e] += (double)x[e];
+    for (int j = 0; j < kRows; ++j)
+      v[j] = *(const uint4*)(kv_row(a.k, l, b, h, min(tb + j * RPI, T - 1)) + col * 16);
+#pragma unroll
+    for (int j = 0; j < kRows; ++j) {
+      float x[8];
+      int n;
+      widen8<BF16>(v[j], x, n);
+      if (tb + j * RPI < t_end) {
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) s[e] += (double)x[e];
+      }
+    }
   }
 #pragma unroll
   for (int e = 0; e < EPC; ++e) sm[threadIdx.x][e] = s[e];
@@ -498,28 +509,35 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   float kb[EPC];  // this lane's channels of the mean key
 #pragma unroll
   for (int e = 0; e < EPC; ++e) kb[e] = (float)kbar[col * EPC + e];
-  for (int tb = c0; tb < min(T, c0 + a.chunk); tb += RPI) {
-    const int t = tb + r0;
-    // a row's 128 products are summed in fp32 (8 per lane, then 16 or 32 lanes); the ratio is formed in double
-    float dot = 0.f, nk = 0.f;
-    if (t < T) {
-      const uint4 v = *(const uint4*)(kv_row(a.k, l, b, h, t) + col * 16);
+  // four rows per lane in flight: the loads are unconditional (a row past the end re-reads the last one)
+  constexpr int kRows = 4;
+  const int t_end = min(T, c0 + a.chunk);
+  for (int tb = c0; tb < t_end; tb += kRows * RPI) {
+    uint4 v[kRows];
+#pragma unroll
+    for (int j = 0; j < kRows; ++j)
+      v[j] = *(const uint4*)(kv_row(a.k, l, b, h, min(tb + j * RPI + r0, T - 1)) + col * 16);
+#pragma unroll
+    for (int j = 0; j < kRows; ++j) {
+      const int t = tb + j * RPI + r0;
+      // a row's 128 products are summed in fp32 (8 per lane, then 16 or 32 lanes); the ratio is formed in double
+      float dot = 0.f, nk = 0.f;
       float x[8];
       int n;
-      widen8<BF16>(v, x, n);
+      widen8<BF16>(v[j], x, n);
 #pragma unroll
       for (int e = 0; e < EPC; ++e) {
         dot = __builtin_fmaf(x[e], kb[e], dot);
         nk = __builtin_fmaf(x[e], x[e], nk);
       }
-    }
-    // the CPR lanes of a row are consecutive lanes of one wave
+      // the CPR lanes of a row are consecutive lanes of one wave
 #pragma unroll
-    for (int o = CPR / 2; o >= 1; o >>= 1) {
-      dot += __shfl_xor(dot, o);
-      nk += __shfl_xor(nk, o);
+      for (int o = CPR / 2; o >= 1; o >>= 1) {
+        dot += __shfl_xor(dot, o);
+        nk += __shfl_xor(nk, o);
+      }
+      if (col == 0 && t < t_end) row_sums[t - c0] = make_float2(dot, nk);
     }
-    if (col == 0 && t < T) row_sums[t - c0] = make_float2(dot, nk);
   }
   __syncthreads();
   // one token per thread for the ratio, so that every lane works
@@ -737,8 +755,9 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
   a.part = (float2*)(ws + wl.part_stats);
   a.fin = (float4*)(ws + wl.fin_stats);
   a.u = u;
-  a.n_chunks = wl.n_chunks;
-  a.chunk = wl.score_chunk;
+  const bool paged = k.layout != AMS_LAYOUT_DENSE;
+  a.n_chunks = paged ? wl.n_chunks_paged : wl.n_chunks;
+  a.chunk = paged ? wl.score_chunk_paged : wl.score_chunk;
   a.n_pad = wl.n_pad;
   a.inv_sqrt_d = (float)(1.0 / sqrt((double)d.D));
   a.c2 = (float)(1.4426950408889634 / sqrt((double)d.D));
@@ -763,8 +782,8 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
       e = bf16 ? run_by_nb<true, 64>(a, nb, mode, s) : run_by_nb<false, 64>(a, nb, mode, s);
     else
       e = bf16 ? run_by_nb<true, 128>(a, nb, mode, s) : run_by_nb<false, 128>(a, nb, mode, s);
-    vc_stride = wl.n_chunks;
-    vc_tokens = wl.score_chunk;
+    vc_stride = a.n_chunks;
+    vc_tokens = a.chunk;
   }
   if (e != hipSuccess) return e;
   if (vc) {
