@@ -548,3 +548,34 @@ def test_score_extreme_logits(oracle, dtype, scale, rtol):
             assert_close_rel(g_h[i], go, rtol=rtol, atol=1e-30, what=f"g unit {i}")
             if scale == 0.0:
                 np.testing.assert_allclose(u_h[i], 1.0 / w.T, rtol=1e-6)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("where", [700, 2999, 40])
+def test_score_late_dominant_key(oracle, dtype, where):
+    """One key far along a chunk is a multiple of a query, so that its logit sits tens of units above
+    everything seen before it: the running maximum of the first sweep jumps in the middle of a wave's
+    blocks and every earlier partial sum is rescaled by a factor near zero.  Other units keep ordinary keys."""
+    w = _workload(dtype, 4, 16, 3000)
+    host = inputs.dense_cache(w, n_threads=4)
+    l, b, h = unit_list(w)[1]
+    if dtype == "bf16":
+        q0 = inputs.bf16_bits_to_f32(host["Q"][l, b, h * w.G, 0])
+        host["K"][l, b, h, where] = inputs.to_bf16_bits((4.0 * q0).astype(np.float32))
+    else:
+        host["K"][l, b, h, where] = 4.0 * host["Q"][l, b, h * w.G, 0]
+    for sc_name in ("mean", "last"):
+        p = params_for(w, scorer=SCORERS[sc_name])
+        ws = workspace(p)
+        K, Q = to_dev(host["K"]), to_dev(host["Q"])
+        u = torch.zeros((p.units, w.T), device=DEV)
+        g = torch.zeros((p.units, w.T), device=DEV)
+        B.ams_score(p, B.dense_view(K, None), to_dev(host["seq_lens"]), Q, u, g, ws)
+        torch.cuda.synchronize()
+        u_h, g_h = to_host(u), to_host(g)
+        assert np.isfinite(u_h).all() and np.isfinite(g_h).all()
+        for i, (l2, b2, h2) in enumerate(unit_list(w)):
+            uo, go = oracle.score(host["Q"][l2, b2, h2 * w.G:(h2 + 1) * w.G].reshape(-1, w.D), host["K"][l2, b2, h2],
+                                  w.G, w.W, SCORERS[sc_name])
+            assert_close_rel(u_h[i], uo, rtol=1e-5, atol=1e-30, what=f"u unit {i}")
+            assert_close_rel(g_h[i], go, rtol=1e-5, atol=1e-30, what=f"g unit {i}")
