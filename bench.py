@@ -48,6 +48,7 @@ def kernel_bytes(label, w, lens=None):
         "score_usage": tok * D * e + 4 * tok,             # K stream + u
         "score_reduce": 0,
         "mass_ema": 4 * tok * 4,                          # u, credit in; credit, m_used out
+        "unit_mass": 4 * tok * 4,                         # the same, with the scan and the quotas in the same launch
         "segment_scan": 4 * tok,                          # m_used in
         "quota": 0,
         "select": 4 * tok + 4 * kept,                     # g in, idx out

@@ -23,6 +23,7 @@
 // P(last of chunk c-1) == C[c] bit for bit and the chain of "first position that reaches k/S"
 // tests is consistent across chunks.  Everything that feeds a comparison is double.
 #include "ams_internal.h"
+#include "quota.h"
 
 namespace ams {
 namespace {
@@ -112,26 +113,28 @@ __device__ __forceinline__ double ordered_sum(const double* p, int n, double2* s
 }
 
 // kPer consecutive fp32 of a row: 16-byte accesses when the row allows it.
-__device__ __forceinline__ void load_run(const float* row, int j0, int T, bool vec, float (&x)[kPer], float fill) {
-  if (vec && j0 + kPer <= T) {
+template <int N>
+__device__ __forceinline__ void load_run(const float* row, int j0, int T, bool vec, float (&x)[N], float fill) {
+  if (vec && j0 + N <= T) {
 #pragma unroll
-    for (int q = 0; q < kPer / 4; ++q) {
+    for (int q = 0; q < N / 4; ++q) {
       const float4 v = *reinterpret_cast<const float4*>(row + j0 + 4 * q);
       x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) x[i] = (j0 + i < T) ? row[j0 + i] : fill;
+    for (int i = 0; i < N; ++i) x[i] = (j0 + i < T) ? row[j0 + i] : fill;
   }
 }
-__device__ __forceinline__ void store_run(float* row, int j0, int T, bool vec, const float (&x)[kPer]) {
-  if (vec && j0 + kPer <= T) {
+template <int N>
+__device__ __forceinline__ void store_run(float* row, int j0, int T, bool vec, const float (&x)[N]) {
+  if (vec && j0 + N <= T) {
 #pragma unroll
-    for (int q = 0; q < kPer / 4; ++q)
+    for (int q = 0; q < N / 4; ++q)
       *reinterpret_cast<float4*>(row + j0 + 4 * q) = make_float4(x[4 * q], x[4 * q + 1], x[4 * q + 2], x[4 * q + 3]);
   } else {
 #pragma unroll
-    for (int i = 0; i < kPer; ++i)
+    for (int i = 0; i < N; ++i)
       if (j0 + i < T) row[j0 + i] = x[i];
   }
 }
@@ -423,6 +426,153 @@ __global__ __launch_bounds__(64) void segment_mass_kernel(MsArgs a, const float*
   if (threadIdx.x == 0) seg_mass_all[(int64_t)unit * a.S + seg] = (float)s;
 }
 
+// Eq. (1), the EMA, the prefix sum with its cuts, the segment masses and the quotas of one unit in ONE
+// workgroup of 1024 threads (up to 64 segments, thresholds k/S, no pooling).  The unit is walked in
+// groups of 1024*PER positions; inside a group thread i owns the PER consecutive positions from i*PER
+// on, so the running prefix is a serial sum per thread, a scan over the lanes, an ordered sum over the
+// 16 waves and the total of the groups before -- no chunk totals through memory, no second read of
+// m_used, and four kernel launches become one.  The next group's usage and credit are requested before
+// the current group is worked on.  The arithmetic per position, the thresholds and the quotas are those
+// of the kernels above.
+constexpr int kUnitBlock = 1024;
+constexpr int kUnitMaxSeg = 64;
+template <int PER>
+__global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const float* u_all, float* credit_all,
+                                                                float* m_used_all, float lambda, float beta,
+                                                                float eps_f, int budget, int q_min,
+                                                                float* seg_mass_all, int32_t* quota_all,
+                                                                int32_t* idx_all, int32_t* n_kept_all, int n_sink,
+                                                                int n_last, uint32_t* flags_all, int n_words) {
+  constexpr int kW = kUnitBlock / 64, kGroup = kUnitBlock * PER;
+  __shared__ double wave_tot[2][kW];
+  __shared__ double ends[2][kUnitBlock];
+  __shared__ double thr[kUnitMaxSeg + 1], cpre[kUnitMaxSeg + 1];
+  __shared__ int32_t bounds[kUnitMaxSeg + 1];
+  __shared__ float mass[kUnitMaxSeg];
+  __shared__ double2 sums;
+  const int unit = blockIdx.x, S = a.S;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = seq_len(a.d, a.seq_lens, b);
+  const float* u = u_all + (int64_t)unit * a.d.t_stride;
+  float* credit = credit_all + (int64_t)unit * a.d.t_stride;
+  float* m_used = m_used_all + (int64_t)unit * a.d.t_stride;
+  float ux[PER], cx[PER];
+  load_run(u, (int)threadIdx.x * PER, T, a.vec, ux, 0.f);  // in flight while the normalisers are summed
+  load_run(credit, (int)threadIdx.x * PER, T, a.vec, cx, 0.f);
+  for (int k = threadIdx.x; k <= S; k += kUnitBlock) {
+    bounds[k] = (k == 0) ? 0 : T;
+    cpre[k] = (k == 0) ? 0.0 : -1.0;
+    thr[k] = (double)k / (double)S;
+  }
+  const int nvc = (T + a.vc_tokens - 1) / a.vc_tokens;
+  const double2 zc = ordered_sum2(a.vc_part + (int64_t)unit * a.vc_stride, nvc, &sums);
+  const double Z = zc.x, c_old = zc.y;
+  const double lam = (double)lambda, bet = (double)beta, eps = (double)eps_f;
+  const double inv_z = 1.0 / Z, inv_csum = 1.0 / (lam * c_old + (1.0 - lam));
+  const double scale = (double)S;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  double C = 0.0;  // prefix at the end of the groups before
+  const int n_groups = (T + kGroup - 1) / kGroup;
+#pragma unroll 1
+  for (int r = 0; r < n_groups; ++r) {
+    const int j0 = r * kGroup + (int)threadIdx.x * PER, par = r & 1;
+    float un[PER], cn_next[PER];
+    if (r + 1 < n_groups) {
+      load_run(u, j0 + kGroup, T, a.vec, un, 0.f);
+      load_run(credit, j0 + kGroup, T, a.vec, cn_next, 0.f);
+    }
+    float mu[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      mu[i] = 0.f;
+      if (j0 + i < T) {
+        const float mc = (float)((fmax((double)ux[i], 0.0) + eps) * inv_z);
+        float cn = mc;
+        mu[i] = mc;  // lambda == 0: credit not used, the mass passes through unchanged
+        if (lambda != 0.f) {
+          cn = (float)(lam * (double)cx[i] + (1.0 - lam) * (double)mc);
+          mu[i] = (float)(bet * (double)mc + (1.0 - bet) * ((double)cn * inv_csum));
+        }
+        cx[i] = cn;
+      }
+    }
+    store_run(credit, j0, T, a.vec, cx);
+    store_run(m_used, j0, T, a.vec, mu);
+    // inclusive prefix: serial over the thread's run, scan over the lanes, ordered sum over the waves
+    double ts = 0.0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) ts += (double)mu[i];
+    double incl = ts;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const double v = __shfl_up(incl, o);
+      if (lane >= o) incl += v;
+    }
+    if (lane == 63) wave_tot[par][wave] = incl;
+    __syncthreads();
+    double off = C;
+    for (int w = 0; w < wave; ++w) off += wave_tot[par][w];
+    double run = off + (incl - ts);  // prefix of the position in front of this thread's run
+#pragma unroll
+    for (int i = 0; i < PER; ++i) run += (double)mu[i];
+    ends[par][threadIdx.x] = run;
+    __syncthreads();
+    const double prev_end = threadIdx.x > 0 ? ends[par][threadIdx.x - 1] : C;
+    C = ends[par][kUnitBlock - 1];
+    int f_prev = thresholds_reached(prev_end, S, thr, scale);
+    // most threads see no threshold between their neighbour's prefix and their own last one (the masses
+    // are not negative, so the prefix does not fall)
+    if (thresholds_reached(run, S, thr, scale) > f_prev) {
+      double P = prev_end;
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        P += (double)mu[i];
+        if (j0 + i < T) {
+          const int f_cur = thresholds_reached(P, S, thr, scale);
+          for (int k = f_prev + 1; k <= f_cur; ++k) {  // position j0+i is the first to reach k/S
+            atomicMin(&bounds[k], j0 + i + 1);
+            cpre[k] = P;
+          }
+          f_prev = max(f_prev, f_cur);
+        }
+      }
+    }
+    if (r + 1 < n_groups) {
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        ux[i] = un[i];
+        cx[i] = cn_next[i];
+      }
+    }
+  }
+  __syncthreads();
+  const double total = C;
+  if ((int)threadIdx.x < S) {
+    const int i = threadIdx.x;
+    const double lo = cpre[i] < 0.0 ? total : cpre[i];
+    const double hi = (i + 1 == S || cpre[i + 1] < 0.0) ? total : cpre[i + 1];
+    mass[i] = (float)(hi - lo);
+    seg_mass_all[(int64_t)unit * S + i] = mass[i];
+  }
+  if ((int)threadIdx.x <= S) a.bounds[(int64_t)unit * (S + 1) + threadIdx.x] = bounds[threadIdx.x];
+  // what the quota kernels do besides the quotas: the -1 tail of idx, the kept count, the cleared bitmap
+  // of the must-keep path; sinks and the recent suffix come out of the budget first
+  const int kept = min(budget, T);
+  const int sinks = min(n_sink, kept);
+  const int bud = kept - sinks - min(n_last, kept - sinks);
+  int32_t* idx = idx_all + (int64_t)unit * budget;
+  for (int j = kept + threadIdx.x; j < budget; j += kUnitBlock) idx[j] = -1;
+  if (threadIdx.x == 0) n_kept_all[unit] = kept;
+  if (flags_all)
+    for (int j = threadIdx.x; j < n_words; j += kUnitBlock) flags_all[(int64_t)unit * n_words + j] = 0u;
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    const int q = quota_wave(S, bud, q_min, bounds, mass);
+    if ((int)threadIdx.x < S) quota_all[(int64_t)unit * S + threadIdx.x] = q;
+  }
+}
+
 MsArgs make_args(const ams_params* p, const Dims& d, const int32_t* seq_lens, char* ws, const WsLayout& wl,
                  int32_t* bounds) {
   MsArgs a;
@@ -490,6 +640,51 @@ hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq
     prof_mark("segment_finalize", s);
     hipLaunchKernelGGL(segment_finalize_kernel, dim3(d.units), dim3(64), 0, s, a, seg_mass);
   }
+  return hipGetLastError();
+}
+
+// The fused step's mass / EMA / segmentation / quota stages in one launch, when the parameters allow it
+// (*ran tells): exactly-S thresholds, no pooling, at most 64 segments.
+hipError_t launch_unit_mass(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
+                            float* credit, float* m_used, int32_t* bounds, float* seg_mass, int32_t* quota,
+                            int32_t* idx, int32_t* n_kept, uint32_t* flags, int n_words, const VcInfo& vc,
+                            char* ws, const WsLayout& wl, hipStream_t s, bool* ran) {
+  *ran = false;
+  static const bool off = [] {
+    const char* e = getenv("AMS_UNIT_MASS");  // tuning aid: 0 keeps the chunked kernels
+    return e && e[0] == '0';
+  }();
+  if (off || p->seg_delta > 0.f || p->pool_kernel > 1 || p->n_segments > kUnitMaxSeg) return hipSuccess;
+  MsArgs a = make_args(p, d, seq_lens, ws, wl, bounds);
+  a.vec = d.t_stride % 4 == 0 && (((uintptr_t)u | (uintptr_t)credit | (uintptr_t)m_used) & 15) == 0;
+  if (vc.have) {  // left by the scorer
+    a.vc_stride = vc.stride;
+    a.vc_tokens = vc.tokens;
+  } else {
+    prof_mark("vc_sums", s);
+    hipLaunchKernelGGL(vc_sums_kernel, dim3(a.n_chunks, d.units), dim3(kBlock), 0, s, a, u, (const float*)credit,
+                       p->mass_eps);
+  }
+  const bool must = p->n_sink > 0 || p->n_last > 0;
+  if (must && !flags) return hipErrorInvalidValue;
+  prof_mark("unit_mass", s);
+  const dim3 grid(d.units), blk(kUnitBlock);
+#define AMS_UNIT_MASS_LAUNCH(PER)                                                                              \
+  hipLaunchKernelGGL((unit_mass_kernel<PER>), grid, blk, 0, s, a, u, credit, m_used, p->ema_lambda, p->ema_beta, \
+                     p->mass_eps, p->budget, p->q_min, seg_mass, quota, idx, n_kept, p->n_sink, p->n_last,       \
+                     must ? flags : nullptr, n_words)
+  static const int per = [] {
+    const char* e = getenv("AMS_UNIT_MASS_PER");  // tuning aid: positions per thread and group (4, 8 or 16)
+    return e ? atoi(e) : 8;
+  }();
+  if (per == 4)
+    AMS_UNIT_MASS_LAUNCH(4);
+  else if (per == 16)
+    AMS_UNIT_MASS_LAUNCH(16);
+  else
+    AMS_UNIT_MASS_LAUNCH(8);
+#undef AMS_UNIT_MASS_LAUNCH
+  *ran = true;
   return hipGetLastError();
 }
 

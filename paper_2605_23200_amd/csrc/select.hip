@@ -14,78 +14,12 @@
 //                scores outside the set (another radix select, over the unset positions), and the
 //                ascending index list is read off the bitmap.
 #include "ams_internal.h"
+#include "quota.h"
 
 namespace ams {
 namespace {
 
 constexpr int kMaxSeg = 1024;
-
-__device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-  return v;
-}
-
-// Quotas for S <= 64: lane i owns segment i.  Sums of masses run in index order over the active
-// lanes and every share is rem * M_i / sum, the same operations in the same order as plain C.
-__device__ __forceinline__ int quota_wave(int S, int bud, int q_min, const int32_t* bounds, const float* mass) {
-  const int lane = threadIdx.x;
-  const bool valid = lane < S;
-  const int len = valid ? bounds[lane + 1] - bounds[lane] : 0;
-  const double mass_d = valid ? (double)mass[lane] : 0.0;
-  const int nonempty = __popcll(__ballot(len > 0));
-  int floor_q = q_min;
-  if (wave_sum(min(floor_q, len)) > bud) floor_q = nonempty > 0 ? bud / nonempty : 0;
-  const int lo = min(floor_q, len);
-  const int room = len - lo;
-  bool active = room > 0;
-  int quo = lo;
-  int rem = bud - wave_sum(lo);
-  double raw = 0.0;
-  // proportional shares; a segment whose share reaches its room is filled and leaves the pool
-  for (;;) {
-    const uint64_t act = __ballot(active);
-    const int n_active = __popcll(act);
-    if (n_active == 0 || rem <= 0) break;
-    double msum = 0.0;
-    for (uint64_t m = act; m; m &= m - 1) msum += __shfl(mass_d, __ffsll((long long)m) - 1);
-    if (active) raw = msum > 0.0 ? (double)rem * mass_d / msum : (double)rem / (double)n_active;
-    const bool sat = active && raw >= (double)room;
-    if (!__ballot(sat)) break;
-    rem -= wave_sum(sat ? room : 0);
-    if (sat) {
-      quo = len;
-      active = false;
-    }
-  }
-  if (rem > 0) {
-    double frac = -1.0;
-    int fl_i = 0;
-    if (active) {
-      const double fl = floor(raw);
-      frac = raw - fl;
-      fl_i = (int)fl;
-      quo += fl_i;
-    }
-    int left = rem - wave_sum(fl_i);
-    // one extra each, largest fractional part first, equal parts by lower segment index
-    while (left > 0) {
-      const bool can = active && quo < len;
-      const uint64_t cm = __ballot(can);
-      if (!cm) break;
-      int rank = 0;
-      for (uint64_t m = cm; m; m &= m - 1) {
-        const int j = __ffsll((long long)m) - 1;
-        const double fj = __shfl(frac, j);
-        if (fj > frac || (fj == frac && j < lane)) ++rank;
-      }
-      const bool take = can && rank < left;
-      if (take) ++quo;
-      left -= __popcll(__ballot(take));
-    }
-  }
-  return quo;
-}
 
 // What both quota kernels do before the quotas: segment masses from the raw output of the prefix-sum
 // kernel (cpre_all / mpart_all, optional: when given, the masses are formed and stored here instead of
@@ -805,13 +739,15 @@ __global__ __launch_bounds__(kFinBlock) void finalize_kernel(Dims d, const int32
 hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* g,
                          const int32_t* bounds, float* seg_mass, int32_t* quota, int32_t* idx,
                          int32_t* n_kept, const double* cpre, const double* mpart, int n_chunks,
-                         uint32_t* flags, int n_words, hipStream_t s) {
+                         uint32_t* flags, int n_words, hipStream_t s, bool quota_done) {
   const int S = p->n_segments;
   if (S > kMaxSeg) return hipErrorInvalidValue;
   const bool must = p->n_sink > 0 || p->n_last > 0;
   if (must && !flags) return hipErrorInvalidValue;
-  prof_mark("quota", s);
-  if (S <= 64)
+  if (!quota_done) prof_mark("quota", s);
+  if (quota_done) {
+    // quotas, the tail of idx, the kept count and the cleared bitmap are already in place
+  } else if (S <= 64)
     hipLaunchKernelGGL(quota_kernel, dim3(d.units), dim3(64), 0, s, d, seq_lens, S, p->budget, p->q_min,
                        bounds, seg_mass, quota, idx, n_kept, cpre, mpart, n_chunks, p->n_sink, p->n_last,
                        must ? flags : nullptr, n_words);
