@@ -396,6 +396,22 @@ def test_segmentation_as_printed_step(oracle, delta, l_min, l_max, pool):
     check_units(oracle, job, host, credit_before[:, :w.T], [0, w.units - 1])
 
 
+@pytest.mark.parametrize("S,pool,n_sink,n_last", [(8, 3, 0, 0), (16, 5, 4, 32), (100, 0, 0, 0), (200, 0, 4, 16)])
+def test_chunked_mass_kernels_step(oracle, S, pool, n_sink, n_last):
+    """Thresholds k/S with pooled usage, or with more than 64 segments: the fused step then runs the
+    chunked mass / prefix / quota kernels instead of the one-workgroup-per-unit kernel."""
+    w = inputs.CONFIGS[1].scaled(L=2, H=3, T=9000, budget=1024, S=S, n_spans=6, span_len=(32, 300),
+                                 n_sink=n_sink, n_last=n_last, pool_kernel=pool)
+    host = inputs.dense_cache(w, n_threads=4)
+    job = Job(w, host)
+    job.step()
+    check_properties_all_units(job)
+    check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), list(range(w.units)))
+    credit_before = to_host(job.credit).copy()
+    job.step()
+    check_units(oracle, job, host, credit_before[:, :w.T], [0, w.units - 1])
+
+
 @pytest.mark.parametrize("dtype,paged", [("bf16", False), ("f32", False), ("bf16", True)])
 def test_head_dim_64_step(oracle, dtype, paged):
     """Whole step on caches with 64 channels per head (rows of 128 / 256 bytes), dense and paged."""
