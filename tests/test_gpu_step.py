@@ -396,6 +396,34 @@ def test_segmentation_as_printed_step(oracle, delta, l_min, l_max, pool):
     check_units(oracle, job, host, credit_before[:, :w.T], [0, w.units - 1])
 
 
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("options", [{}, {"n_sink": 4, "n_last": 32, "causal": True}])
+def test_empty_and_tiny_sequences_in_a_batch(oracle, paged, options):
+    """A batch whose sequences hold 0, 1, 5, 31, 300 and 2049 positions (budget 256, window 32): the
+    empty one keeps nothing and writes nothing, the short ones keep everything, the rest match the oracle."""
+    lens = np.array([0, 1, 5, 31, 300, 2049], np.int32)
+    w = inputs.CONFIGS[2].scaled(L=1, H=2, B=len(lens), T=2049, T_min=2049, budget=256, S=8, n_spans=4,
+                                 span_len=(16, 200), paged=paged, **options)
+    host = inputs.dense_cache(w, n_threads=4)
+    host["seq_lens"][:] = lens
+    job = Job(w, host)
+    sentinel = 123.0
+    job.credit.fill_(0.0)
+    job.credit_dst.fill_(sentinel)
+    job.step()
+    torch.cuda.synchronize()
+    nk, idx, cdst = to_host(job.n_kept), to_host(job.idx), to_host(job.credit_dst)
+    for i, (l, b, h) in enumerate(unit_list(w)):
+        T = int(lens[b])
+        assert nk[i] == min(T, w.budget)
+        assert (idx[i, nk[i]:] == -1).all()
+        if T <= w.budget:
+            np.testing.assert_array_equal(idx[i, :T], np.arange(T))
+        assert (cdst[i, nk[i]:] == sentinel).all()               # nothing written beyond the kept count
+    full = [i for i, (l, b, h) in enumerate(unit_list(w)) if lens[b] > 0]
+    check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), full)
+
+
 @pytest.mark.parametrize("S,pool,n_sink,n_last", [(8, 3, 0, 0), (16, 5, 4, 32), (100, 0, 0, 0), (200, 0, 4, 16)])
 def test_chunked_mass_kernels_step(oracle, S, pool, n_sink, n_last):
     """Thresholds k/S with pooled usage, or with more than 64 segments: the fused step then runs the
