@@ -465,13 +465,44 @@ __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const f
     cpre[k] = (k == 0) ? 0.0 : -1.0;
     thr[k] = (double)k / (double)S;
   }
-  const int nvc = (T + a.vc_tokens - 1) / a.vc_tokens;
-  const double2 zc = ordered_sum2(a.vc_part + (int64_t)unit * a.vc_stride, nvc, &sums);
-  const double Z = zc.x, c_old = zc.y;
   const double lam = (double)lambda, bet = (double)beta, eps = (double)eps_f;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  double2 zc;
+  if (a.vc_part) {  // the scorer left the sums of max(u,0)+eps and of the old credit per chunk
+    const int nvc = (T + a.vc_tokens - 1) / a.vc_tokens;
+    zc = ordered_sum2(a.vc_part + (int64_t)unit * a.vc_stride, nvc, &sums);
+  } else {
+    // no sums from the scorer (causal window): one more walk over the unit, every thread its positions in
+    // order, then the lanes and the waves in a fixed order
+    double v = 0.0, c = 0.0;
+    for (int j = threadIdx.x * 4; j < T; j += kUnitBlock * 4) {
+      float ur[4], cr[4];
+      load_run(u, j, T, a.vec, ur, 0.f);
+      load_run(credit, j, T, a.vec, cr, 0.f);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (j + i < T) {
+          v += fmax((double)ur[i], 0.0) + eps;
+          c += (double)cr[i];
+        }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      v += __shfl_xor(v, o);
+      c += __shfl_xor(c, o);
+    }
+    if (lane == 0) ends[0][wave] = v, ends[1][wave] = c;
+    __syncthreads();
+    zc = make_double2(0.0, 0.0);
+    for (int w = 0; w < kW; ++w) {
+      zc.x += ends[0][w];
+      zc.y += ends[1][w];
+    }
+    __syncthreads();  // ends is used again below
+  }
+  const double Z = zc.x, c_old = zc.y;
   const double inv_z = 1.0 / Z, inv_csum = 1.0 / (lam * c_old + (1.0 - lam));
   const double scale = (double)S;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   double C = 0.0;  // prefix at the end of the groups before
   const int n_groups = (T + kGroup - 1) / kGroup;
 #pragma unroll 1
@@ -661,9 +692,7 @@ hipError_t launch_unit_mass(const ams_params* p, const Dims& d, const int32_t* s
     a.vc_stride = vc.stride;
     a.vc_tokens = vc.tokens;
   } else {
-    prof_mark("vc_sums", s);
-    hipLaunchKernelGGL(vc_sums_kernel, dim3(a.n_chunks, d.units), dim3(kBlock), 0, s, a, u, (const float*)credit,
-                       p->mass_eps);
+    a.vc_part = nullptr;  // the kernel sums for itself
   }
   const bool must = p->n_sink > 0 || p->n_last > 0;
   if (must && !flags) return hipErrorInvalidValue;
