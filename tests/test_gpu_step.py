@@ -293,6 +293,18 @@ def test_config3_long_context(oracle):
     check_units(oracle, job, host, zeros, [0, 1])
 
 
+def test_config3_full_size(oracle):
+    """Config 3 at full size (28 layers x 4 KV heads = 112 units of 131072 positions), the launch shapes
+    `bench.py --config 3` times: properties over every unit, element-by-element parity on two of them."""
+    w = inputs.CONFIGS[3]
+    host = inputs.dense_cache(w, n_threads=16)
+    job = Job(w, host)
+    job.step()
+    torch.cuda.synchronize()
+    check_properties_all_units(job)
+    check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), [5, w.units - 1])
+
+
 @pytest.mark.parametrize("scorer", ["last", "mean", "keydiff", "expected", "expected_vnorm"])
 def test_config4_scorer_sweep(oracle, scorer):
     """Config 4: scorer x S in {1,4,16,64} x budget in T/{8,16,32}; S = 1 must equal a global top-k."""
