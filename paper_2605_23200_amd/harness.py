@@ -81,7 +81,7 @@ class DeviceFilledPagedJob:
 
     def __init__(self, w: inputs.Workload, scorer: int = B.SCORER_MEAN_WINDOW, device: str = "cuda:0", seed: int = 0):
         assert w.paged
-        self.w, self.device = w, device
+        self.w, self.device, self.paged = w, device, True
         lens = inputs.seq_lens(w)
         self.lens_h = lens
         self.t_max = int(lens.max())
@@ -117,3 +117,6 @@ class DeviceFilledPagedJob:
     def step(self, stream=None):
         B.ams_compress_step(self.p, self.src, self.lens, self.Q, self.credit, self.dst, self.credit_dst,
                             self.idx, self.n_kept, self.ws, stream)
+
+    def intermediates(self) -> B.StepIntermediates:
+        return B.workspace_tensors(self.p, self.ws)

@@ -32,8 +32,10 @@ def _kv_out_host(job, host_dtype):
     return Ko, Vo
 
 
-def check_units(oracle, job, host, credit_before, units, scorer=B.SCORER_MEAN_WINDOW, check_scores=True):
-    """Full per-unit comparison of one finished step for the listed unit numbers."""
+def check_units(oracle, job, host, credit_before, units, scorer=B.SCORER_MEAN_WINDOW, check_scores=True,
+                unit_rows=None):
+    """Full per-unit comparison of one finished step for the listed unit numbers.  unit_rows (optional):
+    i -> (Q[N, D], K[T, D], V[T, D], K'[keep, D], V'[keep, D]) for jobs that have no host copy of the cache."""
     w = job.w
     inter = job.intermediates()
     ids = unit_list(w)
@@ -42,15 +44,21 @@ def check_units(oracle, job, host, credit_before, units, scorer=B.SCORER_MEAN_WI
     b_g, sm_g, q_g = (to_host(x[sel]) for x in (inter.bounds, inter.seg_mass, inter.quota))
     idx_g, nk_g = to_host(job.idx[sel]), to_host(job.n_kept[sel])
     cred_g, cdst_g = to_host(job.credit[sel]), to_host(job.credit_dst[sel])
-    Ko, Vo = _kv_out_host(job, host["K"].dtype)
+    if unit_rows is None:
+        Ko, Vo = _kv_out_host(job, host["K"].dtype)
     lens = host["seq_lens"]
     for j, i in enumerate(units):
         l, b, h = ids[i]
         T = int(lens[b])
-        Kh, Vh = host["K"][l, b, h, :T], host["V"][l, b, h, :T]
+        if unit_rows is None:
+            Qh = host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D)
+            Kh, Vh = host["K"][l, b, h, :T], host["V"][l, b, h, :T]
+            Ko_i, Vo_i = Ko[i], Vo[i]
+        else:
+            Qh, Kh, Vh, Ko_i, Vo_i = unit_rows(i)
         if check_scores:
             vnorm = scorer == B.SCORER_EXPECTED_VNORM
-            uo, go = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), Kh, w.G, w.W,
+            uo, go = oracle.score(Qh, Kh, w.G, w.W,
                                   B.SCORER_EXPECTED if vnorm else scorer, causal=w.causal)
             if vnorm:
                 go = oracle.value_weight(go, Vh, 1e-2)
@@ -77,8 +85,8 @@ def check_units(oracle, job, host, credit_before, units, scorer=B.SCORER_MEAN_WI
         assert nk_g[j] == n == len(i_o)
         np.testing.assert_array_equal(idx_g[j, :n], i_o, err_msg=f"idx unit {i}")
         assert (idx_g[j, n:] == -1).all()
-        np.testing.assert_array_equal(Ko[i, :n], Kh[i_o], err_msg=f"K' unit {i}")
-        np.testing.assert_array_equal(Vo[i, :n], Vh[i_o], err_msg=f"V' unit {i}")
+        np.testing.assert_array_equal(Ko_i[:n], Kh[i_o], err_msg=f"K' unit {i}")
+        np.testing.assert_array_equal(Vo_i[:n], Vh[i_o], err_msg=f"V' unit {i}")
         np.testing.assert_array_equal(cdst_g[j, :n], cred_g[j, i_o], err_msg=f"credit' unit {i}")
 
 
@@ -279,6 +287,42 @@ def test_config2_paged_ragged(oracle):
         p = np.arange(T)
         slots = job.src_table_h[b, p // 16].astype(np.int64) * 16 + p % 16
         np.testing.assert_array_equal(Kp[0, slots].transpose(1, 0, 2), host["K"][0, b, :, :T])
+
+
+def test_config2_full_size(oracle):
+    """Config 2 at full size (32 layers x 64 sequences x 8 KV heads = 16384 ragged units in the paged layout,
+    about 95 GB on the device), the launch shapes `bench.py --config 2` times.  The values are drawn on the
+    device, so the rows of the sampled units are read back through the block tables for the oracle."""
+    from paper_2605_23200_amd.harness import DeviceFilledPagedJob
+    w = inputs.CONFIGS[2]
+    job = DeviceFilledPagedJob(w)
+    job.step()
+    torch.cuda.synchronize()
+    check_properties_all_units(job)
+    lens = job.lens_h
+    ids = unit_list(w)
+    src_t, dst_t = job.src_table.long(), job.dst_table.long()
+
+    def rows(i):
+        l, b, h = ids[i]
+        T = int(lens[b])
+        p = torch.arange(T, device=job.device)
+        slots = src_t[b, p // 16] * 16 + p % 16
+        j = torch.arange(job.keep, device=job.device)
+        dslots = dst_t[b, j // 16] * 16 + j % 16
+        Q = to_host(job.Q[l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D).view(torch.int16), np.uint16)
+        return (Q, to_host(job.K[l, slots, h].view(torch.int16), np.uint16),
+                to_host(job.V[l, slots, h].view(torch.int16), np.uint16),
+                to_host(job.K[l, dslots, h].view(torch.int16), np.uint16),
+                to_host(job.V[l, dslots, h].view(torch.int16), np.uint16))
+
+    shortest, longest = int(np.argmin(lens)), int(np.argmax(lens))
+    sample = [shortest * w.H + 1, 9 * w.B * w.H + longest * w.H + 6, w.units - 1]
+    class ZeroCredit:  # credit_before[i, :T] without a [units, T] array of zeros
+        def __getitem__(self, key):
+            return np.zeros(job.t_max, np.float32)[key[1]]
+
+    check_units(oracle, job, {"seq_lens": lens}, ZeroCredit(), sample, unit_rows=rows)
 
 
 def test_config3_long_context(oracle):
