@@ -22,6 +22,8 @@
 // p_local the in-chunk scan; a chunk total IS p_local of the chunk's last position, so
 // P(last of chunk c-1) == C[c] bit for bit and the chain of "first position that reaches k/S"
 // tests is consistent across chunks.  Everything that feeds a comparison is double.
+#include <type_traits>
+
 #include "ams_internal.h"
 #include "quota.h"
 
@@ -427,16 +429,49 @@ __global__ __launch_bounds__(64) void segment_mass_kernel(MsArgs a, const float*
 }
 
 // Eq. (1), the EMA, the prefix sum with its cuts, the segment masses and the quotas of one unit in ONE
-// workgroup of 1024 threads (up to 64 segments, thresholds k/S, no pooling).  The unit is walked in
-// groups of 1024*PER positions; inside a group thread i owns the PER consecutive positions from i*PER
-// on, so the running prefix is a serial sum per thread, a scan over the lanes, an ordered sum over the
-// 16 waves and the total of the groups before -- no chunk totals through memory, no second read of
-// m_used, and four kernel launches become one.  The next group's usage and credit are requested before
-// the current group is worked on.  The arithmetic per position, the thresholds and the quotas are those
-// of the kernels above.
+// workgroup of 1024 threads.  The unit is walked in groups of 1024*PER positions; inside a group thread
+// i owns the PER consecutive positions from i*PER on, so the running prefix is a serial sum per thread,
+// a scan over the lanes, an ordered sum over the 16 waves and the total of the groups before -- no
+// chunk totals through memory, no second read of m_used, and the launches of the chunked kernels above
+// become one.  The next group's usage and credit are requested before the current group is worked on.
+// The arithmetic per position, the thresholds, the split / merge pass and the quotas are those of the
+// kernels above.
+//   GENERAL = false: thresholds k/S, at most 64 segments, no pooling (the headline configuration).
+//   GENERAL = true:  also thresholds k*Delta with the split / merge pass, pooled usage, up to 1024
+//                    segments; needs more LDS (the pooling tile, the quota scratch).
 constexpr int kUnitBlock = 1024;
 constexpr int kUnitMaxSeg = 64;
-template <int PER>
+
+// Pooled usage of one group of positions (see pool_run): the group's scores and r more on either side are
+// staged in LDS, consecutive threads then pool consecutive positions (no bank conflicts), store the result
+// (rounded to fp32 like a stored intermediate) to out[] and add max(pooled, 0) + eps to v.  Ends with a
+// barrier, so that the tile can be refilled.
+template <int GROUP>
+__device__ __forceinline__ void pool_group(const float* u, float* out, int g0, int T, int r, float* tile,
+                                           double eps, double& v) {
+  const int first = g0 - r;  // position of tile[0]
+  for (int e = threadIdx.x; e < GROUP + 2 * r; e += kUnitBlock) {
+    const int t = first + e;
+    tile[e] = (t >= 0 && t < T) ? u[t] : 0.f;
+  }
+  __syncthreads();
+  const double inv_full = 1.0 / (double)(2 * r + 1);
+  for (int e = threadIdx.x; e < GROUP; e += kUnitBlock) {
+    const int t = g0 + e;
+    if (t < T) {
+      const int lo = max(0, t - r), hi = min(T - 1, t + r);
+      double sum = 0.0;
+      for (int j = lo; j <= hi; ++j) sum += (double)tile[j - first];
+      const int n = hi - lo + 1;
+      const float p = (float)(n == 2 * r + 1 ? sum * inv_full : sum / (double)n);
+      out[t] = p;
+      v += fmax((double)p, 0.0) + eps;
+    }
+  }
+  __syncthreads();
+}
+
+template <int PER, bool GENERAL>
 __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const float* u_all, float* credit_all,
                                                                 float* m_used_all, float lambda, float beta,
                                                                 float eps_f, int budget, int q_min,
@@ -444,47 +479,77 @@ __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const f
                                                                 int32_t* idx_all, int32_t* n_kept_all, int n_sink,
                                                                 int n_last, uint32_t* flags_all, int n_words) {
   constexpr int kW = kUnitBlock / 64, kGroup = kUnitBlock * PER;
+  constexpr int kCap = GENERAL ? kMaxSegments : kUnitMaxSeg;
   __shared__ double wave_tot[2][kW];
   __shared__ double ends[2][kUnitBlock];
-  __shared__ double thr[kUnitMaxSeg + 1], cpre[kUnitMaxSeg + 1];
-  __shared__ int32_t bounds[kUnitMaxSeg + 1];
-  __shared__ float mass[kUnitMaxSeg];
+  __shared__ double thr[kCap + 1], cpre[kCap + 1];
+  __shared__ int32_t bounds[kCap + 1];
+  __shared__ float mass[kCap];
   __shared__ double2 sums;
+  __shared__ float tile[GENERAL ? kGroup + 2 * kMaxPoolR : 1];
+  __shared__ int32_t reseg[GENERAL ? kCap + 1 : 1];
+  __shared__ int n_reseg;
+  // Delta mode on caches of up to kEndGroups groups: the prefix at the end of every thread's run, from which
+  // the mass of a segment that the split / merge pass has moved follows without another sum over its positions
+  constexpr int kEndGroups = 4;
+  __shared__ double ends_all[GENERAL ? kEndGroups * kUnitBlock : 1];
+  __shared__ typename std::conditional<GENERAL, QuotaScratch, int>::type qs;
   const int unit = blockIdx.x, S = a.S;
+  const int K = GENERAL ? a.K : S;  // initial segments: thresholds k = 1 .. K-1
+  const bool delta_mode = GENERAL && a.delta > 0.0;
+  const int pool_r = GENERAL ? a.pool_r : 0;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T = seq_len(a.d, a.seq_lens, b);
   const float* u = u_all + (int64_t)unit * a.d.t_stride;
   float* credit = credit_all + (int64_t)unit * a.d.t_stride;
   float* m_used = m_used_all + (int64_t)unit * a.d.t_stride;
+  const int n_groups = (T + kGroup - 1) / kGroup;
+  // with pooling, the pooled usage passes through the m_used row: written while the normalisers are summed,
+  // read back (and overwritten by m_used proper) in the main walk
+  const float* u_src = pool_r > 0 ? m_used : u;
   float ux[PER], cx[PER];
-  load_run(u, (int)threadIdx.x * PER, T, a.vec, ux, 0.f);  // in flight while the normalisers are summed
+  if (pool_r == 0) load_run(u, (int)threadIdx.x * PER, T, a.vec, ux, 0.f);  // in flight while the normalisers are summed
   load_run(credit, (int)threadIdx.x * PER, T, a.vec, cx, 0.f);
   for (int k = threadIdx.x; k <= S; k += kUnitBlock) {
     bounds[k] = (k == 0) ? 0 : T;
     cpre[k] = (k == 0) ? 0.0 : -1.0;
-    thr[k] = (double)k / (double)S;
   }
+  for (int k = threadIdx.x; k <= K; k += kUnitBlock) thr[k] = delta_mode ? (double)k * a.delta : (double)k / (double)S;
   const double lam = (double)lambda, bet = (double)beta, eps = (double)eps_f;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   double2 zc;
-  if (a.vc_part) {  // the scorer left the sums of max(u,0)+eps and of the old credit per chunk
+  if (a.vc_part && pool_r == 0) {  // the scorer left the sums of max(u,0)+eps and of the old credit per chunk
     const int nvc = (T + a.vc_tokens - 1) / a.vc_tokens;
     zc = ordered_sum2(a.vc_part + (int64_t)unit * a.vc_stride, nvc, &sums);
   } else {
-    // no sums from the scorer (causal window): one more walk over the unit, every thread its positions in
-    // order, then the lanes and the waves in a fixed order
+    // no usable sums from the scorer (causal window, pooled usage): one more walk over the unit, every
+    // thread its positions in order, then the lanes and the waves in a fixed order
     double v = 0.0, c = 0.0;
-    for (int j = threadIdx.x * 4; j < T; j += kUnitBlock * 4) {
-      float ur[4], cr[4];
-      load_run(u, j, T, a.vec, ur, 0.f);
-      load_run(credit, j, T, a.vec, cr, 0.f);
+    if (pool_r > 0) {
+      if constexpr (GENERAL) {
+#pragma unroll 1
+        for (int r = 0; r < n_groups; ++r) pool_group<kGroup>(u, m_used, r * kGroup, T, pool_r, tile, eps, v);
+        for (int j = threadIdx.x * 4; j < T; j += kUnitBlock * 4) {
+          float cr[4];
+          load_run(credit, j, T, a.vec, cr, 0.f);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (j + i < T) {
-          v += fmax((double)ur[i], 0.0) + eps;
-          c += (double)cr[i];
+          for (int i = 0; i < 4; ++i)
+            if (j + i < T) c += (double)cr[i];
         }
+      }
+    } else {
+      for (int j = threadIdx.x * 4; j < T; j += kUnitBlock * 4) {
+        float ur[4], cr[4];
+        load_run(u, j, T, a.vec, ur, 0.f);
+        load_run(credit, j, T, a.vec, cr, 0.f);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (j + i < T) {
+            v += fmax((double)ur[i], 0.0) + eps;
+            c += (double)cr[i];
+          }
+      }
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {
@@ -500,17 +565,17 @@ __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const f
     }
     __syncthreads();  // ends is used again below
   }
+  if (pool_r > 0) load_run(u_src, (int)threadIdx.x * PER, T, a.vec, ux, 0.f);
   const double Z = zc.x, c_old = zc.y;
   const double inv_z = 1.0 / Z, inv_csum = 1.0 / (lam * c_old + (1.0 - lam));
-  const double scale = (double)S;
+  const double scale = delta_mode ? 1.0 / a.delta : (double)S;
   double C = 0.0;  // prefix at the end of the groups before
-  const int n_groups = (T + kGroup - 1) / kGroup;
 #pragma unroll 1
   for (int r = 0; r < n_groups; ++r) {
     const int j0 = r * kGroup + (int)threadIdx.x * PER, par = r & 1;
     float un[PER], cn_next[PER];
     if (r + 1 < n_groups) {
-      load_run(u, j0 + kGroup, T, a.vec, un, 0.f);
+      load_run(u_src, j0 + kGroup, T, a.vec, un, 0.f);
       load_run(credit, j0 + kGroup, T, a.vec, cn_next, 0.f);
     }
     float mu[PER];
@@ -548,20 +613,22 @@ __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const f
 #pragma unroll
     for (int i = 0; i < PER; ++i) run += (double)mu[i];
     ends[par][threadIdx.x] = run;
+    if constexpr (GENERAL)
+      if (delta_mode && n_groups <= kEndGroups) ends_all[r * kUnitBlock + threadIdx.x] = run;
     __syncthreads();
     const double prev_end = threadIdx.x > 0 ? ends[par][threadIdx.x - 1] : C;
     C = ends[par][kUnitBlock - 1];
-    int f_prev = thresholds_reached(prev_end, S, thr, scale);
+    int f_prev = thresholds_reached(prev_end, K, thr, scale);
     // most threads see no threshold between their neighbour's prefix and their own last one (the masses
     // are not negative, so the prefix does not fall)
-    if (thresholds_reached(run, S, thr, scale) > f_prev) {
+    if (thresholds_reached(run, K, thr, scale) > f_prev) {
       double P = prev_end;
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
         P += (double)mu[i];
         if (j0 + i < T) {
-          const int f_cur = thresholds_reached(P, S, thr, scale);
-          for (int k = f_prev + 1; k <= f_cur; ++k) {  // position j0+i is the first to reach k/S
+          const int f_cur = thresholds_reached(P, K, thr, scale);
+          for (int k = f_prev + 1; k <= f_cur; ++k) {  // position j0+i is the first to reach threshold k
             atomicMin(&bounds[k], j0 + i + 1);
             cpre[k] = P;
           }
@@ -579,14 +646,83 @@ __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const f
   }
   __syncthreads();
   const double total = C;
-  if ((int)threadIdx.x < S) {
-    const int i = threadIdx.x;
-    const double lo = cpre[i] < 0.0 ? total : cpre[i];
-    const double hi = (i + 1 == S || cpre[i + 1] < 0.0) ? total : cpre[i + 1];
-    mass[i] = (float)(hi - lo);
-    seg_mass_all[(int64_t)unit * S + i] = mass[i];
+  if constexpr (GENERAL) {
+    if (delta_mode) {
+      // the split / merge pass over the initial segments (see resegment_kernel), then the mass of every
+      // final segment summed from the m_used this workgroup has just written
+      if (threadIdx.x == 0) {
+        int n = 0, start = 0;
+        bool have_left = false;
+        for (int i = 1; i <= K; ++i) {
+          const int e = i == K ? T : bounds[i];
+          const int L = e - start;
+          if (L == 0) continue;
+          if (a.l_max > 0 && L > a.l_max) {
+            const int parts = (L + a.l_max - 1) / a.l_max, base = L / parts, extra = L % parts;
+            int pos = start;
+            for (int j = 0; j < parts && n < S; ++j) {
+              pos += base + (j < extra ? 1 : 0);
+              reseg[n++] = pos;
+            }
+            have_left = true;
+            start = e;
+          } else if (a.l_min > 0 && L < a.l_min) {
+            if (have_left) {
+              reseg[n - 1] = e;
+              start = e;
+            }
+          } else {
+            if (n < S) reseg[n++] = e;
+            have_left = true;
+            start = e;
+          }
+        }
+        if (start < T && n < S) reseg[n++] = T;  // the whole sequence was one too-short segment
+        if (n > 0) reseg[n - 1] = T;             // (only matters if the capacity cut the list short)
+        n_reseg = n;
+      }
+      __syncthreads();
+      const int n = n_reseg;
+      for (int i = threadIdx.x; i < S; i += kUnitBlock) bounds[i + 1] = i < n ? reseg[i] : T;
+      __syncthreads();
+      if (n_groups <= kEndGroups) {
+        // prefix in front of every bound: the end of the run before the one the bound lies in, plus the
+        // positions of that run in front of it (the scan's own order of additions)
+        for (int i = threadIdx.x; i <= S; i += kUnitBlock) {
+          const int bnd = bounds[i];
+          double P = 0.0;
+          if (bnd > 0) {
+            const int q = (bnd - 1) / PER;  // run of the last position in front of the bound
+            if (q > 0) P = ends_all[q - 1];
+            for (int t = q * PER; t < bnd; ++t) P += (double)m_used[t];
+          }
+          cpre[i] = P;
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < S; i += kUnitBlock) mass[i] = (float)(cpre[i + 1] - cpre[i]);
+      } else {
+        for (int sg = wave; sg < S; sg += kW) {
+          const int lo = bounds[sg], hi = bounds[sg + 1];
+          double sm = 0.0;
+          for (int t = lo + lane; t < hi; t += 64) sm += (double)m_used[t];
+#pragma unroll
+          for (int o = 32; o >= 1; o >>= 1) sm += __shfl_xor(sm, o);
+          if (lane == 0) mass[sg] = (float)sm;
+        }
+      }
+      __syncthreads();
+    }
   }
-  if ((int)threadIdx.x <= S) a.bounds[(int64_t)unit * (S + 1) + threadIdx.x] = bounds[threadIdx.x];
+  if (!delta_mode) {
+    for (int i = threadIdx.x; i < S; i += kUnitBlock) {
+      const double lo = cpre[i] < 0.0 ? total : cpre[i];
+      const double hi = (i + 1 == S || cpre[i + 1] < 0.0) ? total : cpre[i + 1];
+      mass[i] = (float)(hi - lo);
+    }
+    __syncthreads();
+  }
+  for (int i = threadIdx.x; i < S; i += kUnitBlock) seg_mass_all[(int64_t)unit * S + i] = mass[i];
+  for (int i = threadIdx.x; i <= S; i += kUnitBlock) a.bounds[(int64_t)unit * (S + 1) + i] = bounds[i];
   // what the quota kernels do besides the quotas: the -1 tail of idx, the kept count, the cleared bitmap
   // of the must-keep path; sinks and the recent suffix come out of the budget first
   const int kept = min(budget, T);
@@ -597,10 +733,18 @@ __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const f
   if (threadIdx.x == 0) n_kept_all[unit] = kept;
   if (flags_all)
     for (int j = threadIdx.x; j < n_words; j += kUnitBlock) flags_all[(int64_t)unit * n_words + j] = 0u;
-  __syncthreads();
-  if (threadIdx.x < 64) {
-    const int q = quota_wave(S, bud, q_min, bounds, mass);
-    if ((int)threadIdx.x < S) quota_all[(int64_t)unit * S + threadIdx.x] = q;
+  if (S <= kUnitMaxSeg) {
+    if (threadIdx.x < 64) {
+      const int q = quota_wave(S, bud, q_min, bounds, mass);
+      if ((int)threadIdx.x < S) quota_all[(int64_t)unit * S + threadIdx.x] = q;
+    }
+  } else {
+    if constexpr (GENERAL) {
+      if (threadIdx.x < 64) {  // one wave, no workgroup barriers
+        quota_block<64>(S, bud, q_min, bounds, mass, qs);
+        for (int i = threadIdx.x; i < S; i += 64) quota_all[(int64_t)unit * S + i] = qs.quo[i];
+      }
+    }
   }
 }
 
@@ -675,7 +819,7 @@ hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq
 }
 
 // The fused step's mass / EMA / segmentation / quota stages in one launch, when the parameters allow it
-// (*ran tells): exactly-S thresholds, no pooling, at most 64 segments.
+// (*ran tells).
 hipError_t launch_unit_mass(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
                             float* credit, float* m_used, int32_t* bounds, float* seg_mass, int32_t* quota,
                             int32_t* idx, int32_t* n_kept, uint32_t* flags, int n_words, const VcInfo& vc,
@@ -685,7 +829,7 @@ hipError_t launch_unit_mass(const ams_params* p, const Dims& d, const int32_t* s
     const char* e = getenv("AMS_UNIT_MASS");  // tuning aid: 0 keeps the chunked kernels
     return e && e[0] == '0';
   }();
-  if (off || p->seg_delta > 0.f || p->pool_kernel > 1 || p->n_segments > kUnitMaxSeg) return hipSuccess;
+  if (off || p->n_segments > kMaxSegments) return hipSuccess;
   MsArgs a = make_args(p, d, seq_lens, ws, wl, bounds);
   a.vec = d.t_stride % 4 == 0 && (((uintptr_t)u | (uintptr_t)credit | (uintptr_t)m_used) & 15) == 0;
   if (vc.have) {  // left by the scorer
@@ -698,20 +842,15 @@ hipError_t launch_unit_mass(const ams_params* p, const Dims& d, const int32_t* s
   if (must && !flags) return hipErrorInvalidValue;
   prof_mark("unit_mass", s);
   const dim3 grid(d.units), blk(kUnitBlock);
-#define AMS_UNIT_MASS_LAUNCH(PER)                                                                              \
-  hipLaunchKernelGGL((unit_mass_kernel<PER>), grid, blk, 0, s, a, u, credit, m_used, p->ema_lambda, p->ema_beta, \
-                     p->mass_eps, p->budget, p->q_min, seg_mass, quota, idx, n_kept, p->n_sink, p->n_last,       \
-                     must ? flags : nullptr, n_words)
-  static const int per = [] {
-    const char* e = getenv("AMS_UNIT_MASS_PER");  // tuning aid: positions per thread and group (4, 8 or 16)
-    return e ? atoi(e) : 8;
-  }();
-  if (per == 4)
-    AMS_UNIT_MASS_LAUNCH(4);
-  else if (per == 16)
-    AMS_UNIT_MASS_LAUNCH(16);
+  const bool general = p->seg_delta > 0.f || a.pool_r > 0 || p->n_segments > kUnitMaxSeg;
+#define AMS_UNIT_MASS_LAUNCH(PER, GEN)                                                                          \
+  hipLaunchKernelGGL((unit_mass_kernel<PER, GEN>), grid, blk, 0, s, a, u, credit, m_used, p->ema_lambda,         \
+                     p->ema_beta, p->mass_eps, p->budget, p->q_min, seg_mass, quota, idx, n_kept, p->n_sink,    \
+                     p->n_last, must ? flags : nullptr, n_words)
+  if (general)
+    AMS_UNIT_MASS_LAUNCH(8, true);
   else
-    AMS_UNIT_MASS_LAUNCH(8);
+    AMS_UNIT_MASS_LAUNCH(8, false);
 #undef AMS_UNIT_MASS_LAUNCH
   *ran = true;
   return hipGetLastError();

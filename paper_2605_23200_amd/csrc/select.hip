@@ -82,18 +82,8 @@ __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_le
   if ((int)threadIdx.x < S) quota_all[(int64_t)unit * S + threadIdx.x] = q;
 }
 
-// More than 64 segments (up to 1024): one workgroup of 256 threads per unit, the segments in LDS.
-// Integer sums are order-free; the sum of the masses of the open segments is taken by one thread
-// in index order, the same order as plain C, so that every share is the same double.
-constexpr int kQuotaBlock = 256;
-
-__device__ __forceinline__ int block_sum_int(int v, int* sm) {
-  v = wave_sum(v);
-  __syncthreads();  // sm may still be read from a previous call
-  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return (sm[0] + sm[1]) + (sm[2] + sm[3]);
-}
+// More than 64 segments (up to 1024): one wave per unit as well, the segments in LDS.
+constexpr int kQuotaBlock = 64;
 
 __global__ __launch_bounds__(kQuotaBlock) void quota_block_kernel(Dims d, const int32_t* seq_lens, int S,
                                                                   int budget, int q_min,
@@ -103,104 +93,12 @@ __global__ __launch_bounds__(kQuotaBlock) void quota_block_kernel(Dims d, const 
                                                                   const double* mpart_all, int n_chunks,
                                                                   int n_sink, int n_last, uint32_t* flags_all,
                                                                   int n_words) {
-  __shared__ int32_t len[kMaxSeg], room[kMaxSeg], quo[kMaxSeg];
-  __shared__ double mass_d[kMaxSeg], raw[kMaxSeg];
-  __shared__ uint8_t active[kMaxSeg], can[kMaxSeg];
-  __shared__ int red[4];
-  __shared__ double msum_sm;
+  __shared__ QuotaScratch sc;
   const int unit = blockIdx.x;
   const int bud = quota_prologue(d, seq_lens, S, budget, seg_mass_all, idx_all, n_kept_all, cpre_all, mpart_all,
                                  n_chunks, n_sink, n_last, flags_all, n_words);
-  const int32_t* bounds = bounds_all + (int64_t)unit * (S + 1);
-  const float* mass = seg_mass_all + (int64_t)unit * S;
-  int c_nonempty = 0, c_need = 0;
-  for (int i = threadIdx.x; i < S; i += kQuotaBlock) {
-    len[i] = bounds[i + 1] - bounds[i];
-    mass_d[i] = (double)mass[i];
-    c_nonempty += len[i] > 0;
-    c_need += min(q_min, len[i]);
-  }
-  const int nonempty = block_sum_int(c_nonempty, red);
-  const int need = block_sum_int(c_need, red);
-  int floor_q = q_min;
-  if (need > bud) floor_q = nonempty > 0 ? bud / nonempty : 0;
-  int c_lo = 0;
-  for (int i = threadIdx.x; i < S; i += kQuotaBlock) {
-    const int lo = min(floor_q, len[i]);
-    room[i] = len[i] - lo;
-    active[i] = room[i] > 0;
-    quo[i] = lo;
-    raw[i] = 0.0;
-    c_lo += lo;
-  }
-  int rem = bud - block_sum_int(c_lo, red);
-  // proportional shares; a segment whose share reaches its room is filled and leaves the pool
-  for (;;) {
-    int c_act = 0;
-    for (int i = threadIdx.x; i < S; i += kQuotaBlock) c_act += active[i];
-    const int n_active = block_sum_int(c_act, red);
-    if (n_active == 0 || rem <= 0) break;
-    if (threadIdx.x == 0) {
-      double msum = 0.0;
-      for (int i = 0; i < S; ++i)
-        if (active[i]) msum += mass_d[i];
-      msum_sm = msum;
-    }
-    __syncthreads();
-    const double msum = msum_sm;
-    int c_sat = 0, c_taken = 0;
-    for (int i = threadIdx.x; i < S; i += kQuotaBlock)
-      if (active[i]) {
-        raw[i] = msum > 0.0 ? (double)rem * mass_d[i] / msum : (double)rem / (double)n_active;
-        if (raw[i] >= (double)room[i]) {
-          quo[i] = len[i];
-          active[i] = 0;
-          ++c_sat;
-          c_taken += room[i];
-        }
-      }
-    const int n_sat = block_sum_int(c_sat, red);
-    rem -= block_sum_int(c_taken, red);
-    if (n_sat == 0) break;
-  }
-  if (rem > 0) {
-    int c_given = 0;
-    for (int i = threadIdx.x; i < S; i += kQuotaBlock)
-      if (active[i]) {
-        const double fl = floor(raw[i]);
-        raw[i] -= fl;  // now the fractional part
-        quo[i] += (int)fl;
-        c_given += (int)fl;
-      }
-    int left = rem - block_sum_int(c_given, red);
-    // one extra each, largest fractional part first, equal parts by lower segment index
-    while (left > 0) {
-      int c_can = 0;
-      for (int i = threadIdx.x; i < S; i += kQuotaBlock) {
-        can[i] = active[i] && quo[i] < len[i];
-        c_can += can[i];
-      }
-      const int n_can = block_sum_int(c_can, red);
-      if (n_can == 0) break;
-      int c_take = 0;
-      for (int i = threadIdx.x; i < S; i += kQuotaBlock)
-        if (can[i]) {
-          int rank = 0;
-          if (n_can > left) {  // otherwise everybody is served
-            const double fi = raw[i];
-            for (int j = 0; j < S; ++j)
-              if (can[j] && (raw[j] > fi || (raw[j] == fi && j < i))) ++rank;
-          }
-          if (rank < left) {
-            ++quo[i];
-            ++c_take;
-          }
-        }
-      left -= block_sum_int(c_take, red);
-    }
-  }
-  __syncthreads();
-  for (int i = threadIdx.x; i < S; i += kQuotaBlock) quota_all[(int64_t)unit * S + i] = quo[i];
+  quota_block<kQuotaBlock>(S, bud, q_min, bounds_all + (int64_t)unit * (S + 1), seg_mass_all + (int64_t)unit * S, sc);
+  for (int i = threadIdx.x; i < S; i += kQuotaBlock) quota_all[(int64_t)unit * S + i] = sc.quo[i];
 }
 
 // Order-preserving image of a score: larger float <-> larger unsigned; -0 and +0 coincide and
