@@ -442,33 +442,51 @@ __global__ __launch_bounds__(64) void segment_mass_kernel(MsArgs a, const float*
 constexpr int kUnitBlock = 1024;
 constexpr int kUnitMaxSeg = 64;
 
-// Pooled usage of one group of positions (see pool_run): the group's scores and r more on either side are
-// staged in LDS, consecutive threads then pool consecutive positions (no bank conflicts), store the result
-// (rounded to fp32 like a stored intermediate) to out[] and add max(pooled, 0) + eps to v.  Ends with a
-// barrier, so that the tile can be refilled.
+// Pooled usage of the whole unit (see pool_run), group by group: the group's scores and r more on either
+// side are staged in LDS, consecutive threads then pool consecutive positions (no bank conflicts), store the
+// result (rounded to fp32 like a stored intermediate) to out[] and add max(pooled, 0) + eps to v and the
+// position's old credit to c.  The next group's scores are requested before the current group is pooled.
 template <int GROUP>
-__device__ __forceinline__ void pool_group(const float* u, float* out, int g0, int T, int r, float* tile,
-                                           double eps, double& v) {
-  const int first = g0 - r;  // position of tile[0]
-  for (int e = threadIdx.x; e < GROUP + 2 * r; e += kUnitBlock) {
-    const int t = first + e;
-    tile[e] = (t >= 0 && t < T) ? u[t] : 0.f;
-  }
-  __syncthreads();
+__device__ __forceinline__ void pool_unit(const float* u, const float* credit, float* out, int T, int r,
+                                          float* tile, double eps, double& v, double& c) {
+  constexpr int kStage = (GROUP + 2 * kMaxPoolR + kUnitBlock - 1) / kUnitBlock;
+  const int n_groups = (T + GROUP - 1) / GROUP;
   const double inv_full = 1.0 / (double)(2 * r + 1);
-  for (int e = threadIdx.x; e < GROUP; e += kUnitBlock) {
-    const int t = g0 + e;
-    if (t < T) {
-      const int lo = max(0, t - r), hi = min(T - 1, t + r);
-      double sum = 0.0;
-      for (int j = lo; j <= hi; ++j) sum += (double)tile[j - first];
-      const int n = hi - lo + 1;
-      const float p = (float)(n == 2 * r + 1 ? sum * inv_full : sum / (double)n);
-      out[t] = p;
-      v += fmax((double)p, 0.0) + eps;
+  float stage[kStage];
+  auto fetch = [&](int g0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < kStage; ++q) {
+      const int e = q * kUnitBlock + (int)threadIdx.x, t = g0 - r + e;
+      stage[q] = (e < GROUP + 2 * r && t >= 0 && t < T) ? u[t] : 0.f;
     }
+  };
+  fetch(0);
+#pragma unroll 1
+  for (int g = 0; g < n_groups; ++g) {
+    const int g0 = g * GROUP, first = g0 - r;  // first = position of tile[0]
+#pragma unroll
+    for (int q = 0; q < kStage; ++q) {
+      const int e = q * kUnitBlock + (int)threadIdx.x;
+      if (e < GROUP + 2 * r) tile[e] = stage[q];
+    }
+    __syncthreads();
+    if (g + 1 < n_groups) fetch(g0 + GROUP);
+    for (int e = threadIdx.x; e < GROUP; e += kUnitBlock) {
+      const int t = g0 + e;
+      if (t < T) {
+        const float cr = credit[t];
+        const int lo = max(0, t - r), hi = min(T - 1, t + r);
+        double sum = 0.0;
+        for (int j = lo; j <= hi; ++j) sum += (double)tile[j - first];
+        const int n = hi - lo + 1;
+        const float p = (float)(n == 2 * r + 1 ? sum * inv_full : sum / (double)n);
+        out[t] = p;
+        v += fmax((double)p, 0.0) + eps;
+        c += (double)cr;
+      }
+    }
+    __syncthreads();
   }
-  __syncthreads();
 }
 
 template <int PER, bool GENERAL>
@@ -528,15 +546,7 @@ __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const f
     double v = 0.0, c = 0.0;
     if (pool_r > 0) {
       if constexpr (GENERAL) {
-#pragma unroll 1
-        for (int r = 0; r < n_groups; ++r) pool_group<kGroup>(u, m_used, r * kGroup, T, pool_r, tile, eps, v);
-        for (int j = threadIdx.x * 4; j < T; j += kUnitBlock * 4) {
-          float cr[4];
-          load_run(credit, j, T, a.vec, cr, 0.f);
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (j + i < T) c += (double)cr[i];
-        }
+        pool_unit<kGroup>(u, credit, m_used, T, pool_r, tile, eps, v, c);
       }
     } else {
       for (int j = threadIdx.x * 4; j < T; j += kUnitBlock * 4) {
