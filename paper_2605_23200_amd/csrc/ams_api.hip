@@ -291,9 +291,8 @@ int ams_select(const ams_params* p, const int32_t* seq_lens, const float* g, con
     if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
     flags = (uint32_t*)((char*)ws + wl.flags);
   }
-  // seg_mass is only read here; the launcher's non-const pointer serves the fused path
   return hip_status(launch_select(p, make_dims(p), seq_lens, g, bounds, const_cast<float*>(seg_mass), quota, idx,
-                                  n_kept, nullptr, nullptr, 0, flags, wl.n_words, (hipStream_t)stream),
+                                  n_kept, flags, wl.n_words, (hipStream_t)stream),
                     (hipStream_t)stream);
 }
 
@@ -342,24 +341,11 @@ int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t
   const KvDev vdev = make_kv(p, src, src->v);
   if ((e = launch_score(p, d, make_kv(p, src, src->k), &vdev, seq_lens, q, u, g, credit, &vc, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;
-  const bool adaptive = p->seg_delta > 0.f;
-  bool unit_mass = false;
   if ((e = launch_unit_mass(p, d, seq_lens, u, credit, m_used, bounds, seg_mass, quota, idx, n_kept,
-                            (uint32_t*)(w + wl.flags), wl.n_words, vc, w, wl, s, &unit_mass)) != hipSuccess)
+                            (uint32_t*)(w + wl.flags), wl.n_words, vc, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;
-  if (!unit_mass) {
-    if ((e = launch_ema(p, d, seq_lens, u, credit, m_used, bounds, vc, w, wl, s)) != hipSuccess)
-      return AMS_ERR_HIP;
-    // exactly-S mode: the quota kernel forms the segment masses from the scan's prefix at the cuts;
-    // Delta mode: the cuts move in the split / merge pass and the masses are summed per segment
-    if ((e = launch_segment(p, d, seq_lens, m_used, bounds, adaptive ? seg_mass : nullptr, true, w, wl, s)) !=
-        hipSuccess)
-      return AMS_ERR_HIP;
-  }
-  if ((e = launch_select(p, d, seq_lens, g, bounds, seg_mass, quota, idx, n_kept,
-                         adaptive ? nullptr : (const double*)(w + wl.cpre),
-                         adaptive ? nullptr : (const double*)(w + wl.mpart), wl.n_chunks4k,
-                         (uint32_t*)(w + wl.flags), wl.n_words, s, unit_mass)) != hipSuccess)
+  if ((e = launch_select(p, d, seq_lens, g, bounds, seg_mass, quota, idx, n_kept, (uint32_t*)(w + wl.flags),
+                         wl.n_words, s, true)) != hipSuccess)
     return AMS_ERR_HIP;
   if ((e = launch_compact(p, d, make_kv(p, src, src->k), make_kv(p, src, src->v), make_kv(p, dst, dst->k),
                           make_kv(p, dst, dst->v), idx, n_kept, credit, credit_dst, s)) != hipSuccess)

@@ -110,19 +110,18 @@ hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_len
 hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq_lens,
                           const float* m_used, int32_t* bounds, float* seg_mass, bool have_chunk_totals,
                           char* ws, const WsLayout& wl, hipStream_t s);
-// One launch for launch_ema + launch_segment + the quota part of launch_select (then called with
-// quota_done = true), for the parameter ranges it is written for; *ran = false: nothing was launched.
+// The fused step's mass / EMA / segmentation / quota stages in one launch (one workgroup per unit); it also
+// leaves the -1 tail of idx, the kept counts and the cleared bitmap, so launch_select follows with
+// quota_done = true.  vc: the chunk sums the scorer left, if any.
 hipError_t launch_unit_mass(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
                             float* credit, float* m_used, int32_t* bounds, float* seg_mass, int32_t* quota,
                             int32_t* idx, int32_t* n_kept, uint32_t* flags, int n_words, const VcInfo& vc,
-                            char* ws, const WsLayout& wl, hipStream_t s, bool* ran);
-// cpre / mpart (optional, with n_chunks): the prefix-sum kernel's raw output; when given, seg_mass is
-// WRITTEN by the quota kernel instead of read.  flags (n_words words per unit): bitmap of the kept set,
-// needed when a must-keep set is configured, else may be null.
+                            char* ws, const WsLayout& wl, hipStream_t s);
+// flags (n_words words per unit): bitmap of the kept set, needed when a must-keep set is configured, else
+// may be null.  quota_done: the quotas (and what the quota kernels do besides) are already in place.
 hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* g,
                          const int32_t* bounds, float* seg_mass, int32_t* quota, int32_t* idx,
-                         int32_t* n_kept, const double* cpre, const double* mpart, int n_chunks,
-                         uint32_t* flags, int n_words, hipStream_t s, bool quota_done = false);
+                         int32_t* n_kept, uint32_t* flags, int n_words, hipStream_t s, bool quota_done = false);
 hipError_t launch_compact(const ams_params* p, const Dims& d, const KvDev& ks, const KvDev& vs,
                           const KvDev& kd, const KvDev& vd, const int32_t* idx, const int32_t* n_kept,
                           const float* credit_src, float* credit_dst, hipStream_t s);

@@ -828,18 +828,12 @@ hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq
   return hipGetLastError();
 }
 
-// The fused step's mass / EMA / segmentation / quota stages in one launch, when the parameters allow it
-// (*ran tells).
+// The fused step's mass / EMA / segmentation / quota stages in one launch.
 hipError_t launch_unit_mass(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
                             float* credit, float* m_used, int32_t* bounds, float* seg_mass, int32_t* quota,
                             int32_t* idx, int32_t* n_kept, uint32_t* flags, int n_words, const VcInfo& vc,
-                            char* ws, const WsLayout& wl, hipStream_t s, bool* ran) {
-  *ran = false;
-  static const bool off = [] {
-    const char* e = getenv("AMS_UNIT_MASS");  // tuning aid: 0 keeps the chunked kernels
-    return e && e[0] == '0';
-  }();
-  if (off || p->n_segments > kMaxSegments) return hipSuccess;
+                            char* ws, const WsLayout& wl, hipStream_t s) {
+  if (p->n_segments > kMaxSegments) return hipErrorInvalidValue;
   MsArgs a = make_args(p, d, seq_lens, ws, wl, bounds);
   a.vec = d.t_stride % 4 == 0 && (((uintptr_t)u | (uintptr_t)credit | (uintptr_t)m_used) & 15) == 0;
   if (vc.have) {  // left by the scorer
@@ -862,7 +856,6 @@ hipError_t launch_unit_mass(const ams_params* p, const Dims& d, const int32_t* s
   else
     AMS_UNIT_MASS_LAUNCH(8, false);
 #undef AMS_UNIT_MASS_LAUNCH
-  *ran = true;
   return hipGetLastError();
 }
 

@@ -1,7 +1,7 @@
 // Segment quotas, in-segment top-k and the kept set (Sec. 3.3 "Segment-wise Quota Allocation",
 // "In-Segment Selection" and the must-keep rules; Alg. 1 steps 4-5).
 //
-// quota_kernel   one wave per unit (up to 64 segments; a workgroup of 256 threads above that); the
+// quota_kernel   one wave per unit (up to 64 segments in registers, up to 1024 in LDS); the
 //                arithmetic is a handful of double operations per segment and is done in index
 //                order so that it is reproducible bit for bit.
 // select_kernel  one workgroup per (segment, unit): radix select (4 x 8 bits, most significant
@@ -21,38 +21,15 @@ namespace {
 
 constexpr int kMaxSeg = 1024;
 
-// What both quota kernels do before the quotas: segment masses from the raw output of the prefix-sum
-// kernel (cpre_all / mpart_all, optional: when given, the masses are formed and stored here instead of
-// being read), the -1 tail of idx, the kept count, the cleared bitmap of the must-keep path.
-// Returns the budget the segments share.
-__device__ __forceinline__ int quota_prologue(const Dims& d, const int32_t* seq_lens, int S, int budget,
-                                              float* seg_mass_all, int32_t* idx_all, int32_t* n_kept_all,
-                                              const double* cpre_all, const double* mpart_all, int n_chunks,
-                                              int n_sink, int n_last, uint32_t* flags_all, int n_words) {
+// What both quota kernels do before the quotas: the -1 tail of idx, the kept count, the cleared bitmap of the
+// must-keep path.  Returns the budget the segments share.
+__device__ __forceinline__ int quota_prologue(const Dims& d, const int32_t* seq_lens, int budget,
+                                              int32_t* idx_all, int32_t* n_kept_all, int n_sink, int n_last,
+                                              uint32_t* flags_all, int n_words) {
   const int unit = blockIdx.x, nthr = blockDim.x;
   int l, b, h;
   unit_coords(d, unit, l, b, h);
   const int T = seq_len(d, seq_lens, b);
-  float* mass = seg_mass_all + (int64_t)unit * S;
-  if (cpre_all) {
-    const int nch = (T + kChunk - 1) / kChunk;
-    double total = 0.0;  // chunk totals in index order, by the first wave; the others wait at the barrier
-    if (threadIdx.x < 64) {
-      for (int base = 0; base < nch; base += 64) {
-        const int k = min(64, nch - base);
-        double v = 0.0;
-        if ((int)threadIdx.x < k) v = mpart_all[(int64_t)unit * n_chunks + base + threadIdx.x];
-        for (int j = 0; j < k; ++j) total += __shfl(v, j);
-      }
-      const double* cpre = cpre_all + (int64_t)unit * (S + 1);
-      for (int i = threadIdx.x; i < S; i += 64) {
-        const double lo = cpre[i] < 0.0 ? total : cpre[i];
-        const double hi = (i + 1 == S || cpre[i + 1] < 0.0) ? total : cpre[i + 1];
-        mass[i] = (float)(hi - lo);
-      }
-    }
-    __syncthreads();
-  }
   // must-keep positions go in first: sinks always, the recent suffix as far as it fits; the segments
   // share what is left
   const int kept = min(budget, T);
@@ -71,13 +48,10 @@ __device__ __forceinline__ int quota_prologue(const Dims& d, const int32_t* seq_
 __global__ __launch_bounds__(64) void quota_kernel(Dims d, const int32_t* seq_lens, int S, int budget,
                                                    int q_min, const int32_t* bounds_all,
                                                    float* seg_mass_all, int32_t* quota_all,
-                                                   int32_t* idx_all, int32_t* n_kept_all,
-                                                   const double* cpre_all, const double* mpart_all,
-                                                   int n_chunks, int n_sink, int n_last,
+                                                   int32_t* idx_all, int32_t* n_kept_all, int n_sink, int n_last,
                                                    uint32_t* flags_all, int n_words) {
   const int unit = blockIdx.x;
-  const int bud = quota_prologue(d, seq_lens, S, budget, seg_mass_all, idx_all, n_kept_all, cpre_all, mpart_all,
-                                 n_chunks, n_sink, n_last, flags_all, n_words);
+  const int bud = quota_prologue(d, seq_lens, budget, idx_all, n_kept_all, n_sink, n_last, flags_all, n_words);
   const int q = quota_wave(S, bud, q_min, bounds_all + (int64_t)unit * (S + 1), seg_mass_all + (int64_t)unit * S);
   if ((int)threadIdx.x < S) quota_all[(int64_t)unit * S + threadIdx.x] = q;
 }
@@ -89,14 +63,11 @@ __global__ __launch_bounds__(kQuotaBlock) void quota_block_kernel(Dims d, const 
                                                                   int budget, int q_min,
                                                                   const int32_t* bounds_all, float* seg_mass_all,
                                                                   int32_t* quota_all, int32_t* idx_all,
-                                                                  int32_t* n_kept_all, const double* cpre_all,
-                                                                  const double* mpart_all, int n_chunks,
-                                                                  int n_sink, int n_last, uint32_t* flags_all,
-                                                                  int n_words) {
+                                                                  int32_t* n_kept_all, int n_sink, int n_last,
+                                                                  uint32_t* flags_all, int n_words) {
   __shared__ QuotaScratch sc;
   const int unit = blockIdx.x;
-  const int bud = quota_prologue(d, seq_lens, S, budget, seg_mass_all, idx_all, n_kept_all, cpre_all, mpart_all,
-                                 n_chunks, n_sink, n_last, flags_all, n_words);
+  const int bud = quota_prologue(d, seq_lens, budget, idx_all, n_kept_all, n_sink, n_last, flags_all, n_words);
   quota_block<kQuotaBlock>(S, bud, q_min, bounds_all + (int64_t)unit * (S + 1), seg_mass_all + (int64_t)unit * S, sc);
   for (int i = threadIdx.x; i < S; i += kQuotaBlock) quota_all[(int64_t)unit * S + i] = sc.quo[i];
 }
@@ -636,8 +607,7 @@ __global__ __launch_bounds__(kFinBlock) void finalize_kernel(Dims d, const int32
 
 hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* g,
                          const int32_t* bounds, float* seg_mass, int32_t* quota, int32_t* idx,
-                         int32_t* n_kept, const double* cpre, const double* mpart, int n_chunks,
-                         uint32_t* flags, int n_words, hipStream_t s, bool quota_done) {
+                         int32_t* n_kept, uint32_t* flags, int n_words, hipStream_t s, bool quota_done) {
   const int S = p->n_segments;
   if (S > kMaxSeg) return hipErrorInvalidValue;
   const bool must = p->n_sink > 0 || p->n_last > 0;
@@ -647,11 +617,11 @@ hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_
     // quotas, the tail of idx, the kept count and the cleared bitmap are already in place
   } else if (S <= 64)
     hipLaunchKernelGGL(quota_kernel, dim3(d.units), dim3(64), 0, s, d, seq_lens, S, p->budget, p->q_min,
-                       bounds, seg_mass, quota, idx, n_kept, cpre, mpart, n_chunks, p->n_sink, p->n_last,
+                       bounds, seg_mass, quota, idx, n_kept, p->n_sink, p->n_last,
                        must ? flags : nullptr, n_words);
   else
     hipLaunchKernelGGL(quota_block_kernel, dim3(d.units), dim3(kQuotaBlock), 0, s, d, seq_lens, S, p->budget,
-                       p->q_min, bounds, seg_mass, quota, idx, n_kept, cpre, mpart, n_chunks, p->n_sink,
+                       p->q_min, bounds, seg_mass, quota, idx, n_kept, p->n_sink,
                        p->n_last, must ? flags : nullptr, n_words);
   prof_mark("select", s);
   // expected segment length decides the shape of the selection workgroups

@@ -481,9 +481,9 @@ def test_empty_and_tiny_sequences_in_a_batch(oracle, paged, options):
 
 
 @pytest.mark.parametrize("S,pool,n_sink,n_last", [(8, 3, 0, 0), (16, 5, 4, 32), (100, 0, 0, 0), (200, 0, 4, 16)])
-def test_chunked_mass_kernels_step(oracle, S, pool, n_sink, n_last):
-    """Thresholds k/S with pooled usage, or with more than 64 segments: the fused step then runs the
-    chunked mass / prefix / quota kernels instead of the one-workgroup-per-unit kernel."""
+def test_fixed_thresholds_with_pooling_or_many_segments_step(oracle, S, pool, n_sink, n_last):
+    """Thresholds k/S with pooled usage, or with more than 64 segments: the general form of the
+    one-workgroup-per-unit mass kernel without the split / merge pass, and the many-segment quota."""
     w = inputs.CONFIGS[1].scaled(L=2, H=3, T=9000, budget=1024, S=S, n_spans=6, span_len=(32, 300),
                                  n_sink=n_sink, n_last=n_last, pool_kernel=pool)
     host = inputs.dense_cache(w, n_threads=4)
