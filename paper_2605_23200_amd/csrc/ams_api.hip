@@ -263,8 +263,8 @@ int ams_ema_update(const ams_params* p, const int32_t* seq_lens, const float* u,
   if (!seq_lens || !u || !credit || !m_used || !ws) return AMS_ERR_INVALID_ARG;
   const WsLayout wl = ws_layout(p);
   if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
-  return hip_status(launch_ema(p, make_dims(p), seq_lens, u, credit, m_used, (int32_t*)((char*)ws + wl.bounds),
-                               VcInfo{false, 0, 0}, (char*)ws, wl, (hipStream_t)stream), (hipStream_t)stream);
+  return hip_status(launch_ema(p, make_dims(p), seq_lens, u, credit, m_used, VcInfo{false, 0, 0}, (char*)ws, wl,
+                               (hipStream_t)stream), (hipStream_t)stream);
 }
 
 int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* m_used,
@@ -274,7 +274,7 @@ int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* 
   if (!seq_lens || !m_used || !bounds || !seg_mass || !ws) return AMS_ERR_INVALID_ARG;
   const WsLayout wl = ws_layout(p);
   if (ws_bytes < wl.total) return AMS_ERR_WORKSPACE_TOO_SMALL;
-  return hip_status(launch_segment(p, make_dims(p), seq_lens, m_used, bounds, seg_mass, false, (char*)ws, wl,
+  return hip_status(launch_segment(p, make_dims(p), seq_lens, m_used, bounds, seg_mass, (char*)ws, wl,
                                    (hipStream_t)stream), (hipStream_t)stream);
 }
 

@@ -102,14 +102,13 @@ hipError_t launch_score_oneread(const ams_params* p, const Dims& d, const KvDev&
                                 const void* q, float* u, float* g, const float* credit, bool want_vc,
                                 int* vc_stride, int* vc_tokens, char* ws, const WsLayout& wl,
                                 hipStream_t s, bool* ran);
-// launch_ema also leaves the chunk totals of m_used in the workspace and resets `bounds` (scratch
-// or the caller's) for a following launch_segment(have_chunk_totals = true).
+// The chunked kernels behind ams_ema_update and ams_mass_segment (the fused step uses launch_unit_mass).
 hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
-                      float* credit, float* m_used, int32_t* bounds, const VcInfo& vc, char* ws,
-                      const WsLayout& wl, hipStream_t s);
+                      float* credit, float* m_used, const VcInfo& vc, char* ws, const WsLayout& wl,
+                      hipStream_t s);
 hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq_lens,
-                          const float* m_used, int32_t* bounds, float* seg_mass, bool have_chunk_totals,
-                          char* ws, const WsLayout& wl, hipStream_t s);
+                          const float* m_used, int32_t* bounds, float* seg_mass, char* ws, const WsLayout& wl,
+                          hipStream_t s);
 // The fused step's mass / EMA / segmentation / quota stages in one launch (one workgroup per unit); it also
 // leaves the -1 tail of idx, the kept counts and the cleared bitmap, so launch_select follows with
 // quota_done = true.  vc: the chunk sums the scorer left, if any.

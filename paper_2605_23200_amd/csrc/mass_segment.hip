@@ -2,16 +2,18 @@
 // points (Sec. 3.3 "Mass-based adaptive segmentation"; Alg. 1 step 3): thresholds k/S for exactly S
 // segments, or k*Delta followed by the split / merge pass over the segment lengths.
 //
-// All of it is elementwise work plus a few sums over T, so every unit is cut into chunks of 4096
-// positions and each (chunk, unit) is one workgroup: the chip is filled even with few units.
+// Two forms.  The stage calls (ams_ema_update, ams_mass_segment) cut every unit into chunks of 4096
+// positions and make each (chunk, unit) one workgroup:
 //
 //   vc_sums_kernel       partial sums of max(u,0)+eps and of the old credit per chunk
-//   mass_ema_kernel      m = v/Z, c <- lambda c + (1-lambda) m, m_used; chunk totals of m_used
-//   chunk_total_kernel   (stand-alone segmentation only) chunk totals of a given m_used
+//   mass_ema_kernel      m = v/Z, c <- lambda c + (1-lambda) m, m_used
+//   chunk_total_kernel   chunk totals of a given m_used
 //   segment_scan_kernel  inclusive prefix P(j) and the first j with P(j) >= k/S for every k
 //   segment_finalize_kernel  segment masses from the prefix at the cuts
 //   resegment_kernel     (Delta mode) split above L_max / merge below L_min, one pass from the left
 //   segment_mass_kernel  (Delta mode) segment masses by summing m_used over the final segments
+//
+// The fused step runs all of it, and the quotas, in one workgroup per unit (unit_mass_kernel below).
 //
 // Normalisers: Z is the actual sum of max(u,0)+eps.  The credit normaliser sum(c_new) is taken as
 // lambda * sum(c_old) + (1 - lambda) and the outer normaliser as 1: both identities hold exactly in
@@ -229,15 +231,12 @@ __global__ __launch_bounds__(kBlock) void vc_sums_kernel(MsArgs a, const float* 
 __global__ __launch_bounds__(kBlock) void mass_ema_kernel(MsArgs a, const float* u_all, float* credit_all,
                                                            float* m_used_all, float lambda, float beta,
                                                            float eps_f) {
-  __shared__ double wave_tot[kWaves];
-  __shared__ double bcast;
   __shared__ float tile[kChunk + 2 * kMaxPoolR], pooled[kChunk];
   const int unit = blockIdx.y, chunk = blockIdx.x;
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T = seq_len(a.d, a.seq_lens, b);
   if (chunk * kChunk >= T) return;
-  if (chunk == 0) init_cuts(a, unit, T);
   __shared__ double2 sums;
   const float* u = u_all + (int64_t)unit * a.d.t_stride;
   float* credit = credit_all + (int64_t)unit * a.d.t_stride;
@@ -268,9 +267,6 @@ __global__ __launch_bounds__(kBlock) void mass_ema_kernel(MsArgs a, const float*
   }
   store_run(credit, j0, T, a.vec, cx);
   store_run(m_used, j0, T, a.vec, mu);
-  double p[kPer], total;
-  chunk_scan(mu, p, total, wave_tot, &bcast);
-  if (threadIdx.x == 0) a.mpart[(int64_t)unit * a.n_chunks + chunk] = total;
 }
 
 __global__ __launch_bounds__(kBlock) void chunk_total_kernel(MsArgs a, const float* m_all) {
@@ -783,9 +779,9 @@ MsArgs make_args(const ams_params* p, const Dims& d, const int32_t* seq_lens, ch
 }  // namespace
 
 hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
-                      float* credit, float* m_used, int32_t* bounds, const VcInfo& vc, char* ws,
-                      const WsLayout& wl, hipStream_t s) {
-  MsArgs a = make_args(p, d, seq_lens, ws, wl, bounds);
+                      float* credit, float* m_used, const VcInfo& vc, char* ws, const WsLayout& wl,
+                      hipStream_t s) {
+  MsArgs a = make_args(p, d, seq_lens, ws, wl, nullptr);
   a.vec = d.t_stride % 4 == 0 && (((uintptr_t)u | (uintptr_t)credit | (uintptr_t)m_used) & 15) == 0;
   const dim3 grid(a.n_chunks, d.units);
   if (vc.have && a.pool_r == 0) {  // left by the scorer (sums of the unsmoothed usage)
@@ -802,15 +798,13 @@ hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_len
 }
 
 hipError_t launch_segment(const ams_params* p, const Dims& d, const int32_t* seq_lens,
-                          const float* m_used, int32_t* bounds, float* seg_mass, bool have_chunk_totals,
-                          char* ws, const WsLayout& wl, hipStream_t s) {
+                          const float* m_used, int32_t* bounds, float* seg_mass, char* ws, const WsLayout& wl,
+                          hipStream_t s) {
   MsArgs a = make_args(p, d, seq_lens, ws, wl, bounds);
   a.vec = d.t_stride % 4 == 0 && ((uintptr_t)m_used & 15) == 0;
   const dim3 grid(a.n_chunks, d.units);
-  if (!have_chunk_totals) {
-    prof_mark("chunk_total", s);
-    hipLaunchKernelGGL(chunk_total_kernel, grid, dim3(kBlock), 0, s, a, m_used);
-  }
+  prof_mark("chunk_total", s);
+  hipLaunchKernelGGL(chunk_total_kernel, grid, dim3(kBlock), 0, s, a, m_used);
   prof_mark("segment_scan", s);
   hipLaunchKernelGGL(segment_scan_kernel, grid, dim3(kBlock), 0, s, a, m_used);
   if (a.delta > 0.0) {  // the cuts move, so the masses cannot come from the prefix at the cuts
