@@ -480,6 +480,22 @@ def test_empty_and_tiny_sequences_in_a_batch(oracle, paged, options):
     check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), full)
 
 
+@pytest.mark.parametrize("delta,l_min,l_max,pool", [(0.1, 16, 256, 5), (0.02, 0, 0, 3)])
+def test_segmentation_as_printed_long_cache_step(oracle, delta, l_min, l_max, pool):
+    """The same on a cache of 40000 positions: more groups of positions than the one-workgroup-per-unit
+    kernel keeps run-end prefixes for, so the masses of the moved segments are summed from m_used."""
+    T = 40000
+    cap = int(np.ceil(1 / delta)) + 1 + (T // l_max if l_max else 0)
+    w = inputs.CONFIGS[1].scaled(L=1, H=2, T=T, budget=1024, S=cap, n_spans=12, span_len=(64, 600),
+                                 n_sink=4, n_last=32, causal=True, seg_delta=delta, l_min=l_min, l_max=l_max,
+                                 pool_kernel=pool)
+    host = inputs.dense_cache(w, n_threads=4)
+    job = Job(w, host)
+    job.step()
+    check_properties_all_units(job)
+    check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), list(range(w.units)))
+
+
 @pytest.mark.parametrize("S,pool,n_sink,n_last", [(8, 3, 0, 0), (16, 5, 4, 32), (100, 0, 0, 0), (200, 0, 4, 16)])
 def test_fixed_thresholds_with_pooling_or_many_segments_step(oracle, S, pool, n_sink, n_last):
     """Thresholds k/S with pooled usage, or with more than 64 segments: the general form of the
