@@ -94,7 +94,11 @@ struct Emit {
   }
 };
 
-// The selection kernel comes in two shapes: 256 threads with room for 4096 keys in LDS (segments of
+// 3968 keys + the four histograms come to 19.6 KB: eight workgroups fit the LDS of a CU (4096 keys: seven,
+// and the 4096 workgroups of the headline workload then need three rounds instead of two)
+constexpr int kSelectCap = 3968;
+
+// The selection kernel comes in two shapes: 256 threads with room for 3968 keys in LDS (segments of
 // thousands of positions) and one wave with room for 1024 keys (many short segments: more workgroups
 // per compute unit and no barriers between waves).  BLOCK = threads, CAP = segment lengths up to
 // which the keys are selected from a copy in LDS.
@@ -635,7 +639,7 @@ hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_
       hipLaunchKernelGGL((select_kernel<false, 64, 1024>), grid, dim3(64), 0, s, d, S, p->budget, g, bounds, quota,
                          idx, nullptr, 0);
     else
-      hipLaunchKernelGGL((select_kernel<false, 256, 4096>), grid, dim3(256), 0, s, d, S, p->budget, g, bounds,
+      hipLaunchKernelGGL((select_kernel<false, 256, kSelectCap>), grid, dim3(256), 0, s, d, S, p->budget, g, bounds,
                          quota, idx, nullptr, 0);
     return hipGetLastError();
   }
@@ -643,7 +647,7 @@ hipError_t launch_select(const ams_params* p, const Dims& d, const int32_t* seq_
     hipLaunchKernelGGL((select_kernel<true, 64, 1024>), grid, dim3(64), 0, s, d, S, p->budget, g, bounds, quota,
                        idx, flags, n_words);
   else
-    hipLaunchKernelGGL((select_kernel<true, 256, 4096>), grid, dim3(256), 0, s, d, S, p->budget, g, bounds, quota,
+    hipLaunchKernelGGL((select_kernel<true, 256, kSelectCap>), grid, dim3(256), 0, s, d, S, p->budget, g, bounds, quota,
                        idx, flags, n_words);
   prof_mark("finalize", s);
   hipLaunchKernelGGL(finalize_kernel, dim3(d.units), dim3(kFinBlock), 0, s, d, seq_lens, p->budget, p->n_sink,
