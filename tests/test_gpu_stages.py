@@ -579,3 +579,59 @@ def test_score_late_dominant_key(oracle, dtype, where):
                                   w.G, w.W, SCORERS[sc_name])
             assert_close_rel(u_h[i], uo, rtol=1e-5, atol=1e-30, what=f"u unit {i}")
             assert_close_rel(g_h[i], go, rtol=1e-5, atol=1e-30, what=f"g unit {i}")
+
+
+@pytest.mark.parametrize("n_sink,n_last", [(0, 0), (4, 32)])
+def test_external_score_through_the_stage_calls(oracle, n_sink, n_last):
+    """A selection score the library knows nothing about (here: seeded random numbers with planted ties,
+    standing in for a caller's own scorer) goes through ams_score (usage only, g untouched) -> ams_ema_update
+    -> ams_mass_segment -> ams_select -> ams_compact; every stage against the oracle."""
+    w = _workload("bf16", 4, 16, 5000, n_sink=n_sink, n_last=n_last)
+    host = inputs.dense_cache(w, n_threads=4)
+    p = params_for(w, scorer=B.SCORER_EXTERNAL)
+    ws = workspace(p)
+    units, T = p.units, w.T
+    rng = np.random.default_rng(7)
+    g_h = rng.standard_normal((units, T)).astype(np.float32)
+    g_h[:, ::7] = np.float32(0.25)                                  # many equal scores: ties go to the lower index
+    K, V, Q, lens = to_dev(host["K"]), to_dev(host["V"]), to_dev(host["Q"]), to_dev(host["seq_lens"])
+    u = torch.zeros((units, T), device=DEV)
+    g = to_dev(g_h)
+    credit = torch.zeros((units, T), device=DEV)
+    m_used = torch.zeros((units, T), device=DEV)
+    bounds = torch.zeros((units, w.S + 1), dtype=torch.int32, device=DEV)
+    seg_mass = torch.zeros((units, w.S), device=DEV)
+    quota = torch.zeros((units, w.S), dtype=torch.int32, device=DEV)
+    idx = torch.full((units, w.budget), -9, dtype=torch.int32, device=DEV)
+    n_kept = torch.zeros(units, dtype=torch.int32, device=DEV)
+    Kd = torch.zeros((w.L, w.B, w.H, w.budget, w.D), dtype=K.dtype, device=DEV)
+    Vd = torch.zeros_like(Kd)
+    cdst = torch.zeros((units, w.budget), device=DEV)
+    src, dst = B.dense_view(K, V), B.dense_view(Kd, Vd)
+    B.ams_score(p, src, lens, Q, u, g, ws)
+    B.ams_ema_update(p, lens, u, credit, m_used, ws)
+    B.ams_mass_segment(p, lens, m_used, bounds, seg_mass, ws)
+    B.ams_select(p, lens, g, bounds, seg_mass, quota, idx, n_kept, ws)
+    B.ams_compact(p, src, idx, n_kept, dst, credit, cdst)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_host(g), g_h)                  # the caller's score is left alone
+    u_g, m_g, b_g, sm_g, q_g = (to_host(x) for x in (u, m_used, bounds, seg_mass, quota))
+    idx_g, nk_g, cr_g = to_host(idx), to_host(n_kept), to_host(credit)
+    Ko = to_host(Kd, np.uint16).reshape(units, w.budget, w.D)
+    for i, (l, b, h) in enumerate(unit_list(w)):
+        uo, _ = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), host["K"][l, b, h], w.G, w.W,
+                             B.SCORER_MEAN_WINDOW)
+        assert_close_rel(u_g[i], uo, what=f"u unit {i}")
+        m_o, c_o = oracle.ema(oracle.mass(u_g[i], w.eps), np.zeros(T, np.float32), w.lam, w.beta)
+        assert_close_rel(m_g[i], m_o, what=f"m_used unit {i}")
+        assert_close_rel(cr_g[i], c_o, what=f"credit unit {i}")
+        b_o, sm_o = oracle.segment(m_g[i], w.S)
+        np.testing.assert_array_equal(b_g[i], b_o)
+        assert_close_rel(sm_g[i], sm_o, what=f"seg_mass unit {i}")
+        sinks, last, seg_budget = oracle.must_keep(T, w.budget, n_sink, n_last)
+        q_o = oracle.quota(b_g[i], sm_g[i], seg_budget, w.q_min)
+        np.testing.assert_array_equal(q_g[i], q_o)
+        i_o = oracle.finalize(g_h[i], oracle.select(g_h[i], b_g[i], q_g[i]), sinks, last, w.budget)
+        assert nk_g[i] == w.budget
+        np.testing.assert_array_equal(idx_g[i], i_o)
+        np.testing.assert_array_equal(Ko[i], host["K"][l, b, h][i_o])
