@@ -491,7 +491,8 @@ __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const f
                                                                 float eps_f, int budget, int q_min,
                                                                 float* seg_mass_all, int32_t* quota_all,
                                                                 int32_t* idx_all, int32_t* n_kept_all, int n_sink,
-                                                                int n_last, uint32_t* flags_all, int n_words) {
+                                                                int n_last, uint32_t* flags_all, int n_words,
+                                                                const int32_t* status) {
   constexpr int kW = kUnitBlock / 64, kGroup = kUnitBlock * PER;
   constexpr int kCap = GENERAL ? kMaxSegments : kUnitMaxSeg;
   __shared__ double wave_tot[2][kW];
@@ -615,7 +616,8 @@ __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const f
     __syncthreads();
     double off = C;
     for (int w = 0; w < wave; ++w) off += wave_tot[par][w];
-    double run = off + (incl - ts);  // prefix of the position in front of this thread's run
+    const double start = off + (incl - ts);  // prefix of the position in front of this thread's run
+    double run = start;
 #pragma unroll
     for (int i = 0; i < PER; ++i) run += (double)mu[i];
     ends[par][threadIdx.x] = run;
@@ -628,7 +630,9 @@ __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const f
     // most threads see no threshold between their neighbour's prefix and their own last one (the masses
     // are not negative, so the prefix does not fall)
     if (thresholds_reached(run, K, thr, scale) > f_prev) {
-      double P = prev_end;
+      // the walk repeats the additions that gave `run`, so its last value IS the published end of this
+      // run: every threshold in (neighbour's end, run] is met by exactly one position of this thread
+      double P = start;
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
         P += (double)mu[i];
@@ -736,7 +740,8 @@ __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const f
   const int bud = kept - sinks - min(n_last, kept - sinks);
   int32_t* idx = idx_all + (int64_t)unit * budget;
   for (int j = kept + threadIdx.x; j < budget; j += kUnitBlock) idx[j] = -1;
-  if (threadIdx.x == 0) n_kept_all[unit] = kept;
+  // a scorer whose bounded wait expired left unfinished scores: no unit reports a kept set then
+  if (threadIdx.x == 0) n_kept_all[unit] = (status && *status != 0) ? -1 : kept;
   if (flags_all)
     for (int j = threadIdx.x; j < n_words; j += kUnitBlock) flags_all[(int64_t)unit * n_words + j] = 0u;
   if (S <= kUnitMaxSeg) {
@@ -844,7 +849,7 @@ hipError_t launch_unit_mass(const ams_params* p, const Dims& d, const int32_t* s
 #define AMS_UNIT_MASS_LAUNCH(PER, GEN)                                                                          \
   hipLaunchKernelGGL((unit_mass_kernel<PER, GEN>), grid, blk, 0, s, a, u, credit, m_used, p->ema_lambda,         \
                      p->ema_beta, p->mass_eps, p->budget, p->q_min, seg_mass, quota, idx, n_kept, p->n_sink,    \
-                     p->n_last, must ? flags : nullptr, n_words)
+                     p->n_last, must ? flags : nullptr, n_words, (const int32_t*)park_status_word(ws, wl))
   if (general)
     AMS_UNIT_MASS_LAUNCH(8, true);
   else

@@ -521,6 +521,7 @@ __global__ __launch_bounds__(kFinBlock) void finalize_kernel(Dims d, const int32
       c_eq = 0;
 #pragma unroll
       for (int w = 0; w < kFinWaves; ++w) c_eq += red[w];
+      __syncthreads();  // red[] is written again below: every wave has read it first
       const bool all_eq = c_eq == rem;  // no choice to make among equal scores
 #pragma unroll
       for (int j = 0; j < kFinPer; ++j) {
