@@ -62,6 +62,18 @@ typedef enum {
                                    g = (p + vnorm_eps) * ||v||_2; reads V                  */
 } ams_scorer;
 
+/* How ams_score / ams_compress_step form the softmax statistics (the results agree to rounding;
+ * ams_params.score_path).  AUTO lets the library choose; the other two pin the choice, for
+ * measurements and tests. */
+typedef enum {
+  AMS_SCORE_PATH_AUTO = 0,
+  AMS_SCORE_PATH_TWO_SWEEPS = 1, /* K is streamed twice: statistics, then usage; every configuration  */
+  AMS_SCORE_PATH_ONE_READ = 2    /* K is read once and held on chip between the two products: bf16,
+                                    head_dim 128, at most 128 queries per KV head, dense layout, no
+                                    causal window, mean-window / last-query / key-diversity scorers;
+                                    AMS_ERR_UNSUPPORTED otherwise                                    */
+} ams_score_path;
+
 typedef enum {
   AMS_LAYOUT_DENSE = 0, /* K, V = [layers, batch, kv_heads, t_capacity, head_dim]          */
   AMS_LAYOUT_PAGED = 1  /* per layer a pool [n_slots, kv_heads, head_dim]; token p of
@@ -95,6 +107,7 @@ typedef struct {
   int32_t l_max;      /* seg_delta > 0: segments longer than this are split (0 = off)      */
   int32_t pool_kernel;/* odd k > 1: Eq. (1) sees the k-point centred mean of u (App. A); 0/1 = off */
   float vnorm_eps;    /* epsilon of AMS_SCORER_EXPECTED_VNORM, >= 0 (1e-2 in the paper's runs) */
+  int32_t score_path; /* ams_score_path; 0 = the library chooses                                   */
 } ams_params;
 
 /* A KV cache as the library sees it.  Plain data, [host]; k, v, block_table [dev]. */

@@ -27,12 +27,6 @@ static int padded_queries(int n, bool bf16) {
 // Tokens per workgroup of the scoring sweeps: as many as possible (the query window is loaded once per
 // workgroup), but few enough that the launch has a couple of thousand workgroups to fill 256 CUs.
 static int pick_score_chunk(size_t units, int t_max, bool paged) {
-  static const int forced = [] {
-    const char* e = getenv("AMS_SCORE_CHUNK_TOKENS");  // tuning aid; a multiple of 256 up to kScoreChunk
-    const int v = e ? atoi(e) : 0;
-    return (v >= 256 && v <= kScoreChunk && v % 256 == 0) ? v : 0;
-  }();
-  if (forced) return forced;
   // measured on 256 units: 4096 tokens at 32k positions (1.060 ms per step against 1.077 with 2048 and
   // 1.13 with 1024), 1024 at 2176 positions (0.208 against 0.229 with 2048); 512 and 256 lose to the
   // per-workgroup load of the query window
@@ -64,7 +58,7 @@ WsLayout ws_layout(const ams_params* p) {
   w.seg_mass = o;   o += align256(units * (size_t)p->n_segments * sizeof(float));
   w.quota = o;      o += align256(units * (size_t)p->n_segments * sizeof(int32_t));
   w.kbar = o;       o += align256(units * nc_cap * (size_t)p->head_dim * sizeof(double));
-  w.fused = o;      o += align256(fused_score_ws_bytes((int64_t)units, p->t_max, w.n_pad, p->batch));
+  w.park = o;       o += align256(park_score_ws_bytes(w.n_pad));
   w.n_chunks4k = div_up(p->t_max, kChunk);
   w.vc_part = o;    o += align256(units * (size_t)div_up(p->t_max, 128) * 2 * sizeof(double));  // finest producer: 256 positions per entry
   w.mpart = o;      o += align256(units * w.n_chunks4k * sizeof(double));
@@ -97,6 +91,7 @@ static int check_params(const ams_params* p) {
     return AMS_ERR_INVALID_ARG;
   if (p->scorer < AMS_SCORER_LAST_QUERY || p->scorer > AMS_SCORER_EXPECTED_VNORM) return AMS_ERR_INVALID_ARG;
   if (p->scorer == AMS_SCORER_EXPECTED_VNORM && !(p->vnorm_eps >= 0.f)) return AMS_ERR_INVALID_ARG;
+  if (p->score_path < AMS_SCORE_PATH_AUTO || p->score_path > AMS_SCORE_PATH_ONE_READ) return AMS_ERR_INVALID_ARG;
   if (p->head_dim != 64 && p->head_dim != 128) return AMS_ERR_UNSUPPORTED;
   if (p->n_segments > 1024) return AMS_ERR_UNSUPPORTED;
   const int64_t units = (int64_t)p->n_layers * p->batch * p->n_kv_heads;
@@ -164,9 +159,13 @@ struct Profiler {
 }  // namespace
 
 void prof_mark(const char* label, hipStream_t s);
+static int status_of(hipError_t e) {
+  if (e == hipSuccess) return AMS_OK;
+  return e == hipErrorNotSupported ? AMS_ERR_UNSUPPORTED : AMS_ERR_HIP;  // a pinned path that does not apply
+}
 static int hip_status(hipError_t e, hipStream_t s) {
   prof_mark("end", s);  // closes the interval of the call's last kernel
-  return e == hipSuccess ? AMS_OK : AMS_ERR_HIP;
+  return status_of(e);
 }
 
 void prof_mark(const char* label, hipStream_t s) {
@@ -340,7 +339,7 @@ int ams_compress_step(const ams_params* p, const ams_kv_view* src, const int32_t
   VcInfo vc{false, 0, 0};
   const KvDev vdev = make_kv(p, src, src->v);
   if ((e = launch_score(p, d, make_kv(p, src, src->k), &vdev, seq_lens, q, u, g, credit, &vc, w, wl, s)) != hipSuccess)
-    return AMS_ERR_HIP;
+    return status_of(e);
   if ((e = launch_unit_mass(p, d, seq_lens, u, credit, m_used, bounds, seg_mass, quota, idx, n_kept,
                             (uint32_t*)(w + wl.flags), wl.n_words, vc, w, wl, s)) != hipSuccess)
     return AMS_ERR_HIP;

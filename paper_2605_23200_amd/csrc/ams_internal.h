@@ -69,7 +69,7 @@ inline int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 // Workspace carving (offsets in bytes, 256-byte aligned).
 struct WsLayout {
-  size_t part_stats, fin_stats, u, g, m_used, bounds, seg_mass, quota, kbar, fused, vc_part, mpart, cpre, flags, csum, total;
+  size_t part_stats, fin_stats, u, g, m_used, bounds, seg_mass, quota, kbar, park, vc_part, mpart, cpre, flags, csum, total;
   int n_chunks, n_pad;
   int score_chunk;  // tokens per workgroup of the scoring kernels for these parameters, dense cache
   int score_chunk_paged, n_chunks_paged;  // the same for a paged cache
@@ -97,7 +97,11 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
                         const int32_t* seq_lens,
                         const void* q, float* u, float* g, const float* credit, VcInfo* vc, char* ws,
                         const WsLayout& wl, hipStream_t s);
-size_t fused_score_ws_bytes(int64_t units, int t_max, int n_pad, int batch);
+// The one-read scorer (score_park.hip): limits of its cluster bookkeeping, bytes of its exchange area, and the
+// word in that area that a bounded wait raises when it expires (the kernels after the scorer read it).
+constexpr int kParkMaxWorkgroups = 1024, kParkMaxClusters = 1024, kParkMaxMembers = 1024;
+size_t park_score_ws_bytes(int n_pad);
+int32_t* park_status_word(char* ws, const WsLayout& wl);
 hipError_t launch_score_oneread(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
                                 const void* q, float* u, float* g, const float* credit, bool want_vc,
                                 int* vc_stride, int* vc_tokens, char* ws, const WsLayout& wl,

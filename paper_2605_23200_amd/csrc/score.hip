@@ -219,6 +219,7 @@ __global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(ScoreArgs 
   __shared__ float pm[kReduceThreads];
   __shared__ double pz[kReduceThreads];
   const int unit = blockIdx.x;
+  if (unit == 0 && threadIdx.x == 0 && a.status) *a.status = 0;  // no bounded wait on this path
   int l, b, h;
   unit_coords(a.d, unit, l, b, h);
   const int T = seq_len(a.d, a.seq_lens, b);
@@ -754,6 +755,7 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
   a.q = (const char*)q;
   a.part = (float2*)(ws + wl.part_stats);
   a.fin = (float4*)(ws + wl.fin_stats);
+  a.status = park_status_word(ws, wl);
   a.u = u;
   const bool paged = k.layout != AMS_LAYOUT_DENSE;
   a.n_chunks = paged ? wl.n_chunks_paged : wl.n_chunks;
@@ -773,10 +775,12 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
   bool oneread = false;
   int vc_stride = 0, vc_tokens = 0;
   hipError_t e = hipSuccess;
-  if (!causal)
+  // AMS_SCORE_PATH_AUTO: the two sweeps, which are the faster of the two on every workload measured so far
+  if (p->score_path == AMS_SCORE_PATH_ONE_READ)
     e = launch_score_oneread(p, d, k, seq_lens, q, u, g, credit, vc != nullptr, &vc_stride, &vc_tokens, ws, wl, s,
                              &oneread);
   if (e != hipSuccess) return e;
+  if (!oneread && p->score_path == AMS_SCORE_PATH_ONE_READ) return hipErrorNotSupported;
   if (!oneread) {
     if (d.D == 64)
       e = bf16 ? run_by_nb<true, 64>(a, nb, mode, s) : run_by_nb<false, 64>(a, nb, mode, s);

@@ -38,6 +38,7 @@ struct ScoreArgs {
   double* csum;         // [units]
   float eps;
   bool causal;  // causal window (App. A): query w of the window sees keys 0 .. T-W+w
+  int32_t* status;  // word the one-read scorer raises when a bounded wait expires; the two-sweep path clears it
 };
 
 // Row geometry of a cache of HD channels: bytes per row, stride of a query row in LDS (padded by

@@ -22,7 +22,8 @@ class Job:
     """One workload resident on the GPU: source cache, destination cache, credit, outputs, workspace."""
 
     def __init__(self, w: inputs.Workload, host: dict, scorer: int = B.SCORER_MEAN_WINDOW,
-                 device: str = "cuda:0", credit: np.ndarray | None = None, paged: bool | None = None):
+                 device: str = "cuda:0", credit: np.ndarray | None = None, paged: bool | None = None,
+                 score_path: int = B.SCORE_PATH_AUTO):
         self.w, self.device = w, device
         lens = host["seq_lens"]
         self.t_max = int(lens.max())
@@ -33,7 +34,7 @@ class Job:
                                n_segments=w.S, q_min=w.q_min, ema_lambda=w.lam, ema_beta=w.beta,
                                mass_eps=w.eps, scorer=scorer, n_sink=w.n_sink, n_last=w.n_last,
                                causal=w.causal, seg_delta=w.seg_delta, l_min=w.l_min, l_max=w.l_max,
-                               pool_kernel=w.pool_kernel)
+                               pool_kernel=w.pool_kernel, score_path=score_path)
         self.units = w.units
         self.keep = min(w.budget, self.t_max)
         self.lens = _dev(lens, device)

@@ -56,7 +56,8 @@ def test_workspace_bytes_and_layout():
     ("pool_kernel", 4, B.ERR_INVALID_ARG), ("pool_kernel", 65, B.ERR_INVALID_ARG), ("seg_delta", -0.1, B.ERR_INVALID_ARG),
     ("seg_delta", 1e-4, B.ERR_INVALID_ARG),            # more than 1024 initial segments
     ("seg_delta", 0.05, B.ERR_INVALID_ARG),            # 20 initial segments do not fit the 8 entries
-    ("l_max", 64, B.ERR_INVALID_ARG)])                 # length rules without a target mass
+    ("l_max", 64, B.ERR_INVALID_ARG),                  # length rules without a target mass
+    ("score_path", 3, B.ERR_INVALID_ARG), ("score_path", -1, B.ERR_INVALID_ARG)])
 def test_bad_params_are_rejected_on_the_host(field, value, status):
     p = _good()
     setattr(p, field, value)
@@ -65,6 +66,13 @@ def test_bad_params_are_rejected_on_the_host(field, value, status):
     assert B.lib().ams_workspace_layout(C.byref(p), C.byref(out)) == status
     # the launching entry points return the same status before touching any pointer
     assert B.lib().ams_ema_update(C.byref(p), None, None, None, None, None, 0, None) == status
+
+
+def test_score_path_field():
+    p = _good()
+    for path in (B.SCORE_PATH_AUTO, B.SCORE_PATH_TWO_SWEEPS, B.SCORE_PATH_ONE_READ):
+        p.score_path = path
+        assert B.ams_workspace_bytes(p) > 0            # the workspace does not depend on the path
 
 
 def test_both_head_dimensions_are_accepted():

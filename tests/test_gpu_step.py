@@ -545,26 +545,40 @@ def test_must_keep_paged_ragged(oracle):
     check_units(oracle, job, host, np.zeros((w.units, job.t_max), np.float32), [0, 1, w.units // 2, w.units - 1])
 
 
-def test_one_read_scorer_path(oracle, monkeypatch):
-    """The opt-in cooperative scorer that reads K once (AMS_SCORER=oneread) computes the same event:
-    ragged tail, several tiles per unit, mean-window and last-query scorers."""
-    monkeypatch.setenv("AMS_SCORER", "oneread")
-    for scorer in (B.SCORER_MEAN_WINDOW, B.SCORER_LAST_QUERY):
-        w = inputs.CONFIGS[1].scaled(L=2, H=3, T=5000, budget=512, S=8, n_spans=6, span_len=(32, 300))
-        host = inputs.dense_cache(w, n_threads=4)
-        job = Job(w, host, scorer=scorer)
+@pytest.mark.parametrize("scorer", [B.SCORER_MEAN_WINDOW, B.SCORER_LAST_QUERY, B.SCORER_KEYDIFF])
+def test_both_score_paths(oracle, scorer):
+    """ams_params.score_path pins how the softmax statistics are formed: K held on chip and read once, or
+    streamed twice.  Both compute the same event (ragged tail, several workgroups per unit, more units than
+    clusters run at once would need), and the kernel labels show that the pinned path really ran."""
+    w = inputs.CONFIGS[1].scaled(L=2, H=3, T=5000, budget=512, S=8, n_spans=6, span_len=(32, 300))
+    host = inputs.dense_cache(w, n_threads=4)
+    us = {}
+    for path, ran, not_ran in ((B.SCORE_PATH_ONE_READ, "score_oneread", "score_stats"),
+                               (B.SCORE_PATH_TWO_SWEEPS, "score_stats", "score_oneread")):
+        job = Job(w, host, scorer=scorer, score_path=path)
         B.ams_profile_begin()
         job.step()
         labels = [k for k, _ in B.ams_profile_end()]
-        assert "score_oneread" in labels and "score_stats" not in labels      # the path under test really ran
+        assert ran in labels and not_ran not in labels
         check_properties_all_units(job)
         check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), list(range(w.units)), scorer=scorer)
-    monkeypatch.delenv("AMS_SCORER")
-    job = Job(w, host, scorer=scorer)
-    B.ams_profile_begin()
-    job.step()
-    labels = [k for k, _ in B.ams_profile_end()]
-    assert "score_stats" in labels and "score_usage" in labels               # default: the two sweeps
+        us[path] = job.intermediates().u[:, :w.T].cpu().numpy()
+    np.testing.assert_allclose(us[B.SCORE_PATH_ONE_READ], us[B.SCORE_PATH_TWO_SWEEPS], rtol=2e-5, atol=1e-12)
+
+
+def test_one_read_path_says_when_it_does_not_apply():
+    """A pinned one-read path is refused (AMS_ERR_UNSUPPORTED, nothing half done) where only the two sweeps
+    exist: fp32 caches, the causal window, the moment-based scorers."""
+    base = inputs.CONFIGS[1].scaled(L=1, H=2, T=1000, budget=128, S=4, n_spans=2, span_len=(16, 64))
+    for w, scorer in ((base.scaled(dtype="f32"), B.SCORER_MEAN_WINDOW), (base.scaled(causal=True), B.SCORER_MEAN_WINDOW),
+                      (base, B.SCORER_EXPECTED)):
+        host = inputs.dense_cache(w, n_threads=2)
+        job = Job(w, host, scorer=scorer, score_path=B.SCORE_PATH_ONE_READ)
+        with pytest.raises(B.AmsError) as err:
+            job.step()
+        assert err.value.status == B.ERR_UNSUPPORTED
+        Job(w, host, scorer=scorer, score_path=B.SCORE_PATH_AUTO).step()      # the library's own choice works
+    torch.cuda.synchronize()
 
 
 def test_step_under_graph_capture(oracle):
