@@ -47,6 +47,7 @@ def kernel_bytes(label, w, lens=None):
         "score_stats": tok * D * e,                       # K stream
         "score_usage": tok * D * e + 4 * tok,             # K stream + u
         "score_reduce": 0,
+        "score_oneread": tok * D * e + 4 * tok * 2,       # K stream once, u out, old credit in (for its sum)
         "mass_ema": 4 * tok * 4,                          # u, credit in; credit, m_used out
         "unit_mass": 4 * tok * 4,                         # the same, with the scan and the quotas in the same launch
         "segment_scan": 4 * tok,                          # m_used in
@@ -76,6 +77,8 @@ def main():
     ap.add_argument("--scorer", default="mean_window",
                     choices=["mean_window", "last_query", "keydiff", "expected", "expected_vnorm"],
                     help="base scorer (the headline workload uses mean_window)")
+    ap.add_argument("--score-path", default="auto", choices=["auto", "two_sweeps", "one_read"],
+                    help="ams_params.score_path: how the softmax statistics are formed (the headline line uses auto)")
     ap.add_argument("--no-small-event", action="store_true",
                     help="skip the short event of the literal trajectory (profiling runs: one workload per kernel name)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -105,6 +108,8 @@ def main():
     scorer_id = {"mean_window": B.SCORER_MEAN_WINDOW, "last_query": B.SCORER_LAST_QUERY,
                  "keydiff": B.SCORER_KEYDIFF, "expected": B.SCORER_EXPECTED,
                  "expected_vnorm": B.SCORER_EXPECTED_VNORM}[args.scorer]
+    score_path = {"auto": B.SCORE_PATH_AUTO, "two_sweeps": B.SCORE_PATH_TWO_SWEEPS,
+                  "one_read": B.SCORE_PATH_ONE_READ}[args.score_path]
     n_q = 4
     lens = None
     if w.paged:
@@ -120,7 +125,7 @@ def main():
         if w.T_min is not None:
             sys.exit("bench.py: ragged workloads are benchmarked in the paged layout only")
         host = inputs.dense_cache(w, n_threads=16)
-        job = Job(w, host, scorer=scorer_id)
+        job = Job(w, host, scorer=scorer_id, score_path=score_path)
         q_windows = [job.Q] + [torch.empty_like(job.Q) for _ in range(n_q - 1)]
         for e in range(1, n_q):
             Q = np.zeros_like(host["Q"])
@@ -177,7 +182,7 @@ def main():
     small_ms = None
     if w.n_append > 0 and not w.paged and not args.no_small_event:
         ws_small = w.scaled(T=w.budget + w.n_append, n_spans=max(1, w.n_spans * (w.budget + w.n_append) // w.T))
-        job_s = Job(ws_small, inputs.dense_cache(ws_small, n_threads=16), scorer=scorer_id)
+        job_s = Job(ws_small, inputs.dense_cache(ws_small, n_threads=16), scorer=scorer_id, score_path=score_path)
         for _ in range(5):
             job_s.step(stream)
         torch.cuda.synchronize()
@@ -217,7 +222,7 @@ def main():
                                + ("; causal window" if w.causal else "")
                                + (f"; Delta {w.seg_delta} L {w.l_min}/{w.l_max}" if w.seg_delta else "")
                                + (f"; pool {w.pool_kernel}" if w.pool_kernel > 1 else ""),
-                   "units": w.units, "scorer": args.scorer},
+                   "units": w.units, "scorer": args.scorer, "score_path": args.score_path},
         "effective_GBps": round(eff_gbps, 1), "algorithmic_bytes_per_step": step_bytes,
         "hbm_peak_frac": round(eff_gbps / HBM_PEAK_GBPS, 4),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,

@@ -190,16 +190,14 @@ __global__ __launch_bounds__(kThreads, 2) void score_park_kernel(ParkArgs a) {
   auto unit_len = [&](int unit) __attribute__((always_inline)) -> int {
     return seq_len(a.s.d, a.s.seq_lens, (unit / a.s.d.H) % a.s.d.B);
   };
-  auto request = [&](int unit, int r, uint4 (&dst)[8]) __attribute__((always_inline)) {
-    const int T = unit_len(unit);
+  auto request = [&](int unit, int T, int r, uint4 (&dst)[8]) __attribute__((always_inline)) {
     if (t0w + 32 * r < T) {
       const uint4* p = (const uint4*)row_ptr(unit, T, t0w + 32 * r);
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) dst[ks] = p[ks];
     }
   };
-  auto request_lds = [&](int unit) __attribute__((always_inline)) {
-    const int T = unit_len(unit);
+  auto request_lds = [&](int unit, int T) __attribute__((always_inline)) {
     if (t0w < T) {
       const char* row = row_ptr(unit, T, t0w);
 #pragma unroll
@@ -209,10 +207,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_park_kernel(ParkArgs a) {
     }
   };
   if (cluster < a.s.d.units) {
-    request_lds(cluster);
-    request(cluster, 1, kv[0]);
-    request(cluster, 2, kv[1]);
-    request(cluster, 3, kv[2]);
+    const int T0 = unit_len(cluster);
+    request_lds(cluster, T0);
+    request(cluster, T0, 1, kv[0]);
+    request(cluster, T0, 2, kv[1]);
+    request(cluster, T0, 3, kv[2]);
   }
 #if AMS_PARK_STAGGER
   // the two workgroups of a CU come from the two halves of the grid: out of phase, one computes
@@ -226,6 +225,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_park_kernel(ParkArgs a) {
     unit_coords(a.s.d, unit, l, b, h);
     const int T = seq_len(a.s.d, a.s.seq_lens, b);
     const int next_unit = unit + a.n_clusters;
+    // the next unit's length is fetched here, far from where its keys are requested
+    const int T_next = next_unit < a.s.d.units ? unit_len(next_unit) : 0;
     PARK_MARK(0);
     __syncthreads();  // the previous unit is done with the LDS areas
     load_q<true, NB>(a.s, l, b, h, qlds);
@@ -456,13 +457,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_park_kernel(ParkArgs a) {
     if (t0w < T) usage_pair(std::true_type{}, 0, nullptr, kv[0]);
     asm volatile("" ::: "memory");
     if (next_unit < a.s.d.units) {
-      request_lds(next_unit);
-      request(next_unit, 1, kv[0]);
+      request_lds(next_unit, T_next);
+      request(next_unit, T_next, 1, kv[0]);
     }
     if (t0w + 64 < T) usage_pair(std::false_type{}, 1, kv[1], kv[2]);
     if (next_unit < a.s.d.units) {
-      request(next_unit, 2, kv[1]);
-      request(next_unit, 3, kv[2]);
+      request(next_unit, T_next, 2, kv[1]);
+      request(next_unit, T_next, 3, kv[2]);
     }
     __syncthreads();
     PARK_MARK(5);

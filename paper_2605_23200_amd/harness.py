@@ -50,7 +50,9 @@ class Job:
             self.dst = B.paged_view(self.K, self.V, self.dst_table)
             # the two views share base pointers on purpose; the library's aliasing check is for dense slabs
         else:
-            self.K, self.V = _dev(host["K"], device), _dev(host["V"], device)
+            # a caller that runs many jobs on one cache may upload it once and pass the device copies along
+            self.K = host["K_dev"] if "K_dev" in host else _dev(host["K"], device)
+            self.V = host["V_dev"] if "V_dev" in host else _dev(host["V"], device)
             self.Kd = torch.zeros((w.L, w.B, w.H, self.keep, w.D), dtype=self.K.dtype, device=device)
             self.Vd = torch.zeros_like(self.Kd)
             self.src = B.dense_view(self.K, self.V)
