@@ -205,6 +205,19 @@ int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* 
                      int32_t* bounds, float* seg_mass, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * ams_mass_segment_static - ams_mass_segment for callers that cannot allocate or carry a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same inputs, same
+ * outputs, same kernels, but the scratch (chunk totals and prefix values at the cuts) is an array that
+ * belongs to the library, 1 MiB per GPU, held until the process ends.  The call allocates nothing.
+ *   Limit: 256-byte-rounded units * ceil(t_max / 4096) * 8 + units * (n_segments + 1) * 8 bytes must fit
+ *   in 1 MiB (config 1: 51 KB); AMS_ERR_UNSUPPORTED otherwise, nothing launched.
+ *   All calls on one GPU share the array: calls that overlap in time on one GPU (different streams) race;
+ *   calls in stream order do not (every call rewrites what it reads).
+ */
+int ams_mass_segment_static(const ams_params* p, const int32_t* seq_lens, const float* m_used,
+                            int32_t* bounds, float* seg_mass, void* stream);
+
+/*
  * ams_select - segment quotas, in-segment top-k and the final kept set (Sec. 3.3
  * "Segment-wise Quota Allocation", "In-Segment Selection", must-keep rules; Alg. 1
  * steps 4-5).

@@ -26,7 +26,8 @@ SCORE_PATH_AUTO, SCORE_PATH_TWO_SWEEPS, SCORE_PATH_ONE_READ = 0, 1, 2
 
 EXPORTS = ("ams_status_string", "ams_workspace_bytes", "ams_workspace_layout", "ams_profile_begin",
            "ams_profile_end", "ams_score",
-           "ams_ema_update", "ams_mass_segment", "ams_select", "ams_compact", "ams_compress_step")
+           "ams_ema_update", "ams_mass_segment", "ams_mass_segment_static", "ams_select", "ams_compact",
+           "ams_compress_step")
 
 
 class AmsError(RuntimeError):
@@ -81,6 +82,7 @@ def lib() -> C.CDLL:
         l.ams_score.argtypes = [P, V, p, p, p, p, p, C.c_size_t, p]
         l.ams_ema_update.argtypes = [P, p, p, p, p, p, C.c_size_t, p]
         l.ams_mass_segment.argtypes = [P, p, p, p, p, p, C.c_size_t, p]
+        l.ams_mass_segment_static.argtypes = [P, p, p, p, p, p]
         l.ams_select.argtypes = [P, p, p, p, p, p, p, p, p, C.c_size_t, p]
         l.ams_compact.argtypes = [P, V, p, p, V, p, p, p]
         l.ams_compress_step.argtypes = [P, V, p, p, p, V, p, p, p, p, C.c_size_t, p]
@@ -179,6 +181,11 @@ def ams_mass_segment(p, seq_lens, m_used, bounds, seg_mass, ws=None, stream=None
     _check(lib().ams_mass_segment(C.byref(p), _ptr(seq_lens), _ptr(m_used), _ptr(bounds), _ptr(seg_mass),
                                   _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
                                   _stream(stream)), "ams_mass_segment")
+
+
+def ams_mass_segment_static(p, seq_lens, m_used, bounds, seg_mass, stream=None):
+    _check(lib().ams_mass_segment_static(C.byref(p), _ptr(seq_lens), _ptr(m_used), _ptr(bounds), _ptr(seg_mass),
+                                         _stream(stream)), "ams_mass_segment_static")
 
 
 def ams_select(p, seq_lens, g, bounds, seg_mass, quota, idx, n_kept, ws=None, stream=None):

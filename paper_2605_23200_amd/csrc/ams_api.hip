@@ -277,6 +277,25 @@ int ams_mass_segment(const ams_params* p, const int32_t* seq_lens, const float* 
                                    (hipStream_t)stream), (hipStream_t)stream);
 }
 
+int ams_mass_segment_static(const ams_params* p, const int32_t* seq_lens, const float* m_used,
+                            int32_t* bounds, float* seg_mass, void* stream) {
+  const int rc = check_params(p);
+  if (rc) return rc;
+  if (!seq_lens || !m_used || !bounds || !seg_mass) return AMS_ERR_INVALID_ARG;
+  // the chunk totals and the prefix values at the cuts live in the library's own array
+  WsLayout wl = ws_layout(p);
+  const size_t units = (size_t)p->n_layers * p->batch * p->n_kv_heads;
+  wl.vc_part = 0;  // not touched by the segmentation kernels
+  wl.mpart = 0;
+  wl.cpre = align256(units * (size_t)wl.n_chunks4k * sizeof(double));
+  const size_t need = wl.cpre + align256(units * (size_t)(p->n_segments + 1) * sizeof(double));
+  if (need > kStaticScratchBytes) return AMS_ERR_UNSUPPORTED;
+  char* scratch_ptr = nullptr;
+  if (static_scratch(&scratch_ptr) != hipSuccess) return AMS_ERR_HIP;
+  return hip_status(launch_segment(p, make_dims(p), seq_lens, m_used, bounds, seg_mass, scratch_ptr, wl,
+                                   (hipStream_t)stream), (hipStream_t)stream);
+}
+
 int ams_select(const ams_params* p, const int32_t* seq_lens, const float* g, const int32_t* bounds,
                const float* seg_mass, int32_t* quota, int32_t* idx, int32_t* n_kept,
                void* ws, size_t ws_bytes, void* stream) {

@@ -89,6 +89,11 @@ struct VcInfo {
 // right before a kernel launch, which records a HIP event on that stream.  Off: a single branch.
 void prof_mark(const char* label, hipStream_t s);
 
+// Scratch that belongs to the library (a __device__ array, one copy per GPU) for the entry point that may
+// not take a workspace: its size, and its address on the current device (looked up once per device).
+constexpr size_t kStaticScratchBytes = 1u << 20;
+hipError_t static_scratch(char** out);
+
 // ---- launchers (each returns hipGetLastError() of its launches) ----
 // credit and vc are optional: when vc is given, the scorer also leaves the per-chunk sums that
 // launch_ema needs in the workspace and describes them in *vc.

@@ -781,7 +781,28 @@ MsArgs make_args(const ams_params* p, const Dims& d, const int32_t* seq_lens, ch
   return a;
 }
 
+// Scratch of ams_mass_segment_static: device memory that belongs to the library and lives as long as the
+// process, one copy per GPU.  In host code the array's name is only a handle; the address that kernels and
+// copies may use comes from hipGetSymbolAddress, once per device, with that device current.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 }  // namespace
+
+hipError_t static_scratch(char** out) {
+  constexpr int kMaxDevices = 64;
+  static char* ptr[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if ((e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) != hipSuccess) return e;
+    ptr[dev] = (char*)p;
+  }
+  *out = ptr[dev];
+  return hipSuccess;
+}
 
 hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
                       float* credit, float* m_used, const VcInfo& vc, char* ws, const WsLayout& wl,
