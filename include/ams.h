@@ -68,10 +68,14 @@ typedef enum {
 typedef enum {
   AMS_SCORE_PATH_AUTO = 0,
   AMS_SCORE_PATH_TWO_SWEEPS = 1, /* K is streamed twice: statistics, then usage; every configuration  */
-  AMS_SCORE_PATH_ONE_READ = 2    /* K is read once and held on chip between the two products: bf16,
+  AMS_SCORE_PATH_ONE_READ = 2,   /* K is read once and held on chip between the two products: bf16,
                                     head_dim 128, at most 128 queries per KV head, dense layout, no
                                     causal window, mean-window / last-query / key-diversity scorers;
                                     AMS_ERR_UNSUPPORTED otherwise                                    */
+  AMS_SCORE_PATH_ONE_LAUNCH = 3  /* short caches (t_max <= 4096): one workgroup walks a unit's keys
+                                    twice in one launch; at most 128 queries per KV head, no causal
+                                    window, no moment-based scorer; AMS_ERR_UNSUPPORTED otherwise.
+                                    AUTO takes it when it applies and there are >= 128 units        */
 } ams_score_path;
 
 typedef enum {

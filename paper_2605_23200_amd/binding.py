@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 SCORER_LAST_QUERY, SCORER_MEAN_WINDOW, SCORER_KEYDIFF, SCORER_EXPECTED, SCORER_EXTERNAL = 0, 1, 2, 3, 4
 SCORER_EXPECTED_VNORM = 5
 LAYOUT_DENSE, LAYOUT_PAGED = 0, 1
-SCORE_PATH_AUTO, SCORE_PATH_TWO_SWEEPS, SCORE_PATH_ONE_READ = 0, 1, 2
+SCORE_PATH_AUTO, SCORE_PATH_TWO_SWEEPS, SCORE_PATH_ONE_READ, SCORE_PATH_ONE_LAUNCH = 0, 1, 2, 3
 
 EXPORTS = ("ams_status_string", "ams_workspace_bytes", "ams_workspace_layout", "ams_profile_begin",
            "ams_profile_end", "ams_score",

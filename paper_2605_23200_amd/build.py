@@ -10,7 +10,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libams.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
-SOURCES = ["ams_api.hip", "score.hip", "score_park.hip", "mass_segment.hip", "select.hip", "compact.hip"]
+SOURCES = ["ams_api.hip", "score.hip", "score_park.hip", "score_unit.hip", "mass_segment.hip", "select.hip", "compact.hip"]
 
 # -ffp-contract=off: multiply-adds are fused only where the source says fmaf(), so that host-checkable
 # double arithmetic (quotas, normalisers) rounds exactly like plain C.

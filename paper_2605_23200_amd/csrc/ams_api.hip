@@ -91,7 +91,7 @@ static int check_params(const ams_params* p) {
     return AMS_ERR_INVALID_ARG;
   if (p->scorer < AMS_SCORER_LAST_QUERY || p->scorer > AMS_SCORER_EXPECTED_VNORM) return AMS_ERR_INVALID_ARG;
   if (p->scorer == AMS_SCORER_EXPECTED_VNORM && !(p->vnorm_eps >= 0.f)) return AMS_ERR_INVALID_ARG;
-  if (p->score_path < AMS_SCORE_PATH_AUTO || p->score_path > AMS_SCORE_PATH_ONE_READ) return AMS_ERR_INVALID_ARG;
+  if (p->score_path < AMS_SCORE_PATH_AUTO || p->score_path > AMS_SCORE_PATH_ONE_LAUNCH) return AMS_ERR_INVALID_ARG;
   if (p->head_dim != 64 && p->head_dim != 128) return AMS_ERR_UNSUPPORTED;
   if (p->n_segments > 1024) return AMS_ERR_UNSUPPORTED;
   const int64_t units = (int64_t)p->n_layers * p->batch * p->n_kv_heads;

@@ -111,6 +111,12 @@ hipError_t launch_score_oneread(const ams_params* p, const Dims& d, const KvDev&
                                 const void* q, float* u, float* g, const float* credit, bool want_vc,
                                 int* vc_stride, int* vc_tokens, char* ws, const WsLayout& wl,
                                 hipStream_t s, bool* ran);
+// The one-launch scorer for short caches (score_unit.hip); *ran = false when it does not apply.  It leaves
+// one (sum of max(u,0)+eps, sum of old credit) entry per unit at a.vc_part[unit] when a.vc_part is set.
+struct ScoreArgs;
+hipError_t launch_score_unit(const ScoreArgs& a, bool bf16, int head_dim, int mode, hipStream_t s, bool* ran);
+constexpr int kUnitScorerMinUnits = 128;  // fewer units leave most of the 256 CUs idle: the sweeps win there
+
 // The chunked kernels behind ams_ema_update and ams_mass_segment (the fused step uses launch_unit_mass).
 hipError_t launch_ema(const ams_params* p, const Dims& d, const int32_t* seq_lens, const float* u,
                       float* credit, float* m_used, const VcInfo& vc, char* ws, const WsLayout& wl,

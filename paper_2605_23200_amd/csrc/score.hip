@@ -644,19 +644,14 @@ __global__ __launch_bounds__(kThreads) void vweight_kernel(ScoreArgs a, KvDev v,
     g_row[t] = (float)((exp((double)g_row[t] - M) * inv_z + eps) * sqrt((double)norm2[t - c0]));
 }
 
-template <typename K>
-hipError_t set_lds(K kernel, int bytes) {
-  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-}
-
 template <bool BF16, int NB, bool TAIL, int HD>
 hipError_t launch_stats(const ScoreArgs& a, bool moments, dim3 grid, int lds, hipStream_t s) {
   hipError_t e;
   if (moments) {
-    if ((e = set_lds(score_stats_kernel<BF16, NB, TAIL, true, HD>, lds)) != hipSuccess) return e;
+    if ((e = ensure_lds<score_stats_kernel<BF16, NB, TAIL, true, HD>>(lds)) != hipSuccess) return e;
     hipLaunchKernelGGL((score_stats_kernel<BF16, NB, TAIL, true, HD>), grid, dim3(kThreads), lds, s, a);
   } else {
-    if ((e = set_lds(score_stats_kernel<BF16, NB, TAIL, false, HD>, lds)) != hipSuccess) return e;
+    if ((e = ensure_lds<score_stats_kernel<BF16, NB, TAIL, false, HD>>(lds)) != hipSuccess) return e;
     hipLaunchKernelGGL((score_stats_kernel<BF16, NB, TAIL, false, HD>), grid, dim3(kThreads), lds, s, a);
   }
   return hipGetLastError();
@@ -668,11 +663,11 @@ hipError_t launch_usage(const ScoreArgs& a, int mode, dim3 grid, int lds, hipStr
   hipError_t e;
   switch (mode) {
     case MODE_LAST:
-      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_LAST, TAIL, HD>, lds)) != hipSuccess) return e;
+      if ((e = ensure_lds<score_usage_kernel<BF16, NB, MODE_LAST, TAIL, HD>>(lds)) != hipSuccess) return e;
       hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_LAST, TAIL, HD>), grid, blk, lds, s, a);
       break;
     default:
-      if ((e = set_lds(score_usage_kernel<BF16, NB, MODE_MEAN, TAIL, HD>, lds)) != hipSuccess) return e;
+      if ((e = ensure_lds<score_usage_kernel<BF16, NB, MODE_MEAN, TAIL, HD>>(lds)) != hipSuccess) return e;
       hipLaunchKernelGGL((score_usage_kernel<BF16, NB, MODE_MEAN, TAIL, HD>), grid, blk, lds, s, a);
   }
   return hipGetLastError();
@@ -781,6 +776,18 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
                              &oneread);
   if (e != hipSuccess) return e;
   if (!oneread && p->score_path == AMS_SCORE_PATH_ONE_READ) return hipErrorNotSupported;
+  if (!oneread) {
+    // short caches with enough units to fill the chip: one workgroup per unit, one launch
+    const bool want_unit = p->score_path == AMS_SCORE_PATH_ONE_LAUNCH ||
+                           (p->score_path == AMS_SCORE_PATH_AUTO && d.units >= kUnitScorerMinUnits);
+    if (want_unit) {
+      e = launch_score_unit(a, bf16, d.D, mode, s, &oneread);
+      if (e != hipSuccess) return e;
+      vc_stride = 1;
+      vc_tokens = kScoreChunk;
+    }
+    if (!oneread && p->score_path == AMS_SCORE_PATH_ONE_LAUNCH) return hipErrorNotSupported;
+  }
   if (!oneread) {
     if (d.D == 64)
       e = bf16 ? run_by_nb<true, 64>(a, nb, mode, s) : run_by_nb<false, 64>(a, nb, mode, s);

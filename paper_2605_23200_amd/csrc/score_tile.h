@@ -41,6 +41,21 @@ struct ScoreArgs {
   int32_t* status;  // word the one-read scorer raises when a bounded wait expires; the two-sweep path clears it
 };
 
+// Raises a kernel's dynamic LDS limit once per kernel and device (not before every launch).
+template <auto Kernel>
+inline hipError_t ensure_lds(int bytes) {
+  constexpr int kMaxDevices = 64;
+  static int granted[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (granted[dev] >= bytes) return hipSuccess;
+  e = hipFuncSetAttribute((const void*)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) granted[dev] = bytes;
+  return e;
+}
+
 // Row geometry of a cache of HD channels: bytes per row, stride of a query row in LDS (padded by
 // 16 bytes against bank conflicts), 16-byte vectors per half row (what one lane feeds the MFMA).
 template <bool BF16, int HD = 128>

@@ -57,7 +57,7 @@ def test_workspace_bytes_and_layout():
     ("seg_delta", 1e-4, B.ERR_INVALID_ARG),            # more than 1024 initial segments
     ("seg_delta", 0.05, B.ERR_INVALID_ARG),            # 20 initial segments do not fit the 8 entries
     ("l_max", 64, B.ERR_INVALID_ARG),                  # length rules without a target mass
-    ("score_path", 3, B.ERR_INVALID_ARG), ("score_path", -1, B.ERR_INVALID_ARG)])
+    ("score_path", 4, B.ERR_INVALID_ARG), ("score_path", -1, B.ERR_INVALID_ARG)])
 def test_bad_params_are_rejected_on_the_host(field, value, status):
     p = _good()
     setattr(p, field, value)
@@ -70,7 +70,7 @@ def test_bad_params_are_rejected_on_the_host(field, value, status):
 
 def test_score_path_field():
     p = _good()
-    for path in (B.SCORE_PATH_AUTO, B.SCORE_PATH_TWO_SWEEPS, B.SCORE_PATH_ONE_READ):
+    for path in (B.SCORE_PATH_AUTO, B.SCORE_PATH_TWO_SWEEPS, B.SCORE_PATH_ONE_READ, B.SCORE_PATH_ONE_LAUNCH):
         p.score_path = path
         assert B.ams_workspace_bytes(p) > 0            # the workspace does not depend on the path
 

@@ -602,6 +602,52 @@ def test_both_score_paths(oracle, scorer):
     np.testing.assert_allclose(us[B.SCORE_PATH_ONE_READ], us[B.SCORE_PATH_TWO_SWEEPS], rtol=2e-5, atol=1e-12)
 
 
+@pytest.mark.parametrize("scorer", [B.SCORER_MEAN_WINDOW, B.SCORER_LAST_QUERY, B.SCORER_KEYDIFF])
+@pytest.mark.parametrize("dtype,D,G,W,T,paged", [("bf16", 128, 4, 32, 2176, False), ("bf16", 128, 4, 32, 4096, False),
+                                                  ("f32", 128, 1, 8, 1280, False), ("bf16", 64, 2, 16, 3000, False),
+                                                  ("f32", 64, 3, 5, 257, False), ("bf16", 128, 4, 32, 1, False),
+                                                  ("bf16", 128, 4, 32, 2500, True)])
+def test_one_launch_score_path(oracle, scorer, dtype, D, G, W, T, paged):
+    """Short caches through the pinned one-launch scorer (one workgroup walks a unit's keys twice): the whole
+    event against the oracle on every unit, and the usage equal to the two sweeps' to rounding."""
+    w = inputs.CONFIGS[1].scaled(L=2, H=3, T=T, D=D, G=G, W=W, dtype=dtype, budget=min(256, T), S=8, n_spans=3,
+                                 span_len=(8, 100), paged=paged)
+    host = inputs.dense_cache(w, n_threads=4)
+    us = {}
+    for path, ran in ((B.SCORE_PATH_ONE_LAUNCH, "score_unit"), (B.SCORE_PATH_TWO_SWEEPS, "score_stats")):
+        job = Job(w, host, scorer=scorer, score_path=path)
+        B.ams_profile_begin()
+        job.step()
+        labels = [k for k, _ in B.ams_profile_end()]
+        assert ran in labels and ("score_stats" in labels) == (ran == "score_stats")
+        check_properties_all_units(job)
+        check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), list(range(w.units)), scorer=scorer)
+        us[path] = job.intermediates().u[:, :w.T].cpu().numpy()
+    np.testing.assert_allclose(us[B.SCORE_PATH_ONE_LAUNCH], us[B.SCORE_PATH_TWO_SWEEPS], rtol=2e-5, atol=1e-12)
+
+
+def test_one_launch_path_ragged_batch_and_auto(oracle):
+    """A ragged batch (lengths 0, 1, 31, 300, 2049, 4096) through the one-launch scorer; with at least 128 units
+    the library takes that path by itself, with fewer it keeps the two sweeps."""
+    w = inputs.CONFIGS[2].scaled(L=1, B=6, H=2, T=4096, T_min=None, paged=False, budget=128, S=4, n_spans=2,
+                                 span_len=(4, 40))
+    host = inputs.dense_cache(w, n_threads=4)
+    host["seq_lens"] = np.array([0, 1, 31, 300, 2049, 4096], np.int32)
+    job = Job(w, host, score_path=B.SCORE_PATH_ONE_LAUNCH)
+    job.step()
+    torch.cuda.synchronize()
+    nk, idx = to_host(job.n_kept), to_host(job.idx)
+    assert (nk[:2] == 0).all() and (idx[:2] == -1).all()               # the empty sequence keeps nothing
+    check_units(oracle, job, host, np.zeros((w.units, job.t_max), np.float32), [i for i in range(w.units) if i >= 2])
+    for L, label in ((16, "score_unit"), (4, "score_stats")):          # 128 units / 32 units
+        wa = inputs.CONFIGS[1].scaled(L=L, H=8, T=1500, budget=128, S=4, n_spans=2, span_len=(4, 40))
+        ja = Job(wa, inputs.dense_cache(wa, n_threads=8))
+        B.ams_profile_begin()
+        ja.step()
+        assert label in [k for k, _ in B.ams_profile_end()]
+        check_properties_all_units(ja)
+
+
 def test_one_read_path_says_when_it_does_not_apply():
     """A pinned one-read path is refused (AMS_ERR_UNSUPPORTED, nothing half done) where only the two sweeps
     exist: fp32 caches, the causal window, the moment-based scorers."""
@@ -614,6 +660,12 @@ def test_one_read_path_says_when_it_does_not_apply():
             job.step()
         assert err.value.status == B.ERR_UNSUPPORTED
         Job(w, host, scorer=scorer, score_path=B.SCORE_PATH_AUTO).step()      # the library's own choice works
+    for w, scorer in ((base.scaled(T=5000), B.SCORER_MEAN_WINDOW), (base.scaled(causal=True), B.SCORER_MEAN_WINDOW),
+                      (base, B.SCORER_EXPECTED)):                             # the one-launch path: short caches only
+        job = Job(w, inputs.dense_cache(w, n_threads=2), scorer=scorer, score_path=B.SCORE_PATH_ONE_LAUNCH)
+        with pytest.raises(B.AmsError) as err:
+            job.step()
+        assert err.value.status == B.ERR_UNSUPPORTED
     torch.cuda.synchronize()
 
 
