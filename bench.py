@@ -48,6 +48,7 @@ def kernel_bytes(label, w, lens=None):
         "score_usage": tok * D * e + 4 * tok,             # K stream + u
         "score_reduce": 0,
         "score_oneread": tok * D * e + 4 * tok * 2,       # K stream once, u out, old credit in (for its sum)
+        "score_unit": tok * D * e + 4 * tok * 2,          # short caches: K counted once (the second walk hits the caches)
         "mass_ema": 4 * tok * 4,                          # u, credit in; credit, m_used out
         "unit_mass": 4 * tok * 4,                         # the same, with the scan and the quotas in the same launch
         "segment_scan": 4 * tok,                          # m_used in
