@@ -4,9 +4,12 @@ The paper reports, for its own models and datasets, a region wipe-out rate, the 
 between consecutive compression events and the number / length of adaptive segments.  None of that
 data exists here; this module re-creates the *metrics* on the seeded synthetic caches of
 `inputs.py` so that segment-wise allocation (S > 1) can be compared with a global top-k (S = 1) and
-the EMA credit switched on and off.  The paper does not define the wipe-out rate precisely; here a
-region is a window of `region` consecutive original positions, and it is wiped out by an event when
-it had tokens in the cache before the event and none after it.
+the EMA credit switched on and off.  The paper does not define the wipe-out rate precisely.  Two
+readings are computed here: over the PLANTED SPANS of the synthetic cache (the stand-ins for the
+paper's dense-attention regions) -- a span is wiped out by an event when it had tokens in the cache
+before the event and none after it, and the cumulative figure is the fraction of planted spans with
+no token left after the last event -- and over fixed windows of `region` consecutive original
+positions, the same way.
 
 The metric functions are plain numpy on index sets.  `run_trajectory` drives the HIP library through
 the same C ABI as everything else (there is no other implementation of the method in this package).
@@ -27,6 +30,20 @@ def region_wipeout_rate(present: np.ndarray, kept: np.ndarray, region: int) -> f
     if len(before) == 0:
         return 0.0
     return float(len(np.setdiff1d(before, after, assume_unique=True)) / len(before))
+
+
+def span_wipeout(spans: np.ndarray, present: np.ndarray, kept: np.ndarray):
+    """spans: rows (start, stop, ...) in original positions.  Returns (spans that had a token in `present`,
+    spans among those with no token in `kept`)."""
+    present, kept = np.sort(np.asarray(present)), np.sort(np.asarray(kept))
+    had = gone = 0
+    for row in np.asarray(spans):
+        st, en = int(row[0]), int(row[1])
+        n_before = np.searchsorted(present, en) - np.searchsorted(present, st)
+        if n_before > 0:
+            had += 1
+            gone += int(np.searchsorted(kept, en) - np.searchsorted(kept, st) == 0)
+    return had, gone
 
 
 def retained_iou(kept_a: np.ndarray, kept_b: np.ndarray) -> float:
@@ -126,12 +143,21 @@ def run_trajectory(w, *, n_events: int, scorer=None, device: str = "cuda:0") -> 
     return out
 
 
-def summarize(records: List[EventRecord], region: int = 64) -> dict:
-    """Means over units and events of the metrics above."""
+def summarize(records: List[EventRecord], region: int = 64, unit_spans=None) -> dict:
+    """Means over units and events of the metrics above.  unit_spans: per unit the planted spans (rows
+    start, stop, ...) for the span wipe-out figures."""
     wipe, iou, nseg, slen, middle = [], [], [], [], []
+    span_had = span_gone = span_total = span_dead = 0
     for e, rec in enumerate(records):
         for i in range(len(rec.kept)):
             wipe.append(region_wipeout_rate(rec.present[i], rec.kept[i], region))
+            if unit_spans is not None:
+                had, gone = span_wipeout(unit_spans[i], rec.present[i], rec.kept[i])
+                span_had += had
+                span_gone += gone
+                if e + 1 == len(records):          # planted spans with nothing left at the end of the trajectory
+                    span_total += len(unit_spans[i])
+                    span_dead += len(unit_spans[i]) - span_wipeout(unit_spans[i], rec.kept[i], rec.kept[i])[0]
             n, m = segment_stats(rec.bounds[i])
             nseg.append(n)
             slen.append(m)
@@ -139,9 +165,17 @@ def summarize(records: List[EventRecord], region: int = 64) -> dict:
             middle.append(prof[3:7].mean())
             if e > 0:
                 iou.append(retained_iou(records[e - 1].kept[i], rec.kept[i]))
-    return {"region_wipeout_rate": float(np.mean(wipe)), "retained_iou": float(np.mean(iou)) if iou else None,
+    return {"span_wipeout_rate": span_gone / span_had if span_had else None,
+            "spans_lost_at_end": span_dead / span_total if span_total else None,
+            "region_wipeout_rate": float(np.mean(wipe)), "retained_iou": float(np.mean(iou)) if iou else None,
             "avg_segments": float(np.mean(nseg)), "avg_segment_len": float(np.mean(slen)),
             "middle_retention": float(np.mean(middle)), "region": region}
+
+
+def planted_spans(w) -> list:
+    """Per unit the planted spans of its sequence (positions of the initial cache)."""
+    from . import inputs
+    return [inputs.spans(w, b, w.T) for (l, b, h) in inputs.unit_ids(w)]
 
 
 def main():
@@ -149,6 +183,8 @@ def main():
     ap.add_argument("--config", type=int, default=0)
     ap.add_argument("--events", type=int, default=4)
     ap.add_argument("--region", type=int, default=64)
+    ap.add_argument("--budget", type=int, default=0, help="override the workload's budget (0 = keep it)")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = keep it)")
     args = ap.parse_args()
     from . import binding as B
     from . import inputs
@@ -156,12 +192,17 @@ def main():
     base = inputs.CONFIGS[args.config]
     if base.paged or base.T_min is not None:
         raise SystemExit("dense single-length workloads only")
+    if args.budget:
+        base = base.scaled(budget=args.budget)
+    if args.layers:
+        base = base.scaled(L=args.layers)
     if base.n_append == 0:
         base = base.scaled(n_append=base.budget // 4)
-    variants = {"ams": base, "global_topk (S=1)": base.scaled(S=1), "ams, no credit (lambda=0)": base.scaled(lam=0.0)}
+    variants = {"ams": base, "global_topk (S=1)": base.scaled(S=1), "ams, no credit (lambda=0)": base.scaled(lam=0.0),
+                "global_topk, no credit": base.scaled(S=1, lam=0.0)}
     for name, w in variants.items():
         for sc_name, sc in (("mean_window", B.SCORER_MEAN_WINDOW), ("last_query", B.SCORER_LAST_QUERY)):
-            s = summarize(run_trajectory(w, n_events=args.events, scorer=sc), args.region)
+            s = summarize(run_trajectory(w, n_events=args.events, scorer=sc), args.region, planted_spans(w))
             print(json.dumps({"variant": name, "scorer": sc_name, **s}))
 
 
