@@ -155,6 +155,42 @@ int amso_value_weight(const float* e, const float* V, int T, int D, float eps, f
   return 0;
 }
 
+// Redundancy-aware score: importance minus a softmax-normalised mean cosine similarity to the other keys.
+int amso_redundancy_score(const float* u, const float* K, int T, int D, float mix_lambda, int kernel, float* g) {
+  if (!u || !K || !g || T < 1 || D < 1 || !(mix_lambda >= 0.0f && mix_lambda <= 1.0f)) return -1;
+  if (kernel < 0 || (kernel > 1 && kernel % 2 == 0)) return -1;
+  std::vector<float> a(u, u + T);
+  if (kernel > 1) {
+    const int rc = amso_pool(u, T, kernel, a.data());
+    if (rc) return rc;
+  }
+  std::vector<double> norm((size_t)T);
+  for (int t = 0; t < T; ++t) {
+    double n2 = 0.0;
+    for (int d = 0; d < D; ++d) n2 += (double)K[(size_t)t * D + d] * (double)K[(size_t)t * D + d];
+    norm[t] = std::sqrt(n2);
+  }
+  std::vector<double> r((size_t)T, 0.0);
+  for (int t = 0; t < T && T > 1; ++t) {
+    double acc = 0.0;
+    for (int s = 0; s < T; ++s) {
+      if (s == t) continue;
+      double dot = 0.0;
+      for (int d = 0; d < D; ++d) dot += (double)K[(size_t)t * D + d] * (double)K[(size_t)s * D + d];
+      const double den = norm[t] * norm[s];
+      acc += den > 0.0 ? dot / den : 0.0;
+    }
+    r[t] = acc / (double)(T - 1);
+  }
+  double rmax = -INFINITY;
+  for (int t = 0; t < T; ++t) rmax = std::max(rmax, r[t]);
+  double z = 0.0;
+  for (int t = 0; t < T; ++t) z += std::exp(r[t] - rmax);
+  const double lam = (double)mix_lambda;
+  for (int t = 0; t < T; ++t) g[t] = (float)(lam * (double)a[t] - (1.0 - lam) * (std::exp(r[t] - rmax) / z));
+  return 0;
+}
+
 // Eq. (1).
 int amso_mass(const float* u, int T, float eps, float* m_cur) {
   if (!u || !m_cur || T < 1 || !(eps > 0.0f)) return -1;
@@ -508,10 +544,13 @@ int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K
   std::vector<float> u_((size_t)T), g_((size_t)T), mc((size_t)T), mu((size_t)T), sm((size_t)S);
   std::vector<int32_t> bd((size_t)S + 1), qt((size_t)S);
   int rc;
-  const bool vnorm = p->scorer == AMSO_SCORER_EXPECTED_VNORM;
+  const bool vnorm = p->scorer == AMSO_SCORER_EXPECTED_VNORM, redun = p->scorer == AMSO_SCORER_REDUNDANCY;
   if (vnorm && !V) return -1;
-  if ((rc = amso_score(Q, K, p->G, p->W, T, p->D, vnorm ? AMSO_SCORER_EXPECTED : p->scorer, p->causal, u_.data(),
-                       g_.data())))
+  if ((rc = amso_score(Q, K, p->G, p->W, T, p->D,
+                       vnorm ? AMSO_SCORER_EXPECTED : (redun ? AMSO_SCORER_MEAN_WINDOW : p->scorer), p->causal,
+                       u_.data(), g_.data())))
+    return rc;
+  if (redun && (rc = amso_redundancy_score(u_.data(), K, T, p->D, p->mix_lambda, p->score_kernel, g_.data())))
     return rc;
   if (vnorm) {
     std::vector<float> e(g_);

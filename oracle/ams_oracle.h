@@ -24,7 +24,8 @@
  * trimmed or backfilled; the split / merge rules of amso_segment_adaptive
  * (the paper says "roughly equal" and "a neighboring segment") and the edge
  * handling of amso_pool; the form of the value weighting in amso_value_weight
- * (the paper names the scorer and its epsilon only).
+ * (the paper names the scorer and its epsilon only); the whole form of
+ * amso_redundancy_score (the paper gives one sentence and four parameter names).
  */
 #ifndef AMS_ORACLE_H
 #define AMS_ORACLE_H
@@ -40,7 +41,8 @@ enum {
   AMSO_SCORER_MEAN_WINDOW = 1, /* the usage u itself                            */
   AMSO_SCORER_KEYDIFF = 2,     /* negative cosine to the mean key               */
   AMSO_SCORER_EXPECTED = 3,    /* log Gaussian moment of the query window       */
-  AMSO_SCORER_EXPECTED_VNORM = 5 /* amso_value_weight of the above (whole event only) */
+  AMSO_SCORER_EXPECTED_VNORM = 5, /* amso_value_weight of the above (whole event only) */
+  AMSO_SCORER_REDUNDANCY = 6   /* amso_redundancy_score of the usage (whole event only)  */
 };
 
 /* Step 1 of Alg. 1 (usage) + the plug-in base score g (Sec. 3.3 "In-Segment
@@ -56,6 +58,18 @@ int amso_score(const float* Q, const float* K, int G, int W, int T, int D,
 /* Value-weighted expected attention: p = softmax over the cache of the log-moment
  * scores e [T]; g_t = (p_t + eps) * ||v_t||_2 with V [T][D] widened to float. */
 int amso_value_weight(const float* e, const float* V, int T, int D, float eps, float* g);
+
+/* Redundancy-aware score (Sec. 4 "Universality across diverse base scorers"; App. "Baseline
+ * Configurations": recent attention importance combined with a cosine-similarity-based
+ * redundancy penalty over the cached keys, parameters window 8, kernel 7, lambda 0.07).
+ * Reading taken here:
+ *   a   = u, or with kernel > 1 (odd) the amso_pool of u          (recent attention importance)
+ *   r_t = mean over s != t of cos(k_t, k_s)  (0 for T == 1; a zero key has cosine 0 to everything)
+ *   p   = softmax over t of r                                      (redundancy, on the scale of a: sums to 1)
+ *   g_t = mix_lambda * a_t - (1 - mix_lambda) * p_t.
+ * K [T][D] widened to float.  O(T^2 D): the definition written out. */
+int amso_redundancy_score(const float* u, const float* K, int T, int D, float mix_lambda, int kernel,
+                          float* g);
 
 /* Eq. (1): m_t = (max(u_t,0)+eps) / sum_v (max(u_v,0)+eps). */
 int amso_mass(const float* u, int T, float eps, float* m_cur);
@@ -137,6 +151,8 @@ typedef struct {
   int l_min, l_max;   /* with delta > 0 */
   int pool_kernel;    /* > 1: amso_pool before Eq. (1) */
   float vnorm_eps;    /* eps of amso_value_weight (scorer AMSO_SCORER_EXPECTED_VNORM) */
+  float mix_lambda;   /* amso_redundancy_score (scorer AMSO_SCORER_REDUNDANCY) */
+  int score_kernel;   /* its pooling kernel (odd; 0 or 1 = none) */
 } amso_unit_params;
 
 int amso_compress_unit(const amso_unit_params* p, const float* Q, const float* K,

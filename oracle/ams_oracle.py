@@ -13,6 +13,7 @@ from . import build as _build
 
 SCORER_LAST_QUERY, SCORER_MEAN_WINDOW, SCORER_KEYDIFF, SCORER_EXPECTED = 0, 1, 2, 3
 SCORER_EXPECTED_VNORM = 5
+SCORER_REDUNDANCY = 6
 
 _lib = None
 
@@ -23,7 +24,7 @@ class _UnitParams(C.Structure):
                 ("lam", C.c_float), ("beta", C.c_float), ("eps", C.c_float),
                 ("n_sink", C.c_int), ("n_last", C.c_int), ("causal", C.c_int),
                 ("delta", C.c_float), ("l_min", C.c_int), ("l_max", C.c_int), ("pool_kernel", C.c_int),
-                ("vnorm_eps", C.c_float)]
+                ("vnorm_eps", C.c_float), ("mix_lambda", C.c_float), ("score_kernel", C.c_int)]
 
 
 def lib():
@@ -75,6 +76,17 @@ def value_weight(e, V, eps=1e-2):
     V = np.ascontiguousarray(widen(V))
     g = np.empty_like(e)
     _chk(lib().amso_value_weight(_f(e), _f(V), V.shape[0], V.shape[1], C.c_float(eps), _f(g)), "value_weight")
+    return g
+
+
+def redundancy_score(u, K, mix_lambda=0.07, kernel=7):
+    """u [T], K [T, D] (float32 or bf16 bits) -> g [T]: mix_lambda * pooled u - (1 - mix_lambda) * softmax of the
+    mean cosine similarity of a key to the other keys."""
+    Kf = np.ascontiguousarray(widen(K))
+    u = np.ascontiguousarray(u, dtype=np.float32)
+    T, D = Kf.shape
+    g = np.empty(T, np.float32)
+    _chk(lib().amso_redundancy_score(_f(u), _f(Kf), T, D, C.c_float(mix_lambda), int(kernel), _f(g)), "redundancy_score")
     return g
 
 
@@ -193,7 +205,7 @@ def compact_paged(K_pool, V_pool, src_table, K_pool_out, V_pool_out, dst_table, 
 
 def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_min=1,
                   scorer=SCORER_MEAN_WINDOW, n_sink=0, n_last=0, causal=False, delta=0.0, l_min=0, l_max=0,
-                  pool_kernel=0, vnorm_eps=1e-2):
+                  pool_kernel=0, vnorm_eps=1e-2, mix_lambda=0.07, score_kernel=7):
     """One whole event for one unit.  K, V [T, D] in storage dtype (float32 or
     uint16 = bf16 bits).  Returns a dict with every intermediate."""
     Kf = np.ascontiguousarray(widen(K))
@@ -204,7 +216,7 @@ def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, 
     kept = min(budget, T)
     p = _UnitParams(G, W, T, D, int(scorer), int(budget), int(S), int(q_min), lam, beta, eps,
                     int(n_sink), int(n_last), int(bool(causal)), delta, int(l_min), int(l_max), int(pool_kernel),
-                    vnorm_eps)
+                    vnorm_eps, mix_lambda, int(score_kernel))
     Vf = np.ascontiguousarray(widen(V)) if int(scorer) == SCORER_EXPECTED_VNORM else None
     c = np.array(credit, dtype=np.float32, copy=True)
     out = dict(u=np.empty(T, np.float32), g=np.empty(T, np.float32), m_used=np.empty(T, np.float32),
@@ -228,7 +240,7 @@ def compress_unit(Q, K, V, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, 
 def compress_many(Q, K, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_min=1,
                   scorer=SCORER_MEAN_WINDOW, n_threads=0, want_scores=False, K_rows=None, V_rows=None,
                   n_sink=0, n_last=0, causal=False, delta=0.0, l_min=0, l_max=0, pool_kernel=0, vnorm_eps=1e-2,
-                  V=None):
+                  V=None, mix_lambda=0.07, score_kernel=7):
     """Q [U, G*W, D], K [U, T, D] float32 (already widened), credit [U, T] (updated in
     place).  K_rows, V_rows [U, T, D] in the storage dtype: when given, the kept rows are
     gathered as well (whole event).  Returns (idx [U, budget], n_kept [U], threads_used[, u, g])."""
@@ -238,7 +250,7 @@ def compress_many(Q, K, credit, *, G, W, budget, S, lam, beta=0.9, eps=1e-6, q_m
         assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"]
     p = _UnitParams(G, W, T, D, int(scorer), int(budget), int(S), int(q_min), lam, beta, eps,
                     int(n_sink), int(n_last), int(bool(causal)), delta, int(l_min), int(l_max), int(pool_kernel),
-                    vnorm_eps)
+                    vnorm_eps, mix_lambda, int(score_kernel))
     if int(scorer) == SCORER_EXPECTED_VNORM:
         assert V is not None and V.shape == K.shape and V.dtype == np.float32 and V.flags["C_CONTIGUOUS"]
     idx = np.empty((U, budget), np.int32)
