@@ -57,9 +57,13 @@ typedef enum {
   AMS_SCORER_KEYDIFF = 2,     /* negative cosine between a key and the mean key            */
   AMS_SCORER_EXPECTED = 3,    /* log Gaussian moment of the window's query distribution    */
   AMS_SCORER_EXTERNAL = 4,    /* caller supplies g (stage calls only)                      */
-  AMS_SCORER_EXPECTED_VNORM = 5 /* value-weighted expected attention: p = softmax over the
+  AMS_SCORER_EXPECTED_VNORM = 5, /* value-weighted expected attention: p = softmax over the
                                    cache of the AMS_SCORER_EXPECTED scores,
                                    g = (p + vnorm_eps) * ||v||_2; reads V                  */
+  AMS_SCORER_REDUNDANCY = 6   /* redundancy-aware score (Sec. 4 "Universality across diverse base
+                                 scorers"): g = mix_lambda * a - (1 - mix_lambda) * p, a = u (averaged
+                                 over score_kernel positions when that is > 1), p = softmax over the
+                                 cache of r_t = mean cosine similarity of key t to the unit's other keys */
 } ams_scorer;
 
 /* How ams_score / ams_compress_step form the softmax statistics (the results agree to rounding;
@@ -112,6 +116,10 @@ typedef struct {
   int32_t pool_kernel;/* odd k > 1: Eq. (1) sees the k-point centred mean of u (App. A); 0/1 = off */
   float vnorm_eps;    /* epsilon of AMS_SCORER_EXPECTED_VNORM, >= 0 (1e-2 in the paper's runs) */
   int32_t score_path; /* ams_score_path; 0 = the library chooses                                   */
+  float mix_lambda;   /* AMS_SCORER_REDUNDANCY: weight of the importance term, in [0, 1] (0.07 in the
+                         paper's runs)                                                              */
+  int32_t score_kernel; /* AMS_SCORER_REDUNDANCY: odd k > 1 averages u over k positions first (7 in
+                         the paper's runs); 0 / 1 = off                                            */
 } ams_params;
 
 /* A KV cache as the library sees it.  Plain data, [host]; k, v, block_table [dev]. */

@@ -21,6 +21,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_HIP = 0, 1, 2
 F32, BF16 = 0, 1
 SCORER_LAST_QUERY, SCORER_MEAN_WINDOW, SCORER_KEYDIFF, SCORER_EXPECTED, SCORER_EXTERNAL = 0, 1, 2, 3, 4
 SCORER_EXPECTED_VNORM = 5
+SCORER_REDUNDANCY = 6
 LAYOUT_DENSE, LAYOUT_PAGED = 0, 1
 SCORE_PATH_AUTO, SCORE_PATH_TWO_SWEEPS, SCORE_PATH_ONE_READ, SCORE_PATH_ONE_LAUNCH = 0, 1, 2, 3
 
@@ -44,7 +45,8 @@ class Params(C.Structure):
                 ("ema_lambda", C.c_float), ("ema_beta", C.c_float), ("mass_eps", C.c_float),
                 ("scorer", C.c_int32), ("n_sink", C.c_int32), ("n_last", C.c_int32), ("causal", C.c_int32),
                 ("seg_delta", C.c_float), ("l_min", C.c_int32), ("l_max", C.c_int32), ("pool_kernel", C.c_int32),
-                ("vnorm_eps", C.c_float), ("score_path", C.c_int32)]
+                ("vnorm_eps", C.c_float), ("score_path", C.c_int32),
+                ("mix_lambda", C.c_float), ("score_kernel", C.c_int32)]
 
     @property
     def units(self) -> int:
@@ -120,11 +122,13 @@ def _check(rc: int, what: str):
 def make_params(*, n_layers, batch, n_kv_heads, group, window, head_dim=128, kv_dtype=BF16, t_max,
                 t_stride=None, budget, n_segments, q_min=1, ema_lambda=0.9, ema_beta=0.9, mass_eps=1e-6,
                 scorer=SCORER_MEAN_WINDOW, n_sink=0, n_last=0, causal=False, seg_delta=0.0, l_min=0, l_max=0,
-                pool_kernel=0, vnorm_eps=1e-2, score_path=SCORE_PATH_AUTO) -> Params:
+                pool_kernel=0, vnorm_eps=1e-2, score_path=SCORE_PATH_AUTO,
+                mix_lambda=0.07, score_kernel=7) -> Params:
     return Params(n_layers, batch, n_kv_heads, group, head_dim, window, kv_dtype, t_max,
                   t_stride if t_stride is not None else t_max, budget, n_segments, q_min,
                   ema_lambda, ema_beta, mass_eps, scorer, int(n_sink), int(n_last), int(bool(causal)),
-                  float(seg_delta), int(l_min), int(l_max), int(pool_kernel), float(vnorm_eps), int(score_path))
+                  float(seg_delta), int(l_min), int(l_max), int(pool_kernel), float(vnorm_eps), int(score_path),
+                  float(mix_lambda), int(score_kernel))
 
 
 def dense_view(k: torch.Tensor, v: Optional[torch.Tensor]) -> KvView:

@@ -89,7 +89,11 @@ static int check_params(const ams_params* p) {
   if (!(p->ema_lambda >= 0.f && p->ema_lambda < 1.f) || !(p->ema_beta >= 0.f && p->ema_beta <= 1.f) ||
       !(p->mass_eps > 0.f) || isinf(p->mass_eps))
     return AMS_ERR_INVALID_ARG;
-  if (p->scorer < AMS_SCORER_LAST_QUERY || p->scorer > AMS_SCORER_EXPECTED_VNORM) return AMS_ERR_INVALID_ARG;
+  if (p->scorer < AMS_SCORER_LAST_QUERY || p->scorer > AMS_SCORER_REDUNDANCY) return AMS_ERR_INVALID_ARG;
+  if (p->scorer == AMS_SCORER_REDUNDANCY &&
+      (!(p->mix_lambda >= 0.f && p->mix_lambda <= 1.f) || p->score_kernel < 0 || p->score_kernel > 63 ||
+       (p->score_kernel > 1 && p->score_kernel % 2 == 0)))
+    return AMS_ERR_INVALID_ARG;
   if (p->scorer == AMS_SCORER_EXPECTED_VNORM && !(p->vnorm_eps >= 0.f)) return AMS_ERR_INVALID_ARG;
   if (p->score_path < AMS_SCORE_PATH_AUTO || p->score_path > AMS_SCORE_PATH_ONE_LAUNCH) return AMS_ERR_INVALID_ARG;
   if (p->head_dim != 64 && p->head_dim != 128) return AMS_ERR_UNSUPPORTED;

@@ -434,8 +434,9 @@ __device__ __forceinline__ void widen8(const uint4& v, float (&x)[8], int& n) {
   }
 }
 
-// partial key sums per chunk: ksum[unit][chunk][D] (double)
-template <bool BF16, int HD>
+// partial key sums per chunk: ksum[unit][chunk][D] (double).  NORMALIZE: every key is divided by its
+// length first (the redundancy-aware score needs the sum of the unit vectors; a zero key adds nothing).
+template <bool BF16, int HD, bool NORMALIZE>
 __global__ __launch_bounds__(kThreads) void keysum_kernel(ScoreArgs a, double* ksum) {
   constexpr int CPR = Tr<BF16, HD>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
   __shared__ double sm[kThreads][EPC];
@@ -462,9 +463,18 @@ __global__ __launch_bounds__(kThreads) void keysum_kernel(ScoreArgs a, double* k
       float x[8];
       int n;
       widen8<BF16>(v[j], x, n);
+      double scale = 1.0;
+      if (NORMALIZE) {  // the CPR lanes of a row are consecutive lanes of one wave
+        float n2 = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) n2 = __builtin_fmaf(x[e], x[e], n2);
+#pragma unroll
+        for (int o = CPR / 2; o >= 1; o >>= 1) n2 += __shfl_xor(n2, o);
+        scale = n2 > 0.f ? 1.0 / sqrt((double)n2) : 0.0;
+      }
       if (tb + j * RPI < t_end) {
 #pragma unroll
-        for (int e = 0; e < EPC; ++e) s[e] += (double)x[e];
+        for (int e = 0; e < EPC; ++e) s[e] += (double)x[e] * scale;
       }
     }
   }
@@ -480,7 +490,9 @@ __global__ __launch_bounds__(kThreads) void keysum_kernel(ScoreArgs a, double* k
   }
 }
 
-template <bool BF16, int HD>
+// MEAN_COS = false: g[t] = -cos(k_t, mean key).  MEAN_COS = true (ksum holds sums of unit vectors):
+// g[t] = mean over s != t of cos(k_t, k_s) = (k_t / |k_t| . sum of unit vectors - 1) / (T - 1).
+template <bool BF16, int HD, bool MEAN_COS>
 __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const double* ksum) {
   constexpr int CPR = Tr<BF16, HD>::kRowBytes / 16, EPC = BF16 ? 8 : 4, RPI = kThreads / CPR;
   __shared__ double kbar[128];
@@ -496,7 +508,7 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   if ((int)threadIdx.x < a.d.D) {
     double t = 0.0;
     for (int c = 0; c < nch; ++c) t += ksum[((int64_t)unit * a.n_chunks + c) * a.d.D + threadIdx.x];
-    kbar[threadIdx.x] = t / (double)T;
+    kbar[threadIdx.x] = MEAN_COS ? t : t / (double)T;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -544,8 +556,12 @@ __global__ __launch_bounds__(kThreads) void keydiff_kernel(ScoreArgs a, const do
   // one token per thread for the ratio, so that every lane works
   for (int t = c0 + threadIdx.x; t < min(T, c0 + a.chunk); t += kThreads) {
     const float2 r = row_sums[t - c0];
-    const double den = sqrt((double)r.y) * kbar_norm;
-    g_row[t] = den > 0.0 ? (float)(-(double)r.x / den) : 0.f;
+    if (MEAN_COS) {
+      g_row[t] = (r.y > 0.f && T > 1) ? (float)(((double)r.x / sqrt((double)r.y) - 1.0) / (double)(T - 1)) : 0.f;
+    } else {
+      const double den = sqrt((double)r.y) * kbar_norm;
+      g_row[t] = den > 0.0 ? (float)(-(double)r.x / den) : 0.f;
+    }
   }
 }
 
@@ -722,9 +738,64 @@ hipError_t launch_keydiff(const ScoreArgs& a, char* ws, const WsLayout& wl, hipS
   double* ksum = (double*)(ws + wl.kbar);
   const dim3 grid(a.n_chunks, a.d.units), blk(kThreads);
   prof_mark("keysum", s);
-  hipLaunchKernelGGL((keysum_kernel<BF16, HD>), grid, blk, 0, s, a, ksum);
+  hipLaunchKernelGGL((keysum_kernel<BF16, HD, false>), grid, blk, 0, s, a, ksum);
   prof_mark("keydiff", s);
-  hipLaunchKernelGGL((keydiff_kernel<BF16, HD>), grid, blk, 0, s, a, (const double*)ksum);
+  hipLaunchKernelGGL((keydiff_kernel<BF16, HD, false>), grid, blk, 0, s, a, (const double*)ksum);
+  return hipGetLastError();
+}
+
+// Redundancy-aware score (Sec. 4 "Universality across diverse base scorers"): the mean cosine similarity of
+// every key to the other keys of its unit (two streams of K: the sum of the unit vectors, then one dot product
+// per key), its softmax over the cache, and g = lambda * (pooled) usage - (1 - lambda) * that softmax.
+__global__ __launch_bounds__(kThreads) void redundancy_combine_kernel(ScoreArgs a, const double2* part, float mix_lambda,
+                                                                       int pool_r) {
+  __shared__ double2 stat;
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  int l, b, h;
+  unit_coords(a.d, unit, l, b, h);
+  const int T = seq_len(a.d, a.seq_lens, b);
+  const int c0 = chunk * a.chunk;
+  if (c0 >= T) return;
+  if (threadIdx.x == 0) {  // chunk statistics of the similarities merged in index order
+    const int nch = (T + a.chunk - 1) / a.chunk;
+    double M = -INFINITY;
+    for (int c = 0; c < nch; ++c) M = fmax(M, part[(int64_t)unit * a.n_chunks + c].x);
+    double Z = 0.0;
+    for (int c = 0; c < nch; ++c) {
+      const double2 s = part[(int64_t)unit * a.n_chunks + c];
+      Z += s.y * exp(s.x - M);
+    }
+    stat = make_double2(M, Z);
+  }
+  __syncthreads();
+  const double M = stat.x, inv_z = 1.0 / stat.y, lam = (double)mix_lambda;
+  const float* u_row = a.u + (int64_t)unit * a.d.t_stride;
+  float* g_row = a.g + (int64_t)unit * a.d.t_stride;
+  for (int t = c0 + threadIdx.x; t < min(T, c0 + a.chunk); t += kThreads) {
+    float imp = u_row[t];
+    if (pool_r > 0) {  // the mean of u over the positions t - r .. t + r that exist, stored as fp32
+      const int lo = max(0, t - pool_r), hi = min(T - 1, t + pool_r);
+      double sum = 0.0;
+      for (int j = lo; j <= hi; ++j) sum += (double)u_row[j];
+      imp = (float)(sum / (double)(hi - lo + 1));
+    }
+    g_row[t] = (float)(lam * (double)imp - (1.0 - lam) * (exp((double)g_row[t] - M) * inv_z));
+  }
+}
+
+template <bool BF16, int HD>
+hipError_t launch_redundancy(const ScoreArgs& a, char* ws, const WsLayout& wl, float mix_lambda, int kernel, hipStream_t s) {
+  double* ksum = (double*)(ws + wl.kbar);
+  const dim3 grid(a.n_chunks, a.d.units), blk(kThreads);
+  prof_mark("khat_sum", s);
+  hipLaunchKernelGGL((keysum_kernel<BF16, HD, true>), grid, blk, 0, s, a, ksum);
+  prof_mark("mean_cos", s);
+  hipLaunchKernelGGL((keydiff_kernel<BF16, HD, true>), grid, blk, 0, s, a, (const double*)ksum);
+  prof_mark("esoftmax_part", s);  // the chunk statistics take the place of the key sums, which are used up
+  hipLaunchKernelGGL(esoftmax_part_kernel, grid, blk, 0, s, a, (double2*)(ws + wl.kbar));
+  prof_mark("redundancy_combine", s);
+  hipLaunchKernelGGL(redundancy_combine_kernel, grid, blk, 0, s, a, (const double2*)(ws + wl.kbar), mix_lambda,
+                     kernel > 1 ? kernel / 2 : 0);
   return hipGetLastError();
 }
 
@@ -811,6 +882,15 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
       e = bf16 ? launch_vweight<true, 64>(a, *v, ws, wl, p->vnorm_eps, s) : launch_vweight<false, 64>(a, *v, ws, wl, p->vnorm_eps, s);
     else
       e = bf16 ? launch_vweight<true, 128>(a, *v, ws, wl, p->vnorm_eps, s) : launch_vweight<false, 128>(a, *v, ws, wl, p->vnorm_eps, s);
+  }
+  if (p->scorer == AMS_SCORER_REDUNDANCY) {
+    a.g = g;
+    if (d.D == 64)
+      e = bf16 ? launch_redundancy<true, 64>(a, ws, wl, p->mix_lambda, p->score_kernel, s)
+               : launch_redundancy<false, 64>(a, ws, wl, p->mix_lambda, p->score_kernel, s);
+    else
+      e = bf16 ? launch_redundancy<true, 128>(a, ws, wl, p->mix_lambda, p->score_kernel, s)
+               : launch_redundancy<false, 128>(a, ws, wl, p->mix_lambda, p->score_kernel, s);
   }
   if (p->scorer == AMS_SCORER_KEYDIFF) {
     a.g = g;

@@ -59,3 +59,16 @@ def assert_close_norm(got, want, rtol=1e-5, what=""):
     scale = np.abs(want).max()
     err = np.abs(got - want).max()
     assert err <= rtol * scale, f"{what}: max abs err {err:.3e} vs scale {scale:.3e} (ratio {err / scale:.3e})"
+
+
+def assert_close_terms(got, want, magnitude, rtol=1e-5, atol=1e-12, what=""):
+    """For results that are a signed sum of terms (and may pass through zero): the error of every element is
+    held against rtol times the sum of the magnitudes of ITS terms (`magnitude`, same shape), not against the
+    vector's largest value."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    err = np.abs(got - want)
+    tol = atol + rtol * np.asarray(magnitude, np.float64)
+    bad = err > tol
+    assert not bad.any(), (f"{what}: {bad.sum()} of {bad.size} beyond rtol={rtol} of their terms; worst ratio "
+                           f"{(err / np.maximum(tol, 1e-300)).max():.3f} at {np.argmax(err / np.maximum(tol, 1e-300))}")

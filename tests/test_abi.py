@@ -57,7 +57,8 @@ def test_workspace_bytes_and_layout():
     ("seg_delta", 1e-4, B.ERR_INVALID_ARG),            # more than 1024 initial segments
     ("seg_delta", 0.05, B.ERR_INVALID_ARG),            # 20 initial segments do not fit the 8 entries
     ("l_max", 64, B.ERR_INVALID_ARG),                  # length rules without a target mass
-    ("score_path", 4, B.ERR_INVALID_ARG), ("score_path", -1, B.ERR_INVALID_ARG)])
+    ("score_path", 4, B.ERR_INVALID_ARG), ("score_path", -1, B.ERR_INVALID_ARG),
+    ("scorer", 7, B.ERR_INVALID_ARG)])
 def test_bad_params_are_rejected_on_the_host(field, value, status):
     p = _good()
     setattr(p, field, value)
@@ -73,6 +74,21 @@ def test_score_path_field():
     for path in (B.SCORE_PATH_AUTO, B.SCORE_PATH_TWO_SWEEPS, B.SCORE_PATH_ONE_READ, B.SCORE_PATH_ONE_LAUNCH):
         p.score_path = path
         assert B.ams_workspace_bytes(p) > 0            # the workspace does not depend on the path
+
+
+def test_redundancy_scorer_parameters():
+    p = _good()
+    p.scorer = B.SCORER_REDUNDANCY
+    assert B.ams_workspace_bytes(p) > 0                # defaults: lambda 0.07, kernel 7
+    for field, bad in (("mix_lambda", 1.5), ("mix_lambda", -0.1), ("score_kernel", 4), ("score_kernel", 65),
+                       ("score_kernel", -1)):
+        q = _good()
+        q.scorer = B.SCORER_REDUNDANCY
+        setattr(q, field, bad)
+        assert B.ams_workspace_bytes(q) == 0
+    q = _good()
+    q.mix_lambda = 7.0                                 # ignored by the other scorers
+    assert B.ams_workspace_bytes(q) > 0
 
 
 def test_both_head_dimensions_are_accepted():

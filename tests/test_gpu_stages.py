@@ -10,8 +10,8 @@ import torch
 
 from paper_2605_23200_amd import binding as B
 from paper_2605_23200_amd import inputs
-from gpu_util import (DEV, assert_close_norm, assert_close_rel, params_for, to_dev, to_host, unit_list,
-                      workspace)
+from gpu_util import (DEV, assert_close_norm, assert_close_rel, assert_close_terms, params_for, to_dev, to_host,
+                      unit_list, workspace)
 
 pytestmark = pytest.mark.gpu
 

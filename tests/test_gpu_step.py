@@ -11,7 +11,7 @@ import torch
 from paper_2605_23200_amd import binding as B
 from paper_2605_23200_amd import inputs
 from paper_2605_23200_amd.harness import Job
-from gpu_util import assert_close_norm, assert_close_rel, to_dev, to_host, unit_list
+from gpu_util import assert_close_norm, assert_close_rel, assert_close_terms, to_dev, to_host, unit_list
 
 pytestmark = pytest.mark.gpu
 
@@ -60,11 +60,22 @@ def check_units(oracle, job, host, credit_before, units, scorer=B.SCORER_MEAN_WI
         if check_scores:
             vnorm = scorer == B.SCORER_EXPECTED_VNORM
             uo, go = oracle.score(Qh, Kh, w.G, w.W,
-                                  B.SCORER_EXPECTED if vnorm else scorer, causal=w.causal)
+                                  B.SCORER_EXPECTED if vnorm else (B.SCORER_MEAN_WINDOW if scorer == B.SCORER_REDUNDANCY
+                                                                   else scorer), causal=w.causal)
             if vnorm:
                 go = oracle.value_weight(go, Vh, 1e-2)
             assert_close_rel(u_g[j, :T], uo, what=f"u unit {i}")
-            if scorer in (B.SCORER_MEAN_WINDOW, B.SCORER_LAST_QUERY, B.SCORER_EXPECTED_VNORM):
+            if scorer == B.SCORER_REDUNDANCY:       # the oracle's O(T^2) definition on the GPU's own usage
+                go = oracle.redundancy_score(u_g[j, :T], Kh, mix_lambda=job.p.mix_lambda, kernel=job.p.score_kernel)
+                a = (oracle.pool(u_g[j, :T], job.p.score_kernel) if job.p.score_kernel > 1 else u_g[j, :T]).astype(np.float64)
+                mag = job.p.mix_lambda * np.abs(a) + np.abs(job.p.mix_lambda * a - go.astype(np.float64))
+                assert_close_terms(g_g[j, :T], go, mag, what=f"g unit {i}")
+                continue_scores = False
+            else:
+                continue_scores = True
+            if not continue_scores:
+                pass
+            elif scorer in (B.SCORER_MEAN_WINDOW, B.SCORER_LAST_QUERY, B.SCORER_EXPECTED_VNORM):
                 assert_close_rel(g_g[j, :T], go, what=f"g unit {i}")
             else:
                 assert_close_norm(g_g[j, :T], go, what=f"g unit {i}")
@@ -409,6 +420,24 @@ def test_config4_scorer_sweep(oracle, scorer, cfg4_host):
                     np.testing.assert_array_equal(idx[i], np.sort(order[: w.budget]))
             del job
             torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("options", [{}, dict(n_sink=4, n_last=16, causal=True), dict(paged=True)])
+def test_redundancy_scorer_step(oracle, options):
+    """The whole event with the redundancy-aware plug-in scorer (the R-KV-style score): segments and quotas from
+    the usage as always, the in-segment ranking from the redundancy-aware score; every unit against the oracle."""
+    w = inputs.CONFIGS[1].scaled(L=2, H=3, T=3000, budget=256, S=8, n_spans=5, span_len=(16, 200), **options)
+    host = inputs.dense_cache(w, n_threads=4)
+    job = Job(w, host, scorer=B.SCORER_REDUNDANCY)
+    job.step()
+    torch.cuda.synchronize()
+    check_properties_all_units(job)
+    check_units(oracle, job, host, np.zeros((w.units, w.T), np.float32), list(range(w.units)), scorer=B.SCORER_REDUNDANCY)
+    # the ranking differs from plain attention: the two scorers keep different sets
+    job2 = Job(w, host, scorer=B.SCORER_MEAN_WINDOW)
+    job2.step()
+    torch.cuda.synchronize()
+    assert not torch.equal(job.idx, job2.idx)
 
 
 def test_budget_at_least_length_keeps_everything(oracle):
