@@ -360,6 +360,45 @@ __global__ void segment_finalize_kernel(MsArgs a, float* seg_mass_all) {
   }
 }
 
+// Split / merge pass over the initial segments, one pass from the left (Alg. 1 step 3, the loop over segments;
+// Sec. 3.3 "Mass-based adaptive segmentation").  cut(i), i = 1 .. K, is the end of initial segment i (cut(K) = T).
+// A segment longer than l_max becomes ceil(L / l_max) parts whose lengths differ by at most one, the longer ones
+// first; one shorter than l_min joins the segment to its left, the very first one stays open so that the next
+// initial segment starts where it started; empty initial segments vanish.  Writes the ends of the final segments
+// to out[0 .. n) (at most cap of them) and returns n.  A serial chain of at most K steps: one thread runs it.
+template <typename Cut>
+__device__ __forceinline__ int split_merge_pass(Cut cut, int K, int T, int l_min, int l_max, int cap, int32_t* out) {
+  int n = 0, start = 0;
+  bool have_left = false;
+  for (int i = 1; i <= K; ++i) {
+    const int e = cut(i);
+    const int L = e - start;
+    if (L == 0) continue;
+    if (l_max > 0 && L > l_max) {
+      const int parts = (L + l_max - 1) / l_max, base = L / parts, extra = L % parts;
+      int pos = start;
+      for (int j = 0; j < parts && n < cap; ++j) {
+        pos += base + (j < extra ? 1 : 0);
+        out[n++] = pos;
+      }
+      have_left = true;
+      start = e;
+    } else if (l_min > 0 && L < l_min) {
+      if (have_left) {
+        out[n - 1] = e;
+        start = e;
+      }
+    } else {
+      if (n < cap) out[n++] = e;
+      have_left = true;
+      start = e;
+    }
+  }
+  if (start < T && n < cap) out[n++] = T;  // the whole sequence was one too-short segment
+  if (n > 0) out[n - 1] = T;               // (only matters if the capacity cut the list short)
+  return n;
+}
+
 // Delta mode, after the cut points: one pass over the initial segments from the left (Alg. 1 step 3,
 // the loop over segments).  Longer than l_max: ceil(L / l_max) parts whose lengths differ by at most
 // one, the longer ones first.  Shorter than l_min: joins the segment to its left; the first one
@@ -375,34 +414,8 @@ __global__ __launch_bounds__(64) void resegment_kernel(MsArgs a) {
   const int T = seq_len(a.d, a.seq_lens, b);
   int32_t* bounds = a.bounds + (int64_t)unit * (a.S + 1);
   if (threadIdx.x == 0) {
-    int n = 0, start = 0;
-    bool have_left = false;
-    for (int i = 1; i <= a.K; ++i) {
-      const int e = i == a.K ? T : bounds[i];
-      const int L = e - start;
-      if (L == 0) continue;
-      if (a.l_max > 0 && L > a.l_max) {
-        const int parts = (L + a.l_max - 1) / a.l_max, base = L / parts, extra = L % parts;
-        int pos = start;
-        for (int j = 0; j < parts && n < a.S; ++j) {
-          pos += base + (j < extra ? 1 : 0);
-          out[n++] = pos;
-        }
-        have_left = true;
-        start = e;
-      } else if (a.l_min > 0 && L < a.l_min) {
-        if (have_left) {
-          out[n - 1] = e;
-          start = e;
-        }
-      } else {
-        if (n < a.S) out[n++] = e;
-        have_left = true;
-        start = e;
-      }
-    }
-    if (start < T && n < a.S) out[n++] = T;  // the whole sequence was one too-short segment
-    if (n > 0) out[n - 1] = T;               // (only matters if the capacity cut the list short)
+    const int K = a.K;
+    const int n = split_merge_pass([&](int i) { return i == K ? T : bounds[i]; }, K, T, a.l_min, a.l_max, a.S, out);
     n_out = n;
   }
   __syncthreads();
@@ -661,34 +674,7 @@ __global__ __launch_bounds__(kUnitBlock) void unit_mass_kernel(MsArgs a, const f
       // the split / merge pass over the initial segments (see resegment_kernel), then the mass of every
       // final segment summed from the m_used this workgroup has just written
       if (threadIdx.x == 0) {
-        int n = 0, start = 0;
-        bool have_left = false;
-        for (int i = 1; i <= K; ++i) {
-          const int e = i == K ? T : bounds[i];
-          const int L = e - start;
-          if (L == 0) continue;
-          if (a.l_max > 0 && L > a.l_max) {
-            const int parts = (L + a.l_max - 1) / a.l_max, base = L / parts, extra = L % parts;
-            int pos = start;
-            for (int j = 0; j < parts && n < S; ++j) {
-              pos += base + (j < extra ? 1 : 0);
-              reseg[n++] = pos;
-            }
-            have_left = true;
-            start = e;
-          } else if (a.l_min > 0 && L < a.l_min) {
-            if (have_left) {
-              reseg[n - 1] = e;
-              start = e;
-            }
-          } else {
-            if (n < S) reseg[n++] = e;
-            have_left = true;
-            start = e;
-          }
-        }
-        if (start < T && n < S) reseg[n++] = T;  // the whole sequence was one too-short segment
-        if (n > 0) reseg[n - 1] = T;             // (only matters if the capacity cut the list short)
+        const int n = split_merge_pass([&](int i) { return i == K ? T : bounds[i]; }, K, T, a.l_min, a.l_max, S, reseg);
         n_reseg = n;
       }
       __syncthreads();

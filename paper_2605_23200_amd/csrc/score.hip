@@ -328,7 +328,7 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
   constexpr bool kBufG = MODE == MODE_LAST && NB <= 7;  // (8 column blocks: LDS is needed for the query window)
   __shared__ float u_sm[kScoreChunk];
   __shared__ float g_sm[kBufG ? kScoreChunk : 1];
-  float v_part = 0.f;  // this lane's share of sum(max(u,0)+eps): at most 8 terms
+  float v_part = 0.f;  // this lane's share of sum(max(u,0)+eps): one term per block of 32 keys of this wave (32 blocks per chunk)
   auto block = [&](const uint4 (&av)[Tr<BF16, HD>::kAVecs], int t0) __attribute__((always_inline)) {
     float pu[16], pg[16], pm[16];
 #pragma unroll

@@ -52,13 +52,25 @@ def assert_close_rel(got, want, rtol=1e-5, atol=1e-12, what=""):
                            f"{(err / np.maximum(np.abs(want), 1e-300)).max():.3e} at {np.argmax(err / np.maximum(tol, 1e-300))}")
 
 
-def assert_close_norm(got, want, rtol=1e-5, what=""):
-    """For signed scores that pass through zero: error relative to the largest magnitude of the vector."""
-    got = np.asarray(got, np.float64)
-    want = np.asarray(want, np.float64)
-    scale = np.abs(want).max()
-    err = np.abs(got - want).max()
-    assert err <= rtol * scale, f"{what}: max abs err {err:.3e} vs scale {scale:.3e} (ratio {err / scale:.3e})"
+def score_term_magnitudes(scorer, Q, K):
+    """Per key, the sum of the magnitudes of the terms that the signed base scores add up (what a relative bound
+    has to be relative to when the sum itself passes through zero).  Q [N, D], K [T, D], float32 or bf16 bits.
+    KeyDiff (-cos(k_t, kbar)): sum_d |k_td kbar_d| / (|k_t| |kbar|).
+    Expected attention (mu.k/sqrt(D) + k'Sigma k/(2D)): sum_d |mu_d k_td| / sqrt(D) plus the quadratic form, which
+    is a variance and cannot cancel."""
+    widen = lambda x: (inputs.bf16_bits_to_f32(x) if x.dtype == np.uint16 else x).astype(np.float64)
+    K = widen(np.asarray(K))
+    D = K.shape[1]
+    if scorer == B.SCORER_KEYDIFF:
+        kbar = K.mean(axis=0)
+        den = np.linalg.norm(K, axis=1) * np.linalg.norm(kbar)
+        return np.where(den > 0, (np.abs(K) @ np.abs(kbar)) / np.maximum(den, 1e-300), 0.0)
+    if scorer == B.SCORER_EXPECTED:
+        Q = widen(np.asarray(Q)).reshape(-1, D)
+        mu = Q.mean(axis=0)
+        s = (Q - mu) @ K.T / np.sqrt(D)
+        return (np.abs(K) @ np.abs(mu)) / np.sqrt(D) + 0.5 * (s * s).mean(axis=0)
+    raise ValueError(scorer)
 
 
 def assert_close_terms(got, want, magnitude, rtol=1e-5, atol=1e-12, what=""):

@@ -10,7 +10,7 @@ import torch
 
 from paper_2605_23200_amd import binding as B
 from paper_2605_23200_amd import inputs
-from gpu_util import (DEV, assert_close_norm, assert_close_rel, assert_close_terms, params_for, to_dev, to_host,
+from gpu_util import (DEV, assert_close_rel, assert_close_terms, score_term_magnitudes, params_for, to_dev, to_host,
                       unit_list, workspace)
 
 pytestmark = pytest.mark.gpu
@@ -41,13 +41,13 @@ def test_score_parity(oracle, dtype, G, W, T, scorer):
     torch.cuda.synchronize()
     u_h, g_h = to_host(u), to_host(g)
     for i, (l, b, h) in enumerate(unit_list(w)):
-        uo, go = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), host["K"][l, b, h, :T],
-                              w.G, w.W, SCORERS[scorer])
+        q_i, k_i = host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), host["K"][l, b, h, :T]
+        uo, go = oracle.score(q_i, k_i, w.G, w.W, SCORERS[scorer])
         assert_close_rel(u_h[i], uo, what=f"u unit {i}")
         if scorer in ("mean", "last"):
             assert_close_rel(g_h[i], go, what=f"g unit {i}")
         else:
-            assert_close_norm(g_h[i], go, what=f"g unit {i}")
+            assert_close_terms(g_h[i], go, score_term_magnitudes(SCORERS[scorer], q_i, k_i), what=f"g unit {i}")
 
 
 @pytest.mark.parametrize("dtype,G,W,T", [("bf16", 4, 32, 5000), ("bf16", 4, 32, 2048 + 31), ("bf16", 4, 32, 2048 + 32),
@@ -71,13 +71,13 @@ def test_score_causal_parity(oracle, dtype, G, W, T, scorer):
     torch.cuda.synchronize()
     u_h, g_h = to_host(u), to_host(g)
     for i, (l, b, h) in enumerate(unit_list(w)):
-        uo, go = oracle.score(host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), host["K"][l, b, h, :T],
-                              w.G, w.W, SCORERS[scorer], causal=True)
+        q_i, k_i = host["Q"][l, b, h * w.G:(h + 1) * w.G].reshape(-1, w.D), host["K"][l, b, h, :T]
+        uo, go = oracle.score(q_i, k_i, w.G, w.W, SCORERS[scorer], causal=True)
         assert_close_rel(u_h[i], uo, what=f"u unit {i}")
         if scorer in ("mean", "last"):
             assert_close_rel(g_h[i], go, what=f"g unit {i}")
         else:
-            assert_close_norm(g_h[i], go, what=f"g unit {i}")
+            assert_close_terms(g_h[i], go, score_term_magnitudes(SCORERS[scorer], q_i, k_i), what=f"g unit {i}")
 
 
 @pytest.mark.parametrize("dtype,G,W,T", [("f32", 1, 8, 4096), ("bf16", 4, 32, 5000), ("bf16", 7, 32, 2085),
@@ -135,7 +135,7 @@ def test_score_parity_head_dim_64(oracle, dtype, G, W, T, causal, scorer):
         if scorer in ("mean", "last", "expected_vnorm"):
             assert_close_rel(g_h[i], go, what=f"g unit {i}")
         else:
-            assert_close_norm(g_h[i], go, what=f"g unit {i}")
+            assert_close_terms(g_h[i], go, score_term_magnitudes(sc, q_i, k_i), what=f"g unit {i}")
 
 
 def test_score_ragged_batch_paged(oracle):

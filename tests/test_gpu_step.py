@@ -11,7 +11,7 @@ import torch
 from paper_2605_23200_amd import binding as B
 from paper_2605_23200_amd import inputs
 from paper_2605_23200_amd.harness import Job
-from gpu_util import assert_close_norm, assert_close_rel, assert_close_terms, to_dev, to_host, unit_list
+from gpu_util import assert_close_rel, assert_close_terms, score_term_magnitudes, to_dev, to_host, unit_list
 
 pytestmark = pytest.mark.gpu
 
@@ -70,15 +70,10 @@ def check_units(oracle, job, host, credit_before, units, scorer=B.SCORER_MEAN_WI
                 a = (oracle.pool(u_g[j, :T], job.p.score_kernel) if job.p.score_kernel > 1 else u_g[j, :T]).astype(np.float64)
                 mag = job.p.mix_lambda * np.abs(a) + np.abs(job.p.mix_lambda * a - go.astype(np.float64))
                 assert_close_terms(g_g[j, :T], go, mag, what=f"g unit {i}")
-                continue_scores = False
-            else:
-                continue_scores = True
-            if not continue_scores:
-                pass
             elif scorer in (B.SCORER_MEAN_WINDOW, B.SCORER_LAST_QUERY, B.SCORER_EXPECTED_VNORM):
                 assert_close_rel(g_g[j, :T], go, what=f"g unit {i}")
             else:
-                assert_close_norm(g_g[j, :T], go, what=f"g unit {i}")
+                assert_close_terms(g_g[j, :T], go, score_term_magnitudes(scorer, Qh, Kh), what=f"g unit {i}")
         u_mass = oracle.pool(u_g[j, :T], w.pool_kernel) if w.pool_kernel > 1 else u_g[j, :T]
         m_o, c_o = oracle.ema(oracle.mass(u_mass, w.eps), credit_before[i, :T], w.lam, w.beta)
         assert_close_rel(m_g[j, :T], m_o, what=f"m_used unit {i}")
