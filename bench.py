@@ -49,6 +49,12 @@ def kernel_bytes(label, w, lens=None):
         "score_reduce": 0,
         "score_oneread": tok * D * e + 4 * tok * 2,       # K stream once, u out, old credit in (for its sum)
         "score_unit": tok * D * e + 4 * tok * 2,          # short caches: K counted once (the second walk hits the caches)
+        "khat_sum": tok * D * e,                          # K stream (sum of the normalised keys)
+        "mean_cos": tok * D * e + 4 * tok,                # K stream + the mean cosine per key
+        "esoftmax_part": 4 * tok,                         # the mean cosines once more (softmax statistics)
+        "redundancy_combine": 4 * tok * 3,                # u, mean cosine in; g out
+        "keysum": tok * D * e,                            # K stream (mean key)
+        "keydiff": tok * D * e + 4 * tok,                 # K stream + g
         "mass_ema": 4 * tok * 4,                          # u, credit in; credit, m_used out
         "unit_mass": 4 * tok * 4,                         # the same, with the scan and the quotas in the same launch
         "segment_scan": 4 * tok,                          # m_used in
@@ -76,10 +82,13 @@ def main():
     ap.add_argument("--l-max", type=int, default=0)
     ap.add_argument("--pool", type=int, default=0, help="average-pooling kernel of the usage (odd)")
     ap.add_argument("--scorer", default="mean_window",
-                    choices=["mean_window", "last_query", "keydiff", "expected", "expected_vnorm"],
+                    choices=["mean_window", "last_query", "keydiff", "expected", "expected_vnorm", "redundancy"],
                     help="base scorer (the headline workload uses mean_window)")
-    ap.add_argument("--score-path", default="auto", choices=["auto", "two_sweeps", "one_read"],
+    ap.add_argument("--score-path", default="auto", choices=["auto", "two_sweeps", "one_read", "one_launch"],
                     help="ams_params.score_path: how the softmax statistics are formed (the headline line uses auto)")
+    ap.add_argument("--seq-len", type=int, default=0,
+                    help="run the dense workload at this cache length instead of its own (e.g. budget + appended tokens: "
+                         "the short event of the literal trajectory as the main workload of a profiling run)")
     ap.add_argument("--no-small-event", action="store_true",
                     help="skip the short event of the literal trajectory (profiling runs: one workload per kernel name)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -101,6 +110,12 @@ def main():
     B.lib()                                   # fails loudly if the HIP library is not built
     w = inputs.CONFIGS[args.config].scaled(n_sink=args.n_sink, n_last=args.n_last, causal=args.causal,
                                            pool_kernel=args.pool)
+    if args.seq_len > 0:
+        if w.paged or not (w.W <= args.seq_len <= w.T):
+            sys.exit("bench.py: --seq-len is for the dense workloads, between the window and the configured length")
+        w = w.scaled(T=args.seq_len, n_spans=max(1, w.n_spans * args.seq_len // w.T))
+    if args.scorer == "redundancy":
+        args.no_cpu_baseline = True       # its definition is quadratic in the cache length: hours on the host at 32k
     if args.seg_delta > 0:
         import math
         cap = math.ceil(1 / args.seg_delta) + 1 + (w.T // args.l_max if args.l_max else 0)
@@ -108,9 +123,9 @@ def main():
     t0 = time.time()
     scorer_id = {"mean_window": B.SCORER_MEAN_WINDOW, "last_query": B.SCORER_LAST_QUERY,
                  "keydiff": B.SCORER_KEYDIFF, "expected": B.SCORER_EXPECTED,
-                 "expected_vnorm": B.SCORER_EXPECTED_VNORM}[args.scorer]
+                 "expected_vnorm": B.SCORER_EXPECTED_VNORM, "redundancy": B.SCORER_REDUNDANCY}[args.scorer]
     score_path = {"auto": B.SCORE_PATH_AUTO, "two_sweeps": B.SCORE_PATH_TWO_SWEEPS,
-                  "one_read": B.SCORE_PATH_ONE_READ}[args.score_path]
+                  "one_read": B.SCORE_PATH_ONE_READ, "one_launch": B.SCORE_PATH_ONE_LAUNCH}[args.score_path]
     n_q = 4
     lens = None
     if w.paged:
