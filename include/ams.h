@@ -75,7 +75,11 @@ typedef enum {
   AMS_SCORE_PATH_ONE_READ = 2,   /* K is read once and held on chip between the two products: bf16,
                                     head_dim 128, at most 128 queries per KV head, dense layout, no
                                     causal window, mean-window / last-query / key-diversity scorers;
-                                    AMS_ERR_UNSUPPORTED otherwise                                    */
+                                    AMS_ERR_UNSUPPORTED otherwise.  Its workgroups wait for one
+                                    another (every wait bounded), so it wants the GPU to itself: if
+                                    a wait expires, ams_compress_step writes n_kept = -1 for every
+                                    unit and the outputs of the call are not to be used.  Slower
+                                    than TWO_SWEEPS on the measured workloads; AUTO never takes it   */
   AMS_SCORE_PATH_ONE_LAUNCH = 3  /* short caches (t_max <= 4096): one workgroup walks a unit's keys
                                     twice in one launch; at most 128 queries per KV head, no causal
                                     window, no moment-based scorer; AMS_ERR_UNSUPPORTED otherwise.
