@@ -12,6 +12,8 @@
 //            over the queries of each token                     -> u (and g)
 // The score matrix itself never reaches memory.  The key-diversity and the
 // value-weighted scorers add streaming kernels of their own at the end of the file.
+#include <type_traits>
+
 #include "score_tile.h"
 
 namespace ams {
@@ -32,6 +34,18 @@ namespace {
 #endif
 template <int NB>
 constexpr int kGroup = (NB % AMS_SCORE_GROUP_DIV == 0 && NB >= 4) ? NB / AMS_SCORE_GROUP_DIV : NB;
+// With five or more column blocks (bf16 caches, plain sweeps; two waves per SIMD either way) a block is
+// walked as a software pipeline over its column blocks (score_tile.h: col_frags / col_mma / col_hints):
+// two accumulator tiles and two sets of query fragments live instead of all accumulator tiles, the
+// matrix cores and the vector ALU busy together for longer (30 % of the cycles against 17 %).  Measured
+// at 224 queries per key, same machine: 1.064 + 0.938 ms for the two sweeps against 1.095 + 0.978.  With
+// four column blocks it does not pay: three waves per SIMD do not fit the extra registers (and spill),
+// and the two-wave moment-sum kernel is unchanged by it (0.617 ms either way).
+#ifndef AMS_SCORE_PIPE_MIN_NB
+#define AMS_SCORE_PIPE_MIN_NB 5
+#endif
+template <bool BF16, int NB, bool TAIL>
+constexpr bool kPipe = BF16 && !TAIL && NB >= AMS_SCORE_PIPE_MIN_NB;
 
 // ---------------------------------------------------------------------------------------------
 // Sweep 1: per chunk, per query (max, sum exp2) of the scaled logits.
@@ -107,59 +121,84 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
   const float c2 = a.c2;
   float* g_row = MOMENTS ? a.g + (int64_t)unit * a.d.t_stride : nullptr;
   __shared__ float g_sm[MOMENTS ? kScoreChunk : 1];  // the chunk's moment scores, written once at the end
-  auto block = [&](const uint4 (&av)[Tr<BF16, HD>::kAVecs], int t0) __attribute__((always_inline)) {
-    const bool ragged = t0 + 32 > T;
+  auto block_of = [&](const uint4 (&av)[Tr<BF16, HD>::kAVecs], int t0, auto ragged_c) __attribute__((always_inline)) {
+    constexpr bool ragged = decltype(ragged_c)::value;  // the block reaches past the end of the cache
     // the query fragments are re-read from LDS for every block: keeping them in registers across
     // blocks would cost more registers than the reads cost time, so their address is made opaque
     int qoff = 0;
     asm volatile("" : "+s"(qoff));
     float ref[16], s1[16], s2[16];
+    // the vector work on one column block of logits
+    auto col_moments = [&](const floatx16& acc, int nb) __attribute__((always_inline)) {
+      if (nb == 0) {
 #pragma unroll
-    for (int g0 = 0; g0 < NB; g0 += NG) {
-      floatx16 acc[NG];
-      tile_mma<BF16, NG, HD>(av, qlds + qoff + g0 * 32 * QS, lane, acc);
-      if (MOMENTS) {
-        if (g0 == 0) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            // the half wave's first lane holds the logit against query 0 of the rows this lane owns
-            const float r0 = __builtin_amdgcn_readlane(acc[0][i], 0), r1 = __builtin_amdgcn_readlane(acc[0][i], 32);
-            ref[i] = hf ? r1 : r0;
-            s1[i] = s2[i] = 0.f;
-          }
-        }
-#pragma unroll
-        for (int k = 0; k < NG; ++k) {
-          const bool real = (g0 + k) * 32 + (lane & 31) < a.d.N;  // padded query columns do not count
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float dlt = real ? acc[k][i] - ref[i] : 0.f;
-            s1[i] += dlt;
-            s2[i] = __builtin_fmaf(dlt, dlt, s2[i]);
-          }
+        for (int i = 0; i < 16; ++i) {
+          // the half wave's first lane holds the logit against query 0 of the rows this lane owns
+          const float r0 = __builtin_amdgcn_readlane(acc[i], 0), r1 = __builtin_amdgcn_readlane(acc[i], 32);
+          ref[i] = hf ? r1 : r0;
+          s1[i] = s2[i] = 0.f;
         }
       }
+      const bool real = nb * 32 + (lane & 31) < a.d.N;  // padded query columns do not count
 #pragma unroll
-      for (int k = 0; k < NG; ++k) {
-        const int nb = g0 + k;
-        if (TAIL) {
-          // this column's query sees the keys up to lim (< T, so rows past the end are covered too)
-          const int lim = t_vis0 + (nb * 32 + (lane & 31)) % a.d.W;
+      for (int i = 0; i < 16; ++i) {
+        const float dlt = real ? acc[i] - ref[i] : 0.f;
+        s1[i] += dlt;
+        s2[i] = __builtin_fmaf(dlt, dlt, s2[i]);
+      }
+    };
+    auto col_stats = [&](floatx16& acc, int nb) __attribute__((always_inline)) {
+      if (TAIL) {
+        // this column's query sees the keys up to lim (< T, so rows past the end are covered too)
+        const int lim = t_vis0 + (nb * 32 + (lane & 31)) % a.d.W;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) acc[k][i] = (t0 + acc_row(i, hf) > lim) ? -INFINITY : acc[k][i];
-        } else if (ragged) {
+        for (int i = 0; i < 16; ++i) acc[i] = (t0 + acc_row(i, hf) > lim) ? -INFINITY : acc[i];
+      } else if (ragged) {
 #pragma unroll
-          for (int i = 0; i < 16; ++i) acc[k][i] = (t0 + acc_row(i, hf) >= T) ? -INFINITY : acc[k][i];
+        for (int i = 0; i < 16; ++i) acc[i] = (t0 + acc_row(i, hf) >= T) ? -INFINITY : acc[i];
+      }
+      float mr = acc[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mr = fmaxf(mr, acc[i]);
+      const float mx = fmaxf(m[nb], mr * c2);  // c2 > 0: the maximum commutes with the scale
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i], c2, -mx));
+      z[nb] = __builtin_fmaf(z[nb], __builtin_amdgcn_exp2f(m[nb] - mx), sum);
+      m[nb] = mx;
+    };
+    if constexpr (kPipe<BF16, NB, TAIL> && !ragged) {
+      constexpr int NV = Tr<BF16, HD>::kAVecs;
+      const char* qb = qlds + qoff + (lane & 31) * QS + (lane >> 5) * (Tr<BF16, HD>::kRowBytes / 2);
+      uint4 bq[2][NV];
+      floatx16 acc2[2];
+      col_frags<BF16, HD>(qb, bq[0]);
+      col_frags<BF16, HD>(qb + 32 * QS, bq[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      col_mma<BF16, HD>(av, bq[0], acc2[0]);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (nb + 2 < NB) col_frags<BF16, HD>(qb + (nb + 2) * 32 * QS, bq[nb & 1]);
+        if (nb + 1 < NB) col_mma<BF16, HD>(av, bq[(nb + 1) & 1], acc2[(nb + 1) & 1]);
+        if (MOMENTS) col_moments(acc2[nb & 1], nb);
+        col_stats(acc2[nb & 1], nb);
+        if (nb + 2 < NB)
+          col_hints<NV, MOMENTS ? 10 : 6, 2, true>();
+        else if (nb + 1 < NB)
+          col_hints<NV, MOMENTS ? 10 : 6, 2, false>();
+      }
+    } else {
+#pragma unroll
+      for (int g0 = 0; g0 < NB; g0 += NG) {
+        floatx16 acc[NG];
+        tile_mma<BF16, NG, HD>(av, qlds + qoff + g0 * 32 * QS, lane, acc);
+        if (MOMENTS) {
+#pragma unroll
+          for (int k = 0; k < NG; ++k) col_moments(acc[k], g0 + k);
         }
-        float mr = acc[k][0];
 #pragma unroll
-        for (int i = 1; i < 16; ++i) mr = fmaxf(mr, acc[k][i]);
-        const float mx = fmaxf(m[nb], mr * c2);  // c2 > 0: the maximum commutes with the scale
-        float sum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[k][i], c2, -mx));
-        z[nb] = __builtin_fmaf(z[nb], __builtin_amdgcn_exp2f(m[nb] - mx), sum);
-        m[nb] = mx;
+        for (int k = 0; k < NG; ++k) col_stats(acc[k], g0 + k);
       }
     }
     if (MOMENTS) {
@@ -175,6 +214,12 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4 && !MOMENTS) ? AMS_SCORE
       if ((c & 1) == 0 && t < T_all)
         g_sm[t - c0] = (r_tok + d_mean) * a.inv_sqrt_d + 0.5f * (d_sq - d_mean * d_mean) * (a.inv_sqrt_d * a.inv_sqrt_d);
     }
+  };
+  auto block = [&](const uint4 (&av)[Tr<BF16, HD>::kAVecs], int t0) __attribute__((always_inline)) {
+    if (t0 + 32 > T)
+      block_of(av, t0, std::true_type{});
+    else
+      block_of(av, t0, std::false_type{});
   };
   // this wave's blocks: every fourth block of 32 tokens up to the end of the chunk (or of the cache)
   const int t_lim = min(T, c0 + a.chunk);
@@ -337,32 +382,54 @@ __global__ __launch_bounds__(kThreads, (BF16 && NB <= 4) ? AMS_SCORE_MIN_WAVES :
     constexpr bool masked = TAIL;
     int qoff = 0;  // see the first sweep: the query fragments are re-read per block on purpose
     asm volatile("" : "+s"(qoff));
+    auto col_usage = [&](const floatx16& acc, int nb) __attribute__((always_inline)) {
+      if (masked) {
+        const int lim = t_vis0 + (nb * 32 + c) % a.d.W;  // newest key this column's query sees
 #pragma unroll
-    for (int g0 = 0; g0 < NB; g0 += NG) {
-      floatx16 acc[NG];
-      tile_mma<BF16, NG, HD>(av, qlds + qoff + g0 * 32 * QS, lane, acc);
-#pragma unroll
-      for (int k = 0; k < NG; ++k) {
-        const int nb = g0 + k;
-        if (masked) {
-          const int lim = t_vis0 + (nb * 32 + c) % a.d.W;  // newest key this column's query sees
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[k][i], c2, -f[nb].x));
-            const bool sees = t0 + acc_row(i, hf) <= lim;
-            const float share = sees ? f[nb].y * e : 0.f;
-            pu[i] += share;
-            pm[i] = fmaxf(pm[i], share);
-            if (MODE == MODE_LAST) pg[i] += sees ? f[nb].z * e : 0.f;
-          }
-        } else {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[k][i], c2, -f[nb].x));
-            pu[i] = __builtin_fmaf(f[nb].y, e, pu[i]);
-            if (MODE == MODE_LAST) pg[i] = __builtin_fmaf(f[nb].z, e, pg[i]);
-          }
+        for (int i = 0; i < 16; ++i) {
+          const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i], c2, -f[nb].x));
+          const bool sees = t0 + acc_row(i, hf) <= lim;
+          const float share = sees ? f[nb].y * e : 0.f;
+          pu[i] += share;
+          pm[i] = fmaxf(pm[i], share);
+          if (MODE == MODE_LAST) pg[i] += sees ? f[nb].z * e : 0.f;
         }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i], c2, -f[nb].x));
+          pu[i] = __builtin_fmaf(f[nb].y, e, pu[i]);
+          if (MODE == MODE_LAST) pg[i] = __builtin_fmaf(f[nb].z, e, pg[i]);
+        }
+      }
+    };
+    if constexpr (kPipe<BF16, NB, TAIL>) {
+      constexpr int NV = Tr<BF16, HD>::kAVecs;
+      const char* qb = qlds + qoff + (lane & 31) * QS + (lane >> 5) * (Tr<BF16, HD>::kRowBytes / 2);
+      uint4 bq[2][NV];
+      floatx16 acc2[2];
+      col_frags<BF16, HD>(qb, bq[0]);
+      col_frags<BF16, HD>(qb + 32 * QS, bq[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      col_mma<BF16, HD>(av, bq[0], acc2[0]);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (nb + 2 < NB) col_frags<BF16, HD>(qb + (nb + 2) * 32 * QS, bq[nb & 1]);
+        if (nb + 1 < NB) col_mma<BF16, HD>(av, bq[(nb + 1) & 1], acc2[(nb + 1) & 1]);
+        col_usage(acc2[nb & 1], nb);
+        if (nb + 2 < NB)
+          col_hints<NV, MODE == MODE_LAST ? 6 : 4, 2, true>();
+        else if (nb + 1 < NB)
+          col_hints<NV, MODE == MODE_LAST ? 6 : 4, 2, false>();
+      }
+    } else {
+#pragma unroll
+      for (int g0 = 0; g0 < NB; g0 += NG) {
+        floatx16 acc[NG];
+        tile_mma<BF16, NG, HD>(av, qlds + qoff + g0 * 32 * QS, lane, acc);
+#pragma unroll
+        for (int k = 0; k < NG; ++k) col_usage(acc[k], g0 + k);
       }
     }
     const int t = t0 + acc_row(c >> 1, hf);

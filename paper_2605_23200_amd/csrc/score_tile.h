@@ -148,6 +148,42 @@ __device__ __forceinline__ void tile_mma(const uint4 (&av)[Tr<BF16, HD>::kAVecs]
 
 __device__ __forceinline__ int acc_row(int i, int hf) { return 8 * (i >> 2) + 4 * hf + (i & 3); }
 
+// Software pipeline over the column blocks of a tile (bf16 caches): the query fragments of a column
+// block are read from LDS a whole column block before the matrix instructions that use them, and the
+// matrix instructions of column block nb + 1 are issued between the vector instructions that consume
+// column block nb.  A wave then neither waits for LDS in front of every MFMA nor leaves one of the
+// two pipes idle while it uses the other.
+//   col_frags   this lane's 16-byte query fragments of one column block -> registers
+//   col_mma     acc = K_block . Q_col^T from fragments in registers
+//   col_hints   scheduling hints for one step of the pipeline (STEPS matrix instructions, each
+//               followed by VALU_PER vector and TRANS_PER transcendental instructions)
+template <bool BF16, int HD = 128>
+__device__ __forceinline__ void col_frags(const char* qb, uint4 (&bq)[Tr<BF16, HD>::kAVecs]) {
+#pragma unroll
+  for (int ks = 0; ks < Tr<BF16, HD>::kAVecs; ++ks) bq[ks] = *(const uint4*)(qb + ks * 16);
+}
+template <bool BF16, int HD = 128>
+__device__ __forceinline__ void col_mma(const uint4 (&av)[Tr<BF16, HD>::kAVecs],
+                                        const uint4 (&bq)[Tr<BF16, HD>::kAVecs], floatx16& acc) {
+  static_assert(BF16, "the pipelined walk is written for bf16 caches");
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < Tr<BF16, HD>::kAVecs; ++ks)
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[ks]), __builtin_bit_cast(bf16x8, bq[ks]),
+                                                  acc, 0, 0, 0);
+}
+template <int STEPS, int VALU_PER, int TRANS_PER, bool READS>
+__device__ __forceinline__ void col_hints() {
+  if (READS) __builtin_amdgcn_sched_group_barrier(0x100, STEPS, 0);  // the LDS reads of the column block after next, first
+#pragma unroll
+  for (int i = 0; i < STEPS; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         // MFMA
+    __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER, 0);  // vector ALU
+    if (TRANS_PER > 0) __builtin_amdgcn_sched_group_barrier(0x400, TRANS_PER, 0);  // exp2
+  }
+}
+
 // Sum (or maximum) of 16 per-lane values over the 32 lanes of a half wave, halving the number of live values
 // at every exchange.  Lane c ends up with the total of value index c >> 1.
 // Exchanges: rows of 16 lanes swap through v_permlane16_swap (bit 4 of the lane), then DPP
