@@ -244,6 +244,38 @@ def test_segment_as_printed_parity(oracle, T, delta, l_min, l_max):
         assert_close_rel(seg_mass[i], so, what=f"seg_mass unit {i}")
 
 
+@pytest.mark.parametrize("name", ["worked_example_adaptive_segments.txt", "worked_example_adaptive_segments_2.txt"])
+def test_segment_as_printed_hand_worked(name):
+    """The two hand-worked examples of the split / merge pass (Alg. 1 step 3), held against the files
+    themselves and not against the oracle: both stage entry points."""
+    import os
+    w = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", name)) as f:
+        for line in f:
+            if not line.startswith("#") and line.strip():
+                k, *v = line.split()
+                w[k] = np.array([float(x) for x in v])
+    m = (w["m64"] / 64).astype(np.float32)[None, :]
+    T, cap = m.shape[1], 12
+    want = w["bounds"].astype(np.int32)
+    n = len(want) - 1
+    p = _vec_params(1, T, S=cap)
+    p.seg_delta, p.l_min, p.l_max = float(w["delta"][0]), int(w["l_min"][0]), int(w["l_max"][0])
+    lens = to_dev(np.array([T], np.int32))
+    for static in (False, True):
+        bounds = torch.full((1, cap + 1), -3, dtype=torch.int32, device=DEV)
+        seg_mass = torch.full((1, cap), -3.0, device=DEV)
+        if static:
+            B.ams_mass_segment_static(p, lens, to_dev(m), bounds, seg_mass)
+        else:
+            B.ams_mass_segment(p, lens, to_dev(m), bounds, seg_mass, workspace(p))
+        torch.cuda.synchronize()
+        b, sm = to_host(bounds)[0], to_host(seg_mass)[0]
+        np.testing.assert_array_equal(b[: n + 1], want)
+        assert (b[n + 1:] == T).all() and (sm[n:] == 0).all()
+        np.testing.assert_array_equal(sm[:n], (w["seg_mass64"] / 64).astype(np.float32))
+
+
 def test_segment_as_printed_rejects_small_capacity():
     p = _vec_params(1, 4096, S=20)
     p.seg_delta, p.l_max = 0.1, 128                                      # needs 10 + 32 entries

@@ -8,6 +8,7 @@ import pytest
 from paper_2605_23200_amd import inputs
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden", "worked_example_adaptive_segments.txt")
+GOLD2 = os.path.join(os.path.dirname(__file__), "golden", "worked_example_adaptive_segments_2.txt")
 
 
 def _read(path):
@@ -21,10 +22,11 @@ def _read(path):
     return out
 
 
-def test_worked_example(oracle):
-    w = _read(GOLD)
+@pytest.mark.parametrize("gold", [GOLD, GOLD2], ids=["split_and_merge", "empty_run_of_short_and_overlong"])
+def test_worked_example(oracle, gold):
+    w = _read(gold)
     m = (w["m64"] / 64).astype(np.float32)
-    cap = 8
+    cap = 12
     bounds, seg_mass, n = oracle.segment_adaptive(m, float(w["delta"][0]), int(w["l_min"][0]), int(w["l_max"][0]), cap)
     want = w["bounds"].astype(np.int32)
     assert n == len(want) - 1
