@@ -15,7 +15,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("AMS_LIB", os.path.join(_HERE, "libams.so"))  # AMS_LIB: development override
+LIB_PATH = os.path.join(_HERE, "libams.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_HIP = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
