@@ -168,6 +168,19 @@ int ams_profile_begin(void);
 int ams_profile_end(void* stream, int max_entries, const char** labels, float* ms);
 
 /*
+ * Testing aid for the one path of the library whose workgroups wait for one
+ * another, AMS_SCORE_PATH_ONE_READ (no citation: not part of the method).  Its
+ * waits are bounded polls; `polls` > 0 sets that bound for the launches that
+ * follow (process-wide, not thread-safe), 0 restores the built-in one (about
+ * 0.1 s).  With a bound of 1 every wait that is not satisfied at once expires,
+ * every kernel still runs to its end, and ams_compress_step reports the expiry
+ * as documented at ams_score_path (n_kept = -1 for every unit): the error path
+ * can be exercised without hanging anything.  [host]; AMS_ERR_INVALID_ARG for a
+ * negative bound.
+ */
+int ams_debug_set_wait_limit(int polls);
+
+/*
  * ams_score - usage u and base score g (Alg. 1 step 1; Sec. 3.2; Sec. 3.3).
  *   s[n][t] = q_n . k_t / sqrt(D) over the N = G*W recent queries of the unit,
  *   p = softmax over t, u[t] = mean_n p[n][t]; g per p->scorer (g may equal u

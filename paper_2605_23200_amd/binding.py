@@ -26,7 +26,7 @@ LAYOUT_DENSE, LAYOUT_PAGED = 0, 1
 SCORE_PATH_AUTO, SCORE_PATH_TWO_SWEEPS, SCORE_PATH_ONE_READ, SCORE_PATH_ONE_LAUNCH = 0, 1, 2, 3
 
 EXPORTS = ("ams_status_string", "ams_workspace_bytes", "ams_workspace_layout", "ams_profile_begin",
-           "ams_profile_end", "ams_score",
+           "ams_profile_end", "ams_debug_set_wait_limit", "ams_score",
            "ams_ema_update", "ams_mass_segment", "ams_mass_segment_static", "ams_select", "ams_compact",
            "ams_compress_step")
 
@@ -158,6 +158,10 @@ def ams_workspace_layout(p: Params) -> WorkspaceView:
 
 def ams_profile_begin():
     _check(lib().ams_profile_begin(), "ams_profile_begin")
+
+
+def ams_debug_set_wait_limit(polls: int):
+    _check(lib().ams_debug_set_wait_limit(int(polls)), "ams_debug_set_wait_limit")
 
 
 def ams_profile_end(stream=None, max_entries: int = 4096):

@@ -204,6 +204,12 @@ size_t ams_workspace_bytes(const ams_params* p) {
   return ws_layout(p).total;
 }
 
+int ams_debug_set_wait_limit(int polls) {
+  if (polls < 0) return AMS_ERR_INVALID_ARG;
+  set_park_wait_limit(polls);
+  return AMS_OK;
+}
+
 int ams_profile_begin(void) {
   g_prof.n = 0;
   g_prof.on = true;

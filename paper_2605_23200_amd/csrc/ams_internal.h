@@ -107,6 +107,7 @@ hipError_t launch_score(const ams_params* p, const Dims& d, const KvDev& k, cons
 constexpr int kParkMaxWorkgroups = 1024, kParkMaxClusters = 1024, kParkMaxMembers = 1024;
 size_t park_score_ws_bytes(int n_pad);
 int32_t* park_status_word(char* ws, const WsLayout& wl);
+void set_park_wait_limit(int polls);  // polls a bounded wait of that scorer may take (0: its default)
 hipError_t launch_score_oneread(const ams_params* p, const Dims& d, const KvDev& k, const int32_t* seq_lens,
                                 const void* q, float* u, float* g, const float* credit, bool want_vc,
                                 int* vc_stride, int* vc_tokens, char* ws, const WsLayout& wl,

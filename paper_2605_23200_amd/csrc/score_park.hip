@@ -47,6 +47,8 @@ constexpr int kParkSpin = 1 << 17;               // polls of a bounded wait (abo
 #define PARK_MARK(k) do { } while (0)
 #endif
 
+int g_wait_limit = 0;  // ams_debug_set_wait_limit: 0 = kParkSpin
+
 struct ParkArgs {
   ScoreArgs s;
   float2* part;      // [clusters][2][C][n_pad]  per member (max, sum) in the log2 domain
@@ -55,6 +57,7 @@ struct ParkArgs {
   int C;             // workgroups per cluster
   int n_clusters;
   int vc_stride;     // entries per unit of s.vc_part (one per member)
+  int spin;          // polls a bounded wait may take before it gives up
 #ifdef AMS_PARK_TRACE
   long long* trace;  // [workgroups][64 units][8 marks] timestamps of a measurement build
 #endif
@@ -371,7 +374,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_park_kernel(ParkArgs a) {
       if (threadIdx.x == 0) __hip_atomic_store(flag, seq + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (threadIdx.x == 0) {
-      int budget = kParkSpin;
+      int budget = a.spin;
       while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < seq + 1 && --budget > 0)
         __builtin_amdgcn_s_sleep(2);
       s_ok = budget > 0;
@@ -556,6 +559,8 @@ size_t park_score_ws_bytes(int n_pad) {
   return o;
 }
 
+void set_park_wait_limit(int polls) { g_wait_limit = polls > 0 ? polls : 0; }
+
 int32_t* park_status_word(char* ws, const WsLayout& wl) {
   return (int32_t*)(ws + wl.park + align256((size_t)kParkMaxWorkgroups * 2 * wl.n_pad * sizeof(float2))) +
          2 * kParkMaxClusters;
@@ -603,6 +608,7 @@ hipError_t launch_score_oneread(const ams_params* p, const Dims& d, const KvDev&
   a.sync = (int32_t*)w;
   a.status = a.sync + 2 * kParkMaxClusters;
   a.C = a.n_clusters = a.vc_stride = 0;
+  a.spin = g_wait_limit > 0 ? g_wait_limit : kParkSpin;
   if (vc_stride) *vc_stride = div_up(d.t_max, kParkTok);
   if (vc_tokens) *vc_tokens = kParkTok;
   const int nb = wl.n_pad / 32;

@@ -626,6 +626,29 @@ def test_both_score_paths(oracle, scorer):
     np.testing.assert_allclose(us[B.SCORE_PATH_ONE_READ], us[B.SCORE_PATH_TWO_SWEEPS], rtol=2e-5, atol=1e-12)
 
 
+def test_one_read_path_reports_an_expired_wait():
+    """The one path whose workgroups wait for one another: with the bound of its waits set to a single poll
+    (from the host; every kernel still runs to its end) a member that is not the last to arrive gives up, the
+    step says so with n_kept = -1 for every unit, and the next step with the built-in bound is whole again."""
+    w = inputs.CONFIGS[1].scaled(L=2, H=3, T=5000, budget=512, S=8, n_spans=6, span_len=(32, 300))
+    host = inputs.dense_cache(w, n_threads=4)
+    job = Job(w, host, score_path=B.SCORE_PATH_ONE_READ)
+    B.ams_debug_set_wait_limit(1)
+    try:
+        job.step()
+        torch.cuda.synchronize()
+        assert (job.n_kept.cpu().numpy() == -1).all()
+    finally:
+        B.ams_debug_set_wait_limit(0)
+    with pytest.raises(B.AmsError):
+        B.ams_debug_set_wait_limit(-1)
+    job.credit.zero_()
+    job.step()
+    torch.cuda.synchronize()
+    assert (job.n_kept.cpu().numpy() == w.budget).all()
+    check_properties_all_units(job)
+
+
 @pytest.mark.parametrize("scorer", [B.SCORER_MEAN_WINDOW, B.SCORER_LAST_QUERY, B.SCORER_KEYDIFF])
 @pytest.mark.parametrize("dtype,D,G,W,T,paged", [("bf16", 128, 4, 32, 2176, False), ("bf16", 128, 4, 32, 4096, False),
                                                   ("f32", 128, 1, 8, 1280, False), ("bf16", 64, 2, 16, 3000, False),
